@@ -1,0 +1,375 @@
+"""Pins for the CPU oracle: closed forms, brute force, finite differences, library special
+cases and invariants.  None of these call the HIP path."""
+import math
+import os
+from types import SimpleNamespace
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer as O
+from paper_2504_03662_amd import inputs as I
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def cfg_of(**kw):
+    d = dict(hidden=16, heads=4, ffn=32, tp_attn=1, tp_ffn=1, tp_rank=0, seq=6, micro_batch=2, ln_eps=1e-5)
+    d.update(kw)
+    return SimpleNamespace(**d)
+
+
+def rand_params(cfg, rng, scale=0.3):
+    sh = O.Shape(cfg)
+    dims = dict(ln1_g=(sh.H,), ln1_b=(sh.H,), w_qkv=(sh.H, 3 * sh.Hl), b_qkv=(3 * sh.Hl,), w_o=(sh.Hl, sh.H),
+                b_o=(sh.H,), ln2_g=(sh.H,), ln2_b=(sh.H,), w_fc1=(sh.H, sh.Fl), b_fc1=(sh.Fl,),
+                w_fc2=(sh.Fl, sh.H), b_fc2=(sh.H,))
+    p = {k: scale * rng.standard_normal(v) for k, v in dims.items()}
+    p["ln1_g"] += 1.0
+    p["ln2_g"] += 1.0
+    return p
+
+
+# ------------------------------------------------------------------ closed forms
+
+def test_gelu_matches_normal_cdf_table():
+    rows = [l.split() for l in open(os.path.join(GOLD, "normal_cdf.txt")) if l.strip() and not l.startswith("#")]
+    for zs, ps in rows:
+        z, phi = float(zs), float(ps)
+        assert abs(O.gelu(np.array([z]))[0] - z * phi) < 2e-10 * max(1.0, z)
+        assert abs(O.gelu(np.array([-z]))[0] - (-z) * (1.0 - phi)) < 2e-10 * max(1.0, z)
+    z = np.linspace(-6, 6, 101)
+    assert np.allclose(O.gelu(z) - O.gelu(-z), z, atol=1e-14)          # z Phi(z) + z Phi(-z) = z
+    assert O.gelu(np.zeros(3)).tolist() == [0.0, 0.0, 0.0]
+    ref = np.array([0.5 * t * (1 + math.erf(t / math.sqrt(2))) for t in z])
+    assert np.allclose(O.gelu(z), ref, atol=1e-15)
+
+
+def test_gelu_grad_finite_difference():
+    z = np.linspace(-5, 5, 41)
+    h = 1e-6
+    fd = (O.gelu(z + h) - O.gelu(z - h)) / (2 * h)
+    assert np.allclose(O.gelu_grad(z), fd, atol=1e-9)
+    assert abs(O.gelu_grad(np.array([0.0]))[0] - 0.5) < 1e-15
+
+
+def test_attention_hand_computed_softmax():
+    # dh = 4 so the scale is 1/2: q1 . k1 / 2 = ln 2, q1 . k0 / 2 = 0  ->  P[1] = [1/3, 2/3].
+    q = np.array([[5.0, 1, 2, 3], [2.0, 0, 0, 0]])
+    k = np.array([[0.0, 0, 0, 0], [math.log(2.0), 0, 0, 0]])
+    v = np.array([[1.0, 0, 3, 0], [0.0, 6, 0, 9]])
+    o, p = O.causal_attention_fwd(q, k, v)
+    assert np.allclose(p, [[1.0, 0.0], [1 / 3, 2 / 3]], atol=1e-15)
+    assert np.allclose(o, [[1.0, 0, 3, 0], [1 / 3, 4, 1, 6]], atol=1e-14)
+
+
+def test_layer_norm_closed_form():
+    u = np.array([[1.0, 2.0, 3.0, 4.0]])
+    y, xhat, rstd = O.layer_norm_fwd(u, np.array([1.0, 1, 1, 2]), np.array([0.0, 0, 0, 1]), 0.0)
+    s = math.sqrt(1.25)                                  # biased variance of 1..4
+    assert np.allclose(y, [[-1.5 / s, -0.5 / s, 0.5 / s, 2 * 1.5 / s + 1]], atol=1e-15)
+    y, _, _ = O.layer_norm_fwd(u, np.ones(4), np.zeros(4), 0.75)   # eps inside the root: sqrt(2)
+    assert np.allclose(y, (u - 2.5) / math.sqrt(2.0), atol=1e-15)
+
+
+# ------------------------------------------------------------------ brute force on tiny layers
+
+def brute_layer(cfg, p, x, row_bias_attn, row_bias_mlp):
+    """Loop-only evaluation of the block, scalars throughout."""
+    sh = O.Shape(cfg)
+    T, H = sh.T, sh.H
+
+    def ln(u, g, b):
+        out = [[0.0] * H for _ in range(T)]
+        for t in range(T):
+            m = sum(u[t]) / H
+            var = sum((e - m) ** 2 for e in u[t]) / H
+            for i in range(H):
+                out[t][i] = g[i] * (u[t][i] - m) / math.sqrt(var + sh.eps) + b[i]
+        return out
+
+    def mm(a, w, n_in, n_out):
+        return [[sum(a[t][i] * w[i][j] for i in range(n_in)) for j in range(n_out)] for t in range(T)]
+
+    xs = x.tolist()
+    y1 = ln(xs, p["ln1_g"], p["ln1_b"])
+    qkv = mm(y1, p["w_qkv"], H, 3 * sh.Hl)
+    for t in range(T):
+        for j in range(3 * sh.Hl):
+            qkv[t][j] += p["b_qkv"][j]
+    ctx = [[0.0] * sh.Hl for _ in range(T)]
+    for b in range(sh.B):
+        for h in range(sh.nl):
+            for i in range(sh.S):
+                ti = b * sh.S + i
+                sc = []
+                for j in range(i + 1):
+                    tj = b * sh.S + j
+                    sc.append(sum(qkv[ti][h * sh.dh + d] * qkv[tj][sh.Hl + h * sh.dh + d] for d in range(sh.dh))
+                              / math.sqrt(sh.dh))
+                mx = max(sc)
+                e = [math.exp(s - mx) for s in sc]
+                z = sum(e)
+                for d in range(sh.dh):
+                    ctx[ti][h * sh.dh + d] = sum(e[j] / z * qkv[b * sh.S + j][2 * sh.Hl + h * sh.dh + d]
+                                                 for j in range(i + 1))
+    pa = mm(ctx, p["w_o"], sh.Hl, H)
+    h1 = [[xs[t][i] + pa[t][i] + (p["b_o"][i] if row_bias_attn else 0.0) for i in range(H)] for t in range(T)]
+    y2 = ln(h1, p["ln2_g"], p["ln2_b"])
+    z = mm(y2, p["w_fc1"], H, sh.Fl)
+    act = [[0.0] * sh.Fl for _ in range(T)]
+    for t in range(T):
+        for j in range(sh.Fl):
+            v = z[t][j] + p["b_fc1"][j]
+            act[t][j] = 0.5 * v * (1.0 + math.erf(v / math.sqrt(2.0)))
+    pm = mm(act, p["w_fc2"], sh.Fl, H)
+    return np.array([[h1[t][i] + pm[t][i] + (p["b_fc2"][i] if row_bias_mlp else 0.0) for i in range(H)]
+                     for t in range(T)])
+
+
+@pytest.mark.parametrize("a,f,rb", [(1, 1, True), (2, 1, False), (4, 2, True)])
+def test_forward_matches_brute_force(a, f, rb):
+    rng = np.random.default_rng(11 + a)
+    cfg = cfg_of(tp_attn=a, tp_ffn=f, seq=5, micro_batch=2)
+    p = rand_params(cfg, rng)
+    x = rng.standard_normal((cfg.seq * cfg.micro_batch, cfg.hidden))
+    y = O.layer_fwd(cfg, p, x, "both", rb, not rb)["y"]
+    assert np.allclose(y, brute_layer(cfg, p, x, rb, not rb), rtol=0, atol=1e-12)
+
+
+# ------------------------------------------------------------------ finite differences
+
+def _loss(cfg, p, x, w, phase, **kw):
+    out = O.layer_fwd(cfg, p, x, phase, **kw)
+    key = {"both": "y", "attn": "p_attn", "mlp": "p_mlp"}[phase]
+    return float((out[key] * w).sum())
+
+
+@pytest.mark.parametrize("phase", ["both", "attn", "mlp"])
+@pytest.mark.parametrize("a,f", [(1, 1), (2, 2)])
+def test_backward_matches_finite_differences(phase, a, f):
+    rng = np.random.default_rng(5)
+    cfg = cfg_of(tp_attn=a, tp_ffn=f, seq=4, micro_batch=2, hidden=8, heads=2, ffn=12)
+    p = rand_params(cfg, rng)
+    x = rng.standard_normal((8, 8))
+    w = rng.standard_normal((8, 8))
+    kw = dict(row_bias_attn=True, row_bias_mlp=True)
+    out = O.layer_fwd(cfg, p, x, phase, **kw)
+    dx, g = O.layer_bwd(cfg, p, w, out["cache"], phase, **kw)
+    h = 1e-6
+
+    def fd(arr, idx, setter):
+        old = arr[idx]
+        arr[idx] = old + h
+        lp = setter()
+        arr[idx] = old - h
+        lm = setter()
+        arr[idx] = old
+        return (lp - lm) / (2 * h)
+
+    for idx in [(0, 0), (3, 5), (7, 7), (4, 2)]:
+        assert abs(fd(x, idx, lambda: _loss(cfg, p, x, w, phase, **kw)) - dx[idx]) < 2e-7
+    for name, grad in g.items():
+        arr = p[name]
+        flat = [np.unravel_index(i, arr.shape) for i in rng.choice(arr.size, size=min(arr.size, 6), replace=False)]
+        for idx in flat:
+            num = fd(arr, idx, lambda: _loss(cfg, p, x, w, phase, **kw))
+            assert abs(num - grad[idx]) < 2e-7, (name, idx, num, grad[idx])
+    touched = {"both": O.PARAM_NAMES, "attn": O.ATTN_PARAMS, "mlp": O.MLP_PARAMS}[phase]
+    assert set(g) == set(touched)
+
+
+def test_adjoint_identity_medium():
+    """<dy, J v> = <J^T dy, v> with J v from a directional central difference."""
+    rng = np.random.default_rng(9)
+    cfg = cfg_of(hidden=32, heads=4, ffn=64, seq=16, micro_batch=2)
+    p = rand_params(cfg, rng, 0.2)
+    x = rng.standard_normal((32, 32))
+    v = rng.standard_normal((32, 32))
+    dy = rng.standard_normal((32, 32))
+    out = O.layer_fwd(cfg, p, x)
+    dx, _ = O.layer_bwd(cfg, p, dy, out["cache"])
+    h = 1e-6
+    jv = (O.layer_fwd(cfg, p, x + h * v)["y"] - O.layer_fwd(cfg, p, x - h * v)["y"]) / (2 * h)
+    assert abs((dy * jv).sum() - (dx * v).sum()) < 1e-6 * abs((dx * v).sum()) + 1e-7
+
+
+# ------------------------------------------------------------------ sharding identities
+
+@pytest.mark.parametrize("a,f", [(2, 2), (4, 2), (4, 1), (1, 4)])
+def test_partial_sums_and_column_concat_reproduce_unsharded(a, f):
+    shape = I.LayerShape(32, 4, 64, 1, 1, 0, 8, 2, "f32")
+    full = {k: v.astype(np.float64) for k, v in I.full_params(shape, case=90, random_affine=True).items()}
+    full = {k: (v * 10 if k.startswith("w_") else v) for k, v in full.items()}
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((16, 32))
+    dy = rng.standard_normal((16, 32))
+    ref = O.layer_fwd(shape, full, x)
+    dx_ref, g_ref = O.layer_bwd(shape, full, dy, ref["cache"])
+
+    sa = shape.with_(tp_attn=a, tp_ffn=f)
+    # attention half: x + sum of partials (bias on rank 0 only) = h1
+    outs_a = []
+    for r in range(a):
+        pr = I.shard_params(sa, full, rank_attn=r, rank_ffn=0)
+        outs_a.append((pr, O.layer_fwd(sa, pr, x, "attn", row_bias_attn=(r == 0))))
+    h1 = x + sum(o["p_attn"] for _, o in outs_a)
+    assert np.allclose(h1, ref["h1"], atol=1e-12)
+    qkv_cat = np.concatenate([np.concatenate([o["cache"]["attn"]["qkv"][:, i * sa.hidden_local:(i + 1) * sa.hidden_local]
+                                              for _, o in outs_a], axis=1) for i in range(3)], axis=1)
+    assert np.allclose(qkv_cat, ref["cache"]["attn"]["qkv"], atol=1e-12)
+    outs_m = []
+    for r in range(f):
+        pr = I.shard_params(sa, full, rank_attn=0, rank_ffn=r)
+        outs_m.append((pr, O.layer_fwd(sa, pr, h1, "mlp", row_bias_mlp=(r == 0))))
+    y = h1 + sum(o["p_mlp"] for _, o in outs_m)
+    assert np.allclose(y, ref["y"], atol=1e-12)
+    z_cat = np.concatenate([o["cache"]["mlp"]["z"] for _, o in outs_m], axis=1)
+    assert np.allclose(z_cat, ref["cache"]["mlp"]["z"], atol=1e-12)
+
+    # backward: partial input gradients add up; column-shard gradients are column blocks
+    dh1 = dy.copy()
+    gm = []
+    for r, (pr, o) in enumerate(outs_m):
+        d, g = O.layer_bwd(sa, pr, dy, o["cache"], "mlp", row_bias_mlp=(r == 0))
+        dh1 += d
+        gm.append(g)
+    dx = dh1.copy()
+    ga = []
+    for r, (pr, o) in enumerate(outs_a):
+        d, g = O.layer_bwd(sa, pr, dh1, o["cache"], "attn", row_bias_attn=(r == 0))
+        dx += d
+        ga.append(g)
+    assert np.allclose(dx, dx_ref, atol=1e-11)
+    Hl, H = sa.hidden_local, sa.hidden
+    for n in ("ln1_g", "ln1_b", "b_o"):
+        assert np.allclose(sum(g[n] for g in ga), g_ref[n], atol=1e-11)
+    for n in ("ln2_g", "ln2_b", "b_fc2"):
+        assert np.allclose(sum(g[n] for g in gm), g_ref[n], atol=1e-11)
+    assert np.allclose(np.concatenate([g["w_o"] for g in ga], axis=0), g_ref["w_o"], atol=1e-11)
+    assert np.allclose(np.concatenate([g["w_fc2"] for g in gm], axis=0), g_ref["w_fc2"], atol=1e-11)
+    assert np.allclose(np.concatenate([g["w_fc1"] for g in gm], axis=1), g_ref["w_fc1"], atol=1e-11)
+    assert np.allclose(np.concatenate([g["b_fc1"] for g in gm]), g_ref["b_fc1"], atol=1e-11)
+    for i in range(3):
+        cat = np.concatenate([g["w_qkv"][:, i * Hl:(i + 1) * Hl] for g in ga], axis=1)
+        assert np.allclose(cat, g_ref["w_qkv"][:, i * H:(i + 1) * H], atol=1e-11)
+        catb = np.concatenate([g["b_qkv"][i * Hl:(i + 1) * Hl] for g in ga])
+        assert np.allclose(catb, g_ref["b_qkv"][i * H:(i + 1) * H], atol=1e-11)
+
+
+# ------------------------------------------------------------------ library special cases (torch fp64 CPU)
+
+def test_pieces_match_torch_library_routines():
+    rng = np.random.default_rng(21)
+    u = rng.standard_normal((7, 24)) * 3 + 1
+    g = rng.standard_normal(24)
+    b = rng.standard_normal(24)
+    y, _, _ = O.layer_norm_fwd(u, g, b, 1e-5)
+    yt = torch.nn.functional.layer_norm(torch.from_numpy(u), (24,), torch.from_numpy(g), torch.from_numpy(b), 1e-5)
+    assert np.allclose(y, yt.numpy(), atol=1e-13)
+    z = rng.standard_normal(200) * 3
+    assert np.allclose(O.gelu(z), torch.nn.functional.gelu(torch.from_numpy(z), approximate="none").numpy(), atol=1e-14)
+    q, k, v = (rng.standard_normal((9, 8)) for _ in range(3))
+    o, _ = O.causal_attention_fwd(q, k, v)
+    ot = torch.nn.functional.scaled_dot_product_attention(*(torch.from_numpy(t)[None, None] for t in (q, k, v)),
+                                                          is_causal=True)[0, 0]
+    assert np.allclose(o, ot.numpy(), atol=1e-13)
+
+
+def _torch_block(cfg, p, x, rb_a=True, rb_m=True):
+    """The same block written with torch library calls, differentiated by autograd."""
+    sh = O.Shape(cfg)
+    F = torch.nn.functional
+    y1 = F.layer_norm(x, (sh.H,), p["ln1_g"], p["ln1_b"], sh.eps)
+    qkv = F.linear(y1, p["w_qkv"].T, p["b_qkv"])
+    q, k, v = (qkv[:, i * sh.Hl:(i + 1) * sh.Hl].reshape(sh.B, sh.S, sh.nl, sh.dh).transpose(1, 2) for i in range(3))
+    ctx = F.scaled_dot_product_attention(q, k, v, is_causal=True).transpose(1, 2).reshape(sh.T, sh.Hl)
+    h1 = x + F.linear(ctx, p["w_o"].T, p["b_o"] if rb_a else None)
+    y2 = F.layer_norm(h1, (sh.H,), p["ln2_g"], p["ln2_b"], sh.eps)
+    act = F.gelu(F.linear(y2, p["w_fc1"].T, p["b_fc1"]), approximate="none")
+    return h1 + F.linear(act, p["w_fc2"].T, p["b_fc2"] if rb_m else None)
+
+
+@pytest.mark.parametrize("a,f,rb", [(1, 1, True), (2, 4, False)])
+def test_block_matches_torch_autograd(a, f, rb):
+    rng = np.random.default_rng(31)
+    cfg = cfg_of(hidden=32, heads=4, ffn=64, tp_attn=a, tp_ffn=f, seq=12, micro_batch=3)
+    p = rand_params(cfg, rng, 0.2)
+    x = rng.standard_normal((36, 32))
+    dy = rng.standard_normal((36, 32))
+    out = O.layer_fwd(cfg, p, x, "both", rb, rb)
+    dx, g = O.layer_bwd(cfg, p, dy, out["cache"], "both", rb, rb)
+    pt = {k: torch.tensor(v, dtype=torch.float64, requires_grad=True) for k, v in p.items()}
+    xt = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+    yt = _torch_block(cfg, pt, xt, rb, rb)
+    assert np.allclose(out["y"], yt.detach().numpy(), atol=1e-12)
+    yt.backward(torch.from_numpy(dy))
+    assert np.allclose(dx, xt.grad.numpy(), atol=1e-11)
+    for n in O.PARAM_NAMES:
+        ref = pt[n].grad.numpy() if pt[n].grad is not None else np.zeros_like(p[n])
+        assert np.allclose(g[n], ref, atol=1e-11), n
+
+
+# ------------------------------------------------------------------ invariants
+
+def test_causality_sample_independence_and_identities():
+    rng = np.random.default_rng(41)
+    cfg = cfg_of(hidden=16, heads=2, ffn=32, seq=8, micro_batch=2)
+    p = rand_params(cfg, rng)
+    x = rng.standard_normal((16, 16))
+    y = O.layer_fwd(cfg, p, x)["y"]
+    x2 = x.copy()
+    x2[5:8] += rng.standard_normal((3, 16))          # perturb tokens 5..7 of sample 0
+    y2 = O.layer_fwd(cfg, p, x2)["y"]
+    assert np.array_equal(y[:5], y2[:5]) and not np.allclose(y[5:8], y2[5:8])
+    assert np.array_equal(y[8:], y2[8:])             # sample 1 never sees sample 0
+    # position 0 attends to itself only: ctx row 0 = V row 0
+    ca = O.layer_fwd(cfg, p, x)["cache"]["attn"]
+    assert np.allclose(ca["ctx"][0], ca["qkv"][0, 2 * 16:], atol=1e-15)
+    for pr in ca["probs"].values():
+        assert np.allclose(pr.sum(-1), 1.0, atol=1e-14) and np.all(np.triu(pr, 1) == 0.0)
+    # all weights zero: y = x and dx = dy
+    p0 = {k: np.zeros_like(v) for k, v in p.items()}
+    out0 = O.layer_fwd(cfg, p0, x)
+    assert np.array_equal(out0["y"], x)
+    dy = rng.standard_normal((16, 16))
+    dx0, _ = O.layer_bwd(cfg, p0, dy, out0["cache"])
+    assert np.array_equal(dx0, dy)
+    # backward is linear in dy
+    out = O.layer_fwd(cfg, p, x)
+    d1, g1 = O.layer_bwd(cfg, p, dy, out["cache"])
+    d2, g2 = O.layer_bwd(cfg, p, -2.5 * dy, out["cache"])
+    assert np.allclose(d2, -2.5 * d1, atol=1e-12) and np.allclose(g2["w_fc1"], -2.5 * g1["w_fc1"], atol=1e-12)
+    # LN with unit gain: zero mean, unit variance; LN backward orthogonal to 1 and xhat
+    yln, xhat, rstd = O.layer_norm_fwd(x * 3 + 1, np.ones(16), np.zeros(16), 0.0)
+    assert np.allclose(yln.mean(-1), 0, atol=1e-14) and np.allclose(yln.var(-1), 1, atol=1e-13)
+    du, _, _ = O.layer_norm_bwd(dy, xhat, rstd, np.ones(16))
+    assert np.allclose(du.sum(-1), 0, atol=1e-12) and np.allclose((du * xhat).sum(-1), 0, atol=1e-12)
+
+
+def test_micro_batch_split_equals_batch_and_stack_composes():
+    rng = np.random.default_rng(51)
+    cfg1 = cfg_of(hidden=16, heads=2, ffn=32, seq=6, micro_batch=1)
+    cfg4 = cfg_of(hidden=16, heads=2, ffn=32, seq=6, micro_batch=4)
+    plist = [rand_params(cfg1, rng), rand_params(cfg1, rng)]
+    xs = [rng.standard_normal((6, 16)) for _ in range(4)]
+    dys = [rng.standard_normal((6, 16)) for _ in range(4)]
+    ys, dxs, tot = O.pipeline_stage(cfg1, plist, xs, dys)
+    y, outs = O.stack_fwd(cfg4, plist, np.concatenate(xs))
+    dx, grads = O.stack_bwd(cfg4, plist, np.concatenate(dys), outs)
+    assert np.allclose(np.concatenate(ys), y, atol=1e-12) and np.allclose(np.concatenate(dxs), dx, atol=1e-12)
+    for gt, gb in zip(tot, grads):
+        for n in O.PARAM_NAMES:
+            assert np.allclose(gt[n], gb[n], atol=1e-11), n
+    # a stack is the composition of its blocks
+    o0 = O.layer_fwd(cfg4, plist[0], np.concatenate(xs))
+    o1 = O.layer_fwd(cfg4, plist[1], o0["y"])
+    assert np.array_equal(o1["y"], y)
+
+
+def test_model_flops_matches_survey_table():
+    shape, blocks, mbs = I.WORKLOADS["C3"]
+    assert abs(O.model_flops(shape) / 1e9 - 1288.5) < 0.5
+    shape, blocks, mbs = I.WORKLOADS["C2"]
+    assert abs(O.model_flops(shape, blocks, mbs) / 1e12 - 10.72) < 0.01
