@@ -1,0 +1,141 @@
+/* gx.h - C ABI of libgx: one GPU's share of a pre-LayerNorm transformer block's training step
+ * (forward and backward) on AMD MI355X (gfx950), at the sharded shapes a hybrid
+ * data/tensor/pipeline-parallel strategy assigns to one rank.
+ *
+ * Background (Galvatron paper, arXiv 2504.03662): section 2 "Layer-Specific Parallelism
+ * Optimization" and section 3 "NVIDIA Megatron-LM" describe tensor parallelism as splitting a
+ * layer's matrix products across GPUs, possibly with different degrees for the attention and the
+ * feed-forward halves of a layer; section 2 "Training Phase Adaptation" and section 3
+ * "ParallelismManager" describe micro-batches flowing through a pipeline stage; section 4's
+ * ParallelismConfig record (strategy type, pipeline size, tensor degree, micro-batch size) is the
+ * model for gx_layer_cfg.  The paper prints no layer equations; the block computed here is the
+ * textbook pre-LN GPT block:
+ *
+ *   attention half : y1 = LN(x; ln1_g, ln1_b);  [Q|K|V] = y1 * w_qkv + b_qkv   (column-parallel)
+ *                    causal softmax(Q K^T / sqrt(dh)) V per sample and local head -> ctx
+ *                    p_attn = ctx * w_o (+ b_o)                                 (row-parallel)
+ *   feed-forward   : y2 = LN(h1; ln2_g, ln2_b); z = y2 * w_fc1 + b_fc1; act = gelu_erf(z)
+ *                    p_mlp = act * w_fc2 (+ b_fc2)                              (row-parallel)
+ *   both phases    : h1 = x + p_attn;  y = h1 + p_mlp
+ *
+ * Row-parallel outputs are this rank's PARTIAL sums: the library runs no collective.  With both
+ * phases selected the rank's own partial stands in for the reduced sum (exact when the degree is
+ * 1); with a single phase selected the call returns the pure partial, so that a caller can put a
+ * reduction between the two halves.
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless stated otherwise, owned by the caller, 16-byte
+ *     aligned, and must stay valid until the work queued on `hip_stream` has completed.
+ *   - All matrices are row-major and dense.  T = micro_batch * seq tokens, token t = b * seq + s.
+ *     H = hidden, dh = H / heads, Hl = (heads / tp_attn) * dh, Fl = ffn / tp_ffn.
+ *       x, y, dy, dx, p_attn, p_mlp : [T, H]
+ *       w_qkv [H, 3*Hl]  columns ordered [Q heads | K heads | V heads], dh columns per head
+ *       b_qkv [3*Hl]     w_o [Hl, H]   b_o [H]   w_fc1 [H, Fl]   b_fc1 [Fl]   w_fc2 [Fl, H]   b_fc2 [H]
+ *       ln1_g, ln1_b, ln2_g, ln2_b : [H]
+ *     ("in x out": y = x * W).  Weights are passed ALREADY SHARDED: rank r's column shard is
+ *     columns [r*Hl, (r+1)*Hl) of each of Wq, Wk, Wv (resp. [r*Fl, (r+1)*Fl) of W1); its row shard
+ *     is the same index range of the rows of Wo / W2.
+ *   - Activations and parameters have the element type cfg->dtype (fp32, or bf16 with fp32
+ *     accumulation); parameter gradients are always fp32.
+ *   - Calls only enqueue work on `hip_stream` (a hipStream_t, or NULL for the default stream); they
+ *     never allocate, free or synchronise, and results are bitwise reproducible run to run.
+ *   - Errors are returned as gx_status; nothing is thrown across the boundary.  Configuration and
+ *     pointer checks happen before anything is enqueued.
+ */
+#ifndef GX_H_
+#define GX_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GX_OK = 0,
+  GX_ERR_NULL = 1,      /* a required pointer is NULL */
+  GX_ERR_SHAPE = 2,     /* a size is non-positive or outside what the kernels support */
+  GX_ERR_DIVIS = 3,     /* hidden % heads, heads % tp_attn, ffn % tp_ffn or a vector width fails */
+  GX_ERR_DTYPE = 4,     /* dtype is not GX_F32 / GX_BF16 */
+  GX_ERR_ALIGN = 5,     /* a pointer is not 16-byte aligned */
+  GX_ERR_FLAGS = 6,     /* no phase selected, or unknown flag bits */
+  GX_ERR_ARCH = 7,      /* the current device is not gfx950 */
+  GX_ERR_LAUNCH = 8     /* the HIP runtime refused a launch; see hipGetLastError */
+} gx_status;
+
+typedef enum { GX_F32 = 0, GX_BF16 = 1 } gx_dtype;
+
+enum {
+  GX_PHASE_ATTN = 1,      /* run the attention half */
+  GX_PHASE_MLP = 2,       /* run the feed-forward half (both bits: the whole block) */
+  GX_ROW_BIAS_ATTN = 4,   /* this rank adds b_o to p_attn (exactly one rank of a group should) */
+  GX_ROW_BIAS_MLP = 8,    /* this rank adds b_fc2 to p_mlp */
+  GX_ACCUM_WGRAD = 16,    /* backward: add into the parameter gradients instead of overwriting */
+  GX_RECOMPUTE = 32       /* backward: recompute the forward activations from x; `saved` unused */
+};
+
+/* One rank's share of one block.  tp_rank is informational (which shard the caller passed). */
+typedef struct {
+  int32_t hidden, heads, ffn;
+  int32_t tp_attn, tp_ffn, tp_rank;
+  int32_t seq, micro_batch;
+  int32_t dtype;            /* gx_dtype */
+  int32_t flags;            /* GX_PHASE_* | GX_ROW_BIAS_* | GX_ACCUM_WGRAD | GX_RECOMPUTE */
+  float ln_eps;             /* LayerNorm epsilon (inside the square root; biased variance) */
+} gx_layer_cfg;
+
+/* Parameter shards, element type cfg->dtype.  Pointers of a phase that is not selected may be NULL. */
+typedef struct {
+  const void *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_o, *b_o;
+  const void *ln2_g, *ln2_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
+} gx_params;
+
+/* Parameter gradients, always fp32, same shapes as the parameters. */
+typedef struct {
+  float *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_o, *b_o;
+  float *ln2_g, *ln2_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
+} gx_grads;
+
+/* Host-only check of a configuration (no GPU needed): sizes positive, hidden % heads == 0,
+ * heads % tp_attn == 0, ffn % tp_ffn == 0, 0 <= tp_rank < max(tp_attn, tp_ffn), at least one phase,
+ * no unknown flag, and the kernels' limits: bf16 needs head dim 128, hidden and Fl multiples of 8,
+ * hidden <= 8192; fp32 needs head dim <= 128 and hidden, Fl multiples of 4, hidden <= 4096,
+ * seq <= 8192; every activation tensor must stay below 2 GiB. */
+gx_status gx_layer_validate(const gx_layer_cfg* cfg);
+
+/* Bytes of the opaque `saved` block (activations the forward pass keeps for the backward pass)
+ * and of the opaque `workspace` block (scratch; is_backward selects the pass, and with
+ * GX_RECOMPUTE the backward workspace includes room for the recomputed activations).  Both depend
+ * on cfg's sizes, dtype and flags; 0 is returned for an invalid cfg. */
+size_t gx_layer_saved_bytes(const gx_layer_cfg* cfg);
+size_t gx_layer_workspace_bytes(const gx_layer_cfg* cfg, int is_backward);
+
+/* Forward pass (attention and feed-forward halves as defined at the top of this file).
+ *   both phases : x [T,H] in, y [T,H] out; p_attn / p_mlp optional extra outputs (NULL to skip).
+ *   ATTN only   : x in, p_attn out (required); y, p_mlp ignored.
+ *   MLP only    : x holds h1, p_mlp out (required); y, p_attn ignored.
+ * `saved` (gx_layer_saved_bytes) receives the activations gx_layer_bwd needs; `workspace` may be
+ * NULL when gx_layer_workspace_bytes(cfg, 0) is 0. */
+gx_status gx_layer_fwd(const gx_layer_cfg* cfg, const gx_params* params, const void* x, void* y, void* p_attn,
+                       void* p_mlp, void* saved, void* workspace, void* hip_stream);
+
+/* Backward pass: the exact gradient of what gx_layer_fwd computes for the same cfg.
+ *   both phases : dy = dL/dy in, dx = dL/dx out.
+ *   ATTN only   : dy = dL/dp_attn in, dx = the gradient reaching x through LayerNorm 1 only.
+ *   MLP only    : x holds h1, dy = dL/dp_mlp in, dx = the gradient reaching h1 through LayerNorm 2.
+ * Gradients of the selected phases' parameters are written (or, with GX_ACCUM_WGRAD, added) to
+ * `grads`; a row-parallel bias whose GX_ROW_BIAS_* flag is off gets a zero gradient.  `saved` must
+ * come from gx_layer_fwd with the same cfg, params and x (ignored with GX_RECOMPUTE).  dx may not
+ * alias x or dy. */
+gx_status gx_layer_bwd(const gx_layer_cfg* cfg, const gx_params* params, const void* x, const void* dy, void* dx,
+                       const gx_grads* grads, const void* saved, void* workspace, void* hip_stream);
+
+/* Static strings; never NULL. */
+const char* gx_status_str(gx_status s);
+const char* gx_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GX_H_ */

@@ -1,0 +1,133 @@
+"""ctypes binding of libgx's C ABI (include/gx.h): argument marshalling only.
+
+Pointers are passed as integers (device addresses) or as any object with ``data_ptr()``; the
+stream is a ``hipStream_t`` handle as an integer (0 = default stream).  Every function here has
+the name and meaning of the C entry point it wraps; all compute happens in the library.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgx.so")
+
+GX_OK = 0
+GX_F32, GX_BF16 = 0, 1
+GX_PHASE_ATTN, GX_PHASE_MLP = 1, 2
+GX_ROW_BIAS_ATTN, GX_ROW_BIAS_MLP = 4, 8
+GX_ACCUM_WGRAD, GX_RECOMPUTE = 16, 32
+
+PARAM_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
+               "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
+EXPORTS = ("gx_layer_validate", "gx_layer_saved_bytes", "gx_layer_workspace_bytes", "gx_layer_fwd",
+           "gx_layer_bwd", "gx_status_str", "gx_version")
+
+
+class LayerCfg(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("hidden", "heads", "ffn", "tp_attn", "tp_ffn", "tp_rank", "seq",
+                                               "micro_batch", "dtype", "flags")] + [("ln_eps", ctypes.c_float)]
+
+
+class Params(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in PARAM_NAMES]
+
+
+class Grads(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in PARAM_NAMES]
+
+
+class GxError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__(f"{where}: gx status {self.status} ({status_str(self.status)})")
+
+
+_lib = None
+
+
+def lib():
+    """Load libgx.so (built by ``python -m paper_2504_03662_amd.build``); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} not found: build it with `python -m paper_2504_03662_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        P = ctypes.c_void_p
+        L.gx_layer_validate.argtypes = [ctypes.POINTER(LayerCfg)]
+        L.gx_layer_validate.restype = ctypes.c_int
+        L.gx_layer_saved_bytes.argtypes = [ctypes.POINTER(LayerCfg)]
+        L.gx_layer_saved_bytes.restype = ctypes.c_size_t
+        L.gx_layer_workspace_bytes.argtypes = [ctypes.POINTER(LayerCfg), ctypes.c_int]
+        L.gx_layer_workspace_bytes.restype = ctypes.c_size_t
+        L.gx_layer_fwd.argtypes = [ctypes.POINTER(LayerCfg), ctypes.POINTER(Params), P, P, P, P, P, P, P]
+        L.gx_layer_fwd.restype = ctypes.c_int
+        L.gx_layer_bwd.argtypes = [ctypes.POINTER(LayerCfg), ctypes.POINTER(Params), P, P, P, ctypes.POINTER(Grads),
+                                   P, P, P]
+        L.gx_layer_bwd.restype = ctypes.c_int
+        L.gx_status_str.argtypes = [ctypes.c_int]
+        L.gx_status_str.restype = ctypes.c_char_p
+        L.gx_version.argtypes = []
+        L.gx_version.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def make_cfg(hidden, heads, ffn, tp_attn=1, tp_ffn=1, tp_rank=0, seq=1, micro_batch=1, dtype=GX_F32, flags=3,
+             ln_eps=1e-5):
+    return LayerCfg(hidden, heads, ffn, tp_attn, tp_ffn, tp_rank, seq, micro_batch, dtype, flags, ln_eps)
+
+
+def _struct(cls, tensors):
+    s = cls()
+    for n in PARAM_NAMES:
+        t = tensors.get(n) if tensors else None
+        setattr(s, n, None if t is None else _ptr(t).value)
+    return s
+
+
+def status_str(status):
+    return lib().gx_status_str(int(status)).decode()
+
+
+def version():
+    return lib().gx_version().decode()
+
+
+def layer_validate(cfg):
+    return int(lib().gx_layer_validate(ctypes.byref(cfg)))
+
+
+def layer_saved_bytes(cfg):
+    return int(lib().gx_layer_saved_bytes(ctypes.byref(cfg)))
+
+
+def layer_workspace_bytes(cfg, is_backward):
+    return int(lib().gx_layer_workspace_bytes(ctypes.byref(cfg), int(bool(is_backward))))
+
+
+def layer_fwd(cfg, params, x, y, p_attn, p_mlp, saved, workspace, stream=0, check=True):
+    p = _struct(Params, params)
+    st = lib().gx_layer_fwd(ctypes.byref(cfg), ctypes.byref(p), _ptr(x), _ptr(y), _ptr(p_attn), _ptr(p_mlp),
+                            _ptr(saved), _ptr(workspace), ctypes.c_void_p(stream))
+    if check and st != GX_OK:
+        raise GxError(st, "gx_layer_fwd")
+    return int(st)
+
+
+def layer_bwd(cfg, params, x, dy, dx, grads, saved, workspace, stream=0, check=True):
+    p = _struct(Params, params)
+    g = _struct(Grads, grads)
+    st = lib().gx_layer_bwd(ctypes.byref(cfg), ctypes.byref(p), _ptr(x), _ptr(dy), _ptr(dx), ctypes.byref(g),
+                            _ptr(saved), _ptr(workspace), ctypes.c_void_p(stream))
+    if check and st != GX_OK:
+        raise GxError(st, "gx_layer_bwd")
+    return int(st)

@@ -1,0 +1,486 @@
+// Flash-style causal attention for gfx950, bf16 in / fp32 accumulate, head dim 128.
+//
+// Forward: a workgroup owns a block of query rows of one (sample, head); K and V tiles of 64 rows
+// stream through a double-buffered LDS stage (direct-to-LDS buffer loads).  Each wavefront keeps
+// 32 query rows and works on the transposed problem S^T = K Q^T, so that a lane owns one query
+// column of every v_mfma_f32_32x32x16_bf16 accumulator: the online-softmax row statistics are
+// lane-local (plus one cross-half shuffle), and the probabilities, once rounded to bf16, are
+// already laid out as the B operand of O^T = V^T P^T.  V^T (and every other operand whose
+// reduction index is strided in memory) is read with the transposing ds_read_b64_tr_b16.
+//
+// Backward: D = rowsum(dO * O); then two kernels so that every output has exactly one writer
+// and sums run in a fixed order (no atomics): one owns key/value rows and produces dK, dV, the
+// other owns query rows and produces dQ.  Probabilities are recomputed from the saved
+// log-sum-exp.
+#include "gx_kernels.h"
+
+namespace gx {
+namespace {
+
+constexpr int DH = 128;
+constexpr int ROWB = DH * 2;           // bytes per tile row
+constexpr unsigned OOB = 0x80000000u;
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+// 16 B chunk c of tile row r lives at chunk c ^ swz(r).  The low row bits move whole 64 B groups
+// (4 consecutive rows read by a transposing load fall in distinct banks); the next two bits
+// permute inside a group (16 consecutive rows read by ds_read_b128 at one chunk stay distinct).
+GX_DEVINL int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+
+typedef __attribute__((address_space(3))) bf16x4* lds_bf16x4_ptr;
+
+// direct-to-LDS load of ROWS x DH starting at global row `row0` of one (sample, head, q|k|v)
+// column block; rows at or beyond `nrows` are zero-filled.  elem0 = element offset of (row 0,
+// first column) from the tensor start; ld = row stride in elements.
+template <int ROWS, int NW>
+GX_DEVINL void tile_load(__amdgpu_buffer_rsrc_t rsrc, unsigned elem0, int ld, int row0, int nrows, char* dst,
+                         int wave, int lane) {
+  constexpr int PER_WAVE = ROWS / 4 / NW;
+  static_assert(PER_WAVE >= 1, "tile too small for the workgroup");
+#pragma unroll
+  for (int i = 0; i < PER_WAVE; i++) {
+    const int q = wave * PER_WAVE + i;
+    const int r = 4 * q + (lane >> 4);
+    const int c = (lane & 15) ^ swz(r);
+    const unsigned off = (row0 + r < nrows) ? (elem0 + (unsigned)((row0 + r) * ld + c * 8)) * 2u : OOB;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(dst + q * 1024), 16, off, 0, 0, 0);
+  }
+}
+
+// MFMA operand whose 32 rows are tile rows r0..r0+31 and whose reduction index is the head
+// dimension (step s covers d = 16 s .. 16 s + 15)
+GX_DEVINL bf16x8 frag_rows(const char* tile, int r, int s, int g) {
+  const int c = (2 * s + g) ^ swz(r);
+  return *reinterpret_cast<const bf16x8*>(tile + r * ROWB + (c << 4));
+}
+// MFMA operand whose 32 rows are head-dim columns 32 dt .. 32 dt + 31 and whose reduction index
+// runs over 16 tile rows starting at rbase, in the slot order of an accumulator column
+// (slot (g, e) <-> row rbase + 8 (e / 4) + 4 g + e % 4)
+GX_DEVINL bf16x8 frag_cols(const char* tile, int rbase, int dt, int lane) {
+  const int g = lane >> 5, s = lane & 15, hb = (lane >> 4) & 1;
+  const int r = rbase + 4 * g + (s >> 2);
+  const int d0 = 32 * dt + 16 * hb + 4 * (s & 3);
+  const int c = d0 >> 3, within = (d0 & 7) * 2;
+  const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+      (lds_bf16x4_ptr)(tile + r * ROWB + ((c ^ swz(r)) << 4) + within));
+  const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+      (lds_bf16x4_ptr)(tile + (r + 8) * ROWB + ((c ^ swz(r + 8)) << 4) + within));
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// registers v = 8 h .. 8 h + 7 of an accumulator, rounded to bf16, as an MFMA operand
+GX_DEVINL bf16x8 pack_half(const f32x16& a, int h) {
+  bf16x8 o;
+#pragma unroll
+  for (int e = 0; e < 8; e++) o[e] = (bf16)a[8 * h + e];
+  return o;
+}
+
+GX_DEVINL f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int v = 0; v < 16; v++) z[v] = 0.f;
+  return z;
+}
+
+// this lane's 8 steps of a 32-row operand read straight from global memory (row clamped)
+GX_DEVINL void load_row_frags(const bf16* base, int ld, int row, int nrows, int g, bf16x8 (&out)[DH / 16]) {
+  const bf16* p = base + (size_t)min(row, nrows - 1) * ld + 8 * g;
+#pragma unroll
+  for (int s = 0; s < DH / 16; s++) out[s] = *reinterpret_cast<const bf16x8*>(p + 16 * s);
+}
+
+#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
+#define WAIT_VM0() __builtin_amdgcn_s_waitcnt(0x0F70)
+
+// ------------------------------------------------------------------------------- forward
+constexpr int F_NW = 4, F_BQ = 32 * F_NW, F_BKV = 64;
+constexpr int F_STAGE = 2 * F_BKV * ROWB;      // K tile | V tile
+
+__global__ void __launch_bounds__(64 * F_NW) attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ ctx,
+                                                             float* __restrict__ lse, int S, int nl,
+                                                             unsigned qkv_bytes) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int g = lane >> 5, l32 = lane & 31;
+  const int nq = (S + F_BQ - 1) / F_BQ;
+  const int qt = nq - 1 - blockIdx.x;                 // longest rows first
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int Hl = nl * DH, ld = 3 * Hl;
+  const int i0 = qt * F_BQ, iw = i0 + wave * 32;      // this wave's first query row
+  const unsigned eq = (unsigned)((size_t)b * S * ld + h * DH);
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(qkv), 0, qkv_bytes,
+                                                                        0x00020000);
+  bf16x8 qf[DH / 16];
+  load_row_frags(qkv + eq, ld, iw + l32, S, g, qf);
+
+  f32x16 o[DH / 32];
+#pragma unroll
+  for (int dt = 0; dt < DH / 32; dt++) o[dt] = zero16();
+  float m = -INFINITY, lsum = 0.f;
+  const float c2 = rsqrtf((float)DH) * LOG2E;
+
+  const int jend = min(S, i0 + F_BQ);                 // keys 0 .. jend-1 can be visible
+  const int nt = (jend + F_BKV - 1) / F_BKV;
+  tile_load<F_BKV, F_NW>(rsrc, eq + Hl, ld, 0, S, smem, wave, lane);
+  tile_load<F_BKV, F_NW>(rsrc, eq + 2 * Hl, ld, 0, S, smem + F_BKV * ROWB, wave, lane);
+  WAIT_VM0();
+  __syncthreads();
+  for (int t = 0; t < nt; t++) {
+    const int j0 = t * F_BKV;
+    if (t + 1 < nt) {
+      char* nxt = smem + ((t + 1) & 1) * F_STAGE;
+      tile_load<F_BKV, F_NW>(rsrc, eq + Hl, ld, j0 + F_BKV, S, nxt, wave, lane);
+      tile_load<F_BKV, F_NW>(rsrc, eq + 2 * Hl, ld, j0 + F_BKV, S, nxt + F_BKV * ROWB, wave, lane);
+    }
+    if (j0 <= iw + 31) {                               // wave-uniform: some key of the tile is visible
+      const char* kt = smem + (t & 1) * F_STAGE;
+      const char* vt = kt + F_BKV * ROWB;
+      f32x16 sacc[2];
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++) {
+        sacc[jt] = zero16();
+#pragma unroll
+        for (int s = 0; s < DH / 16; s++) sacc[jt] = MFMA(frag_rows(kt, 32 * jt + l32, s, g), qf[s], sacc[jt]);
+      }
+      // online softmax for query column i = iw + l32 (base-2 exponentials)
+      const int i = iw + l32;
+      const bool diag = (j0 + F_BKV - 1 > iw);
+      float mloc = -INFINITY;
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+          float sv = sacc[jt][v] * c2;
+          if (diag) {
+            const int j = j0 + 32 * jt + 8 * (v >> 2) + 4 * g + (v & 3);
+            if (j > i) sv = -INFINITY;
+          }
+          sacc[jt][v] = sv;
+          mloc = fmaxf(mloc, sv);
+        }
+      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+      const float mnew = fmaxf(m, mloc);
+      const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+      m = mnew;
+      float psum = 0.f;
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+          const float p = __builtin_amdgcn_exp2f(sacc[jt][v] - mnew);
+          sacc[jt][v] = p;
+          psum += p;
+        }
+      lsum = lsum * alpha + psum;
+#pragma unroll
+      for (int dt = 0; dt < DH / 32; dt++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) o[dt][v] *= alpha;
+      // O^T += V^T P^T, 16 keys per step
+#pragma unroll
+      for (int u = 0; u < 4; u++) {
+        const bf16x8 pf = pack_half(sacc[u >> 1], u & 1);
+#pragma unroll
+        for (int dt = 0; dt < DH / 32; dt++) o[dt] = MFMA(frag_cols(vt, 16 * u, dt, lane), pf, o[dt]);
+      }
+    }
+    WAIT_VM0();
+    __syncthreads();
+  }
+  lsum += __shfl_xor(lsum, 32, 64);
+  const int i = iw + l32;
+  if (i < S) {
+    const float inv = 1.0f / lsum;
+    bf16* orow = ctx + ((size_t)b * S + i) * Hl + h * DH;
+#pragma unroll
+    for (int dt = 0; dt < DH / 32; dt++)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; q4++) {
+        bf16x4 pk;
+#pragma unroll
+        for (int e = 0; e < 4; e++) pk[e] = (bf16)(o[dt][4 * q4 + e] * inv);
+        *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * q4 + 4 * g) = pk;
+      }
+    if (g == 0) lse[((size_t)b * nl + h) * S + i] = (m + __builtin_amdgcn_logf(lsum)) * LN2;
+  }
+}
+
+// ------------------------------------------------------------------------------- backward: D
+// D[b, h, s] = sum_d dO * O; 16 lanes per (token, head), 8 elements each
+__global__ void __launch_bounds__(256) attn_dsum_kernel(const bf16* __restrict__ ctx, const bf16* __restrict__ dctx,
+                                                        float* __restrict__ dsum, int B, int S, int nl) {
+  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  const long pair = gid >> 4;                 // (token, head) index
+  const int sub = gid & 15;
+  const long npair = (long)B * S * nl;
+  float acc = 0.f;
+  if (pair < npair) {
+    const bf16x8 a = *reinterpret_cast<const bf16x8*>(ctx + pair * DH + sub * 8);
+    const bf16x8 d = *reinterpret_cast<const bf16x8*>(dctx + pair * DH + sub * 8);
+#pragma unroll
+    for (int e = 0; e < 8; e++) acc += (float)a[e] * (float)d[e];
+  }
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+  if (pair < npair && sub == 0) {
+    const long tok = pair / nl;
+    const int h = (int)(pair % nl);
+    const long b = tok / S, s = tok % S;
+    dsum[(b * nl + h) * S + s] = acc;
+  }
+}
+
+// ------------------------------------------------------------------------------- backward: dK, dV
+constexpr int KV_NW = 4, KV_BJ = 32 * KV_NW, KV_BI = 32;
+constexpr int KV_STAGE = 2 * KV_BI * ROWB + 2 * KV_BI * 4;   // Q tile | dO tile | lse2[32] | D[32]
+
+__global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __restrict__ qkv,
+                                                                  const bf16* __restrict__ dctx,
+                                                                  const float* __restrict__ lse,
+                                                                  const float* __restrict__ dsum,
+                                                                  bf16* __restrict__ dqkv, int S, int nl,
+                                                                  unsigned qkv_bytes, unsigned dctx_bytes) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int g = lane >> 5, l32 = lane & 31;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int Hl = nl * DH, ld = 3 * Hl;
+  const int j0 = blockIdx.x * KV_BJ, jw = j0 + wave * 32;
+  const unsigned eq = (unsigned)((size_t)b * S * ld + h * DH);
+  const unsigned edo = (unsigned)((size_t)b * S * Hl + h * DH);
+  const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(qkv), 0, qkv_bytes,
+                                                                      0x00020000);
+  const __amdgpu_buffer_rsrc_t rdo = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(dctx), 0, dctx_bytes,
+                                                                       0x00020000);
+  bf16x8 kf[DH / 16], vf[DH / 16];
+  load_row_frags(qkv + eq + Hl, ld, jw + l32, S, g, kf);
+  load_row_frags(qkv + eq + 2 * Hl, ld, jw + l32, S, g, vf);
+  f32x16 dk[DH / 32], dv[DH / 32];
+#pragma unroll
+  for (int dt = 0; dt < DH / 32; dt++) { dk[dt] = zero16(); dv[dt] = zero16(); }
+  const float scale = rsqrtf((float)DH), c2 = scale * LOG2E;
+  const float* lrow = lse + ((size_t)b * nl + h) * S;
+  const float* drow = dsum + ((size_t)b * nl + h) * S;
+
+  const int t0 = j0 / KV_BI, nt = (S + KV_BI - 1) / KV_BI;     // query tiles t0 .. nt-1 see these keys
+  auto stage_load = [&](int t) {
+    char* st = smem + (t & 1) * KV_STAGE;
+    tile_load<KV_BI, KV_NW>(rq, eq, ld, t * KV_BI, S, st, wave, lane);
+    tile_load<KV_BI, KV_NW>(rdo, edo, Hl, t * KV_BI, S, st + KV_BI * ROWB, wave, lane);
+    if (threadIdx.x < 64) {
+      float* aux = reinterpret_cast<float*>(st + 2 * KV_BI * ROWB);
+      const int i = t * KV_BI + (threadIdx.x & 31);
+      // rows beyond the sequence get lse = +inf, so their recomputed probabilities are exactly 0
+      if (threadIdx.x < 32) aux[threadIdx.x] = (i < S) ? lrow[i] * LOG2E : INFINITY;
+      else aux[threadIdx.x] = (i < S) ? drow[i] : 0.f;
+    }
+  };
+  stage_load(t0);
+  WAIT_VM0();
+  __syncthreads();
+  for (int t = t0; t < nt; t++) {
+    if (t + 1 < nt) stage_load(t + 1);
+    const int it0 = t * KV_BI;
+    if (it0 + KV_BI - 1 >= jw) {                        // wave-uniform: some query of the tile sees a key
+      const char* qt = smem + (t & 1) * KV_STAGE;
+      const char* dot = qt + KV_BI * ROWB;
+      const float* aux = reinterpret_cast<const float*>(qt + 2 * KV_BI * ROWB);
+      f32x16 sacc = zero16(), pacc = zero16();
+#pragma unroll
+      for (int s = 0; s < DH / 16; s++) {
+        sacc = MFMA(frag_rows(qt, l32, s, g), kf[s], sacc);      // S[i][j]
+        pacc = MFMA(frag_rows(dot, l32, s, g), vf[s], pacc);     // dP[i][j]
+      }
+      const int j = jw + l32;
+      const bool diag = (it0 < jw + 31);
+#pragma unroll
+      for (int q4 = 0; q4 < 4; q4++) {
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(aux + 8 * q4 + 4 * g);
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(aux + 32 + 8 * q4 + 4 * g);
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          const int v = 4 * q4 + e;
+          float p = __builtin_amdgcn_exp2f(sacc[v] * c2 - l4[e]);
+          if (diag && j > it0 + 8 * q4 + 4 * g + e) p = 0.f;
+          sacc[v] = p;
+          pacc[v] = p * (pacc[v] - d4[e]);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 2; u++) {
+        const bf16x8 pf = pack_half(sacc, u), dsf = pack_half(pacc, u);
+#pragma unroll
+        for (int dt = 0; dt < DH / 32; dt++) {
+          dv[dt] = MFMA(pf, frag_cols(dot, 16 * u, dt, lane), dv[dt]);   // dV[j][d] += P^T dO
+          dk[dt] = MFMA(dsf, frag_cols(qt, 16 * u, dt, lane), dk[dt]);   // dK[j][d] += dS^T Q
+        }
+      }
+    }
+    WAIT_VM0();
+    __syncthreads();
+  }
+  // accumulator register v of lane l is row 8 (v/4) + 4 g + v%4, column l%32 of its 32x32 tile
+#pragma unroll
+  for (int dt = 0; dt < DH / 32; dt++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) {
+      const int j = jw + 8 * (v >> 2) + 4 * g + (v & 3);
+      if (j < S) {
+        bf16* row = dqkv + ((size_t)b * S + j) * ld + h * DH + 32 * dt + l32;
+        row[Hl] = (bf16)(dk[dt][v] * scale);
+        row[2 * Hl] = (bf16)dv[dt][v];
+      }
+    }
+}
+
+// ------------------------------------------------------------------------------- backward: dQ
+constexpr int Q_NW = 4, Q_BQ = 32 * Q_NW, Q_BKV = 64;
+constexpr int Q_STAGE = 2 * Q_BKV * ROWB;
+
+__global__ void __launch_bounds__(64 * Q_NW) attn_bwd_dq_kernel(const bf16* __restrict__ qkv,
+                                                                const bf16* __restrict__ dctx,
+                                                                const float* __restrict__ lse,
+                                                                const float* __restrict__ dsum,
+                                                                bf16* __restrict__ dqkv, int S, int nl,
+                                                                unsigned qkv_bytes) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int g = lane >> 5, l32 = lane & 31;
+  const int nq = (S + Q_BQ - 1) / Q_BQ;
+  const int qt = nq - 1 - blockIdx.x;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int Hl = nl * DH, ld = 3 * Hl;
+  const int i0 = qt * Q_BQ, iw = i0 + wave * 32;
+  const unsigned eq = (unsigned)((size_t)b * S * ld + h * DH);
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(qkv), 0, qkv_bytes,
+                                                                        0x00020000);
+  bf16x8 qf[DH / 16], dof[DH / 16];
+  load_row_frags(qkv + eq, ld, iw + l32, S, g, qf);
+  load_row_frags(dctx + (size_t)b * S * Hl + h * DH, Hl, iw + l32, S, g, dof);
+  const int i = iw + l32;
+  const int ic = min(i, S - 1);
+  const float scale = rsqrtf((float)DH), c2 = scale * LOG2E;
+  const float lse2 = lse[((size_t)b * nl + h) * S + ic] * LOG2E;
+  const float dd = dsum[((size_t)b * nl + h) * S + ic];
+  f32x16 dq[DH / 32];
+#pragma unroll
+  for (int dt = 0; dt < DH / 32; dt++) dq[dt] = zero16();
+
+  const int jend = min(S, i0 + Q_BQ);
+  const int nt = (jend + Q_BKV - 1) / Q_BKV;
+  tile_load<Q_BKV, Q_NW>(rsrc, eq + Hl, ld, 0, S, smem, wave, lane);
+  tile_load<Q_BKV, Q_NW>(rsrc, eq + 2 * Hl, ld, 0, S, smem + Q_BKV * ROWB, wave, lane);
+  WAIT_VM0();
+  __syncthreads();
+  for (int t = 0; t < nt; t++) {
+    const int j0 = t * Q_BKV;
+    if (t + 1 < nt) {
+      char* nxt = smem + ((t + 1) & 1) * Q_STAGE;
+      tile_load<Q_BKV, Q_NW>(rsrc, eq + Hl, ld, j0 + Q_BKV, S, nxt, wave, lane);
+      tile_load<Q_BKV, Q_NW>(rsrc, eq + 2 * Hl, ld, j0 + Q_BKV, S, nxt + Q_BKV * ROWB, wave, lane);
+    }
+    if (j0 <= iw + 31) {
+      const char* kt = smem + (t & 1) * Q_STAGE;
+      const char* vt = kt + Q_BKV * ROWB;
+      f32x16 sacc[2], pacc[2];
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++) {
+        sacc[jt] = zero16();
+        pacc[jt] = zero16();
+#pragma unroll
+        for (int s = 0; s < DH / 16; s++) {
+          sacc[jt] = MFMA(frag_rows(kt, 32 * jt + l32, s, g), qf[s], sacc[jt]);    // S^T[j][i]
+          pacc[jt] = MFMA(frag_rows(vt, 32 * jt + l32, s, g), dof[s], pacc[jt]);   // dP^T[j][i]
+        }
+      }
+      const bool diag = (j0 + Q_BKV - 1 > iw);
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+          float p = __builtin_amdgcn_exp2f(sacc[jt][v] * c2 - lse2);
+          if (diag && j0 + 32 * jt + 8 * (v >> 2) + 4 * g + (v & 3) > i) p = 0.f;
+          pacc[jt][v] = p * (pacc[jt][v] - dd);                                    // dS^T
+        }
+#pragma unroll
+      for (int u = 0; u < 4; u++) {
+        const bf16x8 dsf = pack_half(pacc[u >> 1], u & 1);
+#pragma unroll
+        for (int dt = 0; dt < DH / 32; dt++) dq[dt] = MFMA(frag_cols(kt, 16 * u, dt, lane), dsf, dq[dt]);
+      }
+    }
+    WAIT_VM0();
+    __syncthreads();
+  }
+  if (i < S) {
+    bf16* row = dqkv + ((size_t)b * S + i) * ld + h * DH;
+#pragma unroll
+    for (int dt = 0; dt < DH / 32; dt++)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; q4++) {
+        bf16x4 pk;
+#pragma unroll
+        for (int e = 0; e < 4; e++) pk[e] = (bf16)(dq[dt][4 * q4 + e] * scale);
+        *reinterpret_cast<bf16x4*>(row + 32 * dt + 8 * q4 + 4 * g) = pk;
+      }
+  }
+}
+
+template <typename K>
+hipError_t set_smem(K kernel, int bytes) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             bytes);
+}
+
+bool attn_shape_ok(const AttnArgs& a) {
+  if (a.dh != DH || a.B <= 0 || a.S <= 0 || a.nl <= 0) return false;
+  const size_t bytes = (size_t)a.B * a.S * 3 * a.nl * DH * 2;
+  return bytes < (1ul << 31);
+}
+
+}  // namespace
+
+hipError_t attn_fwd_bf16(const AttnArgs& a, hipStream_t s) {
+  if (!attn_shape_ok(a)) return hipErrorInvalidValue;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = set_smem(attn_fwd_kernel, 2 * F_STAGE);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const unsigned qkv_bytes = (unsigned)((size_t)a.B * a.S * 3 * a.nl * DH * 2);
+  dim3 grid(cdiv(a.S, F_BQ), a.nl, a.B);
+  hipLaunchKernelGGL(attn_fwd_kernel, grid, dim3(64 * F_NW), 2 * F_STAGE, s, (const bf16*)a.qkv, (bf16*)a.ctx, a.lse,
+                     a.S, a.nl, qkv_bytes);
+  return hipGetLastError();
+}
+
+hipError_t attn_bwd_bf16(const AttnArgs& a, hipStream_t s) {
+  if (!attn_shape_ok(a)) return hipErrorInvalidValue;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = set_smem(attn_bwd_dkv_kernel, 2 * KV_STAGE);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel, 2 * Q_STAGE);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const unsigned qkv_bytes = (unsigned)((size_t)a.B * a.S * 3 * a.nl * DH * 2);
+  const unsigned dctx_bytes = qkv_bytes / 3;
+  const long npair = (long)a.B * a.S * a.nl;
+  hipLaunchKernelGGL(attn_dsum_kernel, dim3(cdiv(npair * 16, 256)), dim3(256), 0, s, (const bf16*)a.ctx,
+                     (const bf16*)a.dctx, a.dsum, a.B, a.S, a.nl);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3(cdiv(a.S, KV_BJ), a.nl, a.B), dim3(64 * KV_NW), 2 * KV_STAGE, s,
+                     (const bf16*)a.qkv, (const bf16*)a.dctx, a.lse, a.dsum, (bf16*)a.dqkv, a.S, a.nl, qkv_bytes,
+                     dctx_bytes);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(cdiv(a.S, Q_BQ), a.nl, a.B), dim3(64 * Q_NW), 2 * Q_STAGE, s,
+                     (const bf16*)a.qkv, (const bf16*)a.dctx, a.lse, a.dsum, (bf16*)a.dqkv, a.S, a.nl, qkv_bytes);
+  return hipGetLastError();
+}
+
+}  // namespace gx

@@ -1,0 +1,258 @@
+// bf16 MFMA GEMM family for gfx950: the dense contractions of one rank's transformer-block share
+// (column-parallel QKV / FC1, row-parallel out-proj / FC2, their input and weight gradients).
+//
+// One workgroup of 8 wavefronts computes a 256x256 tile of C with a K step of 64.  Operand tiles
+// go from HBM straight into LDS (buffer_load ... lds, 16 B per lane, no register staging) into a
+// double buffer; fragments for v_mfma_f32_32x32x16_bf16 are read with ds_read_b128 when the
+// reduction index is contiguous in memory ("K-major" tiles) and with the transposing
+// ds_read_b64_tr_b16 when it is strided ("MN-major" tiles), so no operand is ever transposed in
+// HBM.  LDS positions are XOR-swizzled on the global-address side because a direct-to-LDS load
+// fixes each lane's LDS slot.
+#include "gx_kernels.h"
+
+namespace gx {
+namespace {
+
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int NTHREADS = 512;
+constexpr int TILE_BYTES = 256 * BK * 2;        // one operand tile: 32 KB
+constexpr int SMEM_BYTES = 4 * TILE_BYTES;      // A[2] | B[2]
+constexpr unsigned OOB = 0x80000000u;           // beyond num_records: the load writes zeros
+
+// K-major tile: [256 rows][64 k], 128 B per row, 16 B chunk c of row r stored at c ^ swz_k(r).
+GX_DEVINL int swz_k(int r) { return (r >> 1) & 7; }
+// MN-major tile: [64 k-rows][256 cols], 512 B per k-row, 16 B chunk c of k-row kr stored at
+// c ^ swz_mn(kr) (moves whole 64 B groups so that 4 consecutive k-rows fall in distinct banks).
+GX_DEVINL int swz_mn(int kr) { return (kr & 3) << 2; }
+
+GX_DEVINL __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+
+template <bool KMAJOR>
+struct TileLoader {
+  // k-invariant part of this lane's four load addresses (elements), and validity
+  unsigned base[4];
+  int kc[4];          // K-major: k offset of the chunk; MN-major: k-row of the chunk
+  __amdgpu_buffer_rsrc_t rsrc;
+  int ld, K;
+
+  GX_DEVINL void init(const bf16* ptr, unsigned bytes, int ld_, int K_, int origin, int extent, int wave,
+                      int lane) {
+    rsrc = make_rsrc(ptr, bytes);
+    ld = ld_;
+    K = K_;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      int q = wave * 4 + i;
+      if (KMAJOR) {
+        int r = 8 * q + (lane >> 3);
+        int c = (lane & 7) ^ swz_k(r);
+        kc[i] = c * 8;
+        base[i] = (origin + r < extent) ? (unsigned)((origin + r) * ld + c * 8) : OOB;
+      } else {
+        int kr = 2 * q + (lane >> 5);
+        int c = (lane & 31) ^ swz_mn(kr);
+        kc[i] = kr;
+        base[i] = (origin + c * 8 < extent) ? (unsigned)(kr * ld + origin + c * 8) : OOB;
+      }
+    }
+  }
+  // issue this wave's share of the tile starting at reduction index k0 into LDS at `dst`
+  GX_DEVINL void issue(char* dst, int k0, int wave) const {
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      unsigned off;
+      if (KMAJOR) off = (base[i] != OOB && k0 + kc[i] < K) ? (base[i] + (unsigned)k0) * 2u : OOB;
+      else        off = (base[i] != OOB && k0 + kc[i] < K) ? (base[i] + (unsigned)(k0 * ld)) * 2u : OOB;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(dst + (wave * 4 + i) * 1024), 16, off, 0, 0, 0);
+    }
+  }
+};
+
+// fragment of a 32-row block for k sub-step ks (16 k), K-major tile
+GX_DEVINL bf16x8 frag_k(const char* tile, int row, int ks, int g) {
+  int c = (2 * ks + g) ^ swz_k(row);
+  return *reinterpret_cast<const bf16x8*>(tile + row * 128 + (c << 4));
+}
+// fragment of a 32-column block for k sub-step ks, MN-major tile (two transposing reads)
+GX_DEVINL bf16x8 frag_mn(const char* tile, int col0, int ks, int lane) {
+  int g = lane >> 5, s = lane & 15;
+  int kr = 16 * ks + 8 * g + (s >> 2);
+  int ne = col0 + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
+  int c = (ne >> 3) ^ swz_mn(kr);
+  const char* p = tile + kr * 512 + (c << 4) + (ne & 7) * 2;
+  typedef __attribute__((address_space(3))) bf16x4* lp;
+  bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lp)(p));
+  bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lp)(p + 4 * 512));
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+template <int LAY, int EPI>
+__global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  constexpr bool A_K = (LAY != LAY_TN);
+  constexpr bool B_K = (LAY == LAY_NT);
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave >> 2, wn = wave & 3;          // 2 x 4 waves, 128 x 64 per wave
+  const int grp = lane >> 5, l32 = lane & 31;
+
+  // tile index: spread consecutive tiles over the 8 XCDs' round-robin dispatch so that each XCD
+  // (own L2) works on a compact block of tiles, then walk tiles in groups of 8 tile-rows.
+  const int tm = (g.M + BM - 1) / BM, tn = (g.N + BN - 1) / BN;
+  int pid = blockIdx.x;
+  const int nwg = gridDim.x;
+  if ((nwg & 7) == 0) pid = (pid & 7) * (nwg >> 3) + (pid >> 3);
+  constexpr int GROUP = 8;
+  const int in_group = GROUP * tn;
+  const int first_m = (pid / in_group) * GROUP;
+  const int gsize = min(tm - first_m, GROUP);
+  const int pm = first_m + (pid % in_group) % gsize;
+  const int pn = (pid % in_group) / gsize;
+  const int m0 = pm * BM, n0 = pn * BN;
+
+  const bf16* A = static_cast<const bf16*>(g.A);
+  const bf16* B = static_cast<const bf16*>(g.B);
+  TileLoader<A_K> la;
+  TileLoader<B_K> lb;
+  la.init(A, (unsigned)((size_t)(A_K ? g.M : g.K) * g.lda * 2), g.lda, g.K, m0, g.M, wave, lane);
+  lb.init(B, (unsigned)((size_t)(B_K ? g.N : g.K) * g.ldb * 2), g.ldb, g.K, n0, g.N, wave, lane);
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; i++)
+#pragma unroll
+    for (int j = 0; j < 2; j++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
+
+  const int nk = (g.K + BK - 1) / BK;
+  la.issue(smem, 0, wave);
+  lb.issue(smem + 2 * TILE_BYTES, 0, wave);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's LDS-DMA has landed
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; kt++) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) {
+      la.issue(smem + (cur ^ 1) * TILE_BYTES, (kt + 1) * BK, wave);
+      lb.issue(smem + (2 + (cur ^ 1)) * TILE_BYTES, (kt + 1) * BK, wave);
+    }
+    const char* ta = smem + cur * TILE_BYTES;
+    const char* tb = smem + (2 + cur) * TILE_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ks++) {
+      bf16x8 af[4], bfr[2];
+#pragma unroll
+      for (int mi = 0; mi < 4; mi++) {
+        if (A_K) af[mi] = frag_k(ta, wm * 128 + mi * 32 + l32, ks, grp);
+        else     af[mi] = frag_mn(ta, wm * 128 + mi * 32, ks, lane);
+      }
+#pragma unroll
+      for (int ni = 0; ni < 2; ni++) {
+        if (B_K) bfr[ni] = frag_k(tb, wn * 64 + ni * 32 + l32, ks, grp);
+        else     bfr[ni] = frag_mn(tb, wn * 64 + ni * 32, ks, lane);
+      }
+#pragma unroll
+      for (int mi = 0; mi < 4; mi++)
+#pragma unroll
+        for (int ni = 0; ni < 2; ni++)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+  }
+
+  // epilogue: accumulator register v of lane l is C[8*(v/4) + 4*(l/32) + v%4][l%32] of its tile
+  const bf16* bias = static_cast<const bf16*>(g.bias);
+  const bf16* resid = static_cast<const bf16*>(g.resid);
+  const bf16* zin = static_cast<const bf16*>(g.z);
+  bf16* aux = static_cast<bf16*>(g.aux);
+#pragma unroll
+  for (int ni = 0; ni < 2; ni++) {
+    const int col = n0 + wn * 64 + ni * 32 + l32;
+    if (col >= g.N) continue;
+    float bv = 0.f;
+    if ((EPI == EPI_BIAS || EPI == EPI_RESID || EPI == EPI_GELU) && bias) bv = (float)bias[col];
+#pragma unroll
+    for (int mi = 0; mi < 4; mi++) {
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        const int row = m0 + wm * 128 + mi * 32 + 8 * (v >> 2) + 4 * grp + (v & 3);
+        if (row >= g.M) continue;
+        const size_t idx = (size_t)row * g.ldc + col;
+        float x = acc[mi][ni][v];
+        if (EPI == EPI_STORE) {
+          static_cast<bf16*>(g.C)[idx] = (bf16)x;
+        } else if (EPI == EPI_BIAS) {
+          static_cast<bf16*>(g.C)[idx] = (bf16)(x + bv);
+        } else if (EPI == EPI_RESID) {
+          x += bv;
+          if (aux) aux[idx] = (bf16)x;
+          static_cast<bf16*>(g.C)[idx] = (bf16)(x + (float)resid[idx]);
+        } else if (EPI == EPI_GELU) {
+          x += bv;
+          static_cast<bf16*>(g.C)[idx] = (bf16)x;
+          aux[idx] = (bf16)gelu_f(x);
+        } else if (EPI == EPI_DGELU) {
+          static_cast<bf16*>(g.C)[idx] = (bf16)(x * gelu_grad_f((float)zin[idx]));
+        } else if (EPI == EPI_F32) {
+          static_cast<float*>(g.C)[idx] = x;
+        } else {
+          static_cast<float*>(g.C)[idx] += x;
+        }
+      }
+    }
+  }
+}
+
+template <int LAY, int EPI>
+hipError_t launch(const GemmArgs& g, hipStream_t s) {
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<LAY, EPI>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int tm = cdiv(g.M, BM), tn = cdiv(g.N, BN);
+  hipLaunchKernelGGL((gemm_kernel<LAY, EPI>), dim3(tm * tn), dim3(NTHREADS), SMEM_BYTES, s, g);
+  return hipGetLastError();
+}
+
+template <int LAY>
+hipError_t dispatch_epi(Epilogue epi, const GemmArgs& g, hipStream_t s) {
+  switch (epi) {
+    case EPI_STORE: return launch<LAY, EPI_STORE>(g, s);
+    case EPI_BIAS: return launch<LAY, EPI_BIAS>(g, s);
+    case EPI_RESID: return launch<LAY, EPI_RESID>(g, s);
+    case EPI_GELU: return launch<LAY, EPI_GELU>(g, s);
+    case EPI_DGELU: return launch<LAY, EPI_DGELU>(g, s);
+    case EPI_F32: return launch<LAY, EPI_F32>(g, s);
+    case EPI_F32_ACC: return launch<LAY, EPI_F32_ACC>(g, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+hipError_t gemm_bf16(Layout lay, Epilogue epi, const GemmArgs& g, hipStream_t s) {
+  if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
+  // 16-byte chunks along each operand's contiguous index; 31-bit byte offsets in buffer loads
+  const long a_rows = (lay == LAY_TN) ? g.K : g.M, b_rows = (lay == LAY_NT) ? g.N : g.K;
+  if ((g.lda & 7) || (g.ldb & 7)) return hipErrorInvalidValue;
+  if (lay != LAY_TN && (g.K & 7)) return hipErrorInvalidValue;
+  if (lay == LAY_TN && (g.M & 7)) return hipErrorInvalidValue;
+  if (lay != LAY_NT && (g.N & 7)) return hipErrorInvalidValue;
+  if (a_rows * g.lda * 2 >= (1L << 31) || b_rows * g.ldb * 2 >= (1L << 31)) return hipErrorInvalidValue;
+  if ((reinterpret_cast<uintptr_t>(g.A) | reinterpret_cast<uintptr_t>(g.B)) & 15) return hipErrorInvalidValue;
+  switch (lay) {
+    case LAY_NN: return dispatch_epi<LAY_NN>(epi, g, s);
+    case LAY_NT: return dispatch_epi<LAY_NT>(epi, g, s);
+    case LAY_TN: return dispatch_epi<LAY_TN>(epi, g, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace gx

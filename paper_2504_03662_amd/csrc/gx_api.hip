@@ -1,0 +1,411 @@
+// C-ABI entry points of libgx: validation, buffer planning and the kernel sequences of one
+// rank's block forward and backward pass.  Everything here is host code that only enqueues
+// kernels on the caller's stream.
+#include "../../include/gx.h"
+#include "gx_kernels.h"
+
+#include <string.h>
+
+namespace {
+
+using namespace gx;
+
+constexpr int ALL_FLAGS = GX_PHASE_ATTN | GX_PHASE_MLP | GX_ROW_BIAS_ATTN | GX_ROW_BIAS_MLP | GX_ACCUM_WGRAD |
+                          GX_RECOMPUTE;
+
+struct Dims {
+  long T, H, Hl, Fl, S, B, nl, dh;
+  size_t e;        // bytes per activation element
+  bool bf;
+};
+
+Dims dims_of(const gx_layer_cfg& c) {
+  Dims d;
+  d.H = c.hidden;
+  d.dh = c.hidden / c.heads;
+  d.nl = c.heads / c.tp_attn;
+  d.Hl = d.nl * d.dh;
+  d.Fl = c.ffn / c.tp_ffn;
+  d.S = c.seq;
+  d.B = c.micro_batch;
+  d.T = d.S * d.B;
+  d.bf = (c.dtype == GX_BF16);
+  d.e = d.bf ? 2 : 4;
+  return d;
+}
+
+size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// Bump allocator over an opaque block; with base == nullptr it only measures.
+struct Arena {
+  char* base;
+  size_t off = 0;
+  explicit Arena(void* b) : base(static_cast<char*>(b)) {}
+  void* take(size_t bytes) {
+    void* p = base ? base + off : nullptr;
+    off += align_up(bytes);
+    return p;
+  }
+};
+
+// Activations the forward pass keeps for the backward pass.
+struct Saved {
+  float *mean1, *rstd1, *lse, *mean2, *rstd2;
+  void *y1, *qkv, *ctx, *h1, *y2, *z, *act;
+};
+
+Saved plan_saved(const gx_layer_cfg& c, Arena& a) {
+  const Dims d = dims_of(c);
+  Saved s;
+  memset(&s, 0, sizeof(s));
+  if (c.flags & GX_PHASE_ATTN) {
+    s.mean1 = static_cast<float*>(a.take(d.T * 4));
+    s.rstd1 = static_cast<float*>(a.take(d.T * 4));
+    s.y1 = a.take(d.T * d.H * d.e);
+    s.qkv = a.take(d.T * 3 * d.Hl * d.e);
+    s.ctx = a.take(d.T * d.Hl * d.e);
+    s.lse = static_cast<float*>(a.take(d.B * d.nl * d.S * 4));
+  }
+  if ((c.flags & GX_PHASE_ATTN) && (c.flags & GX_PHASE_MLP)) s.h1 = a.take(d.T * d.H * d.e);
+  if (c.flags & GX_PHASE_MLP) {
+    s.mean2 = static_cast<float*>(a.take(d.T * 4));
+    s.rstd2 = static_cast<float*>(a.take(d.T * 4));
+    s.y2 = a.take(d.T * d.H * d.e);
+    s.z = a.take(d.T * d.Fl * d.e);
+    s.act = a.take(d.T * d.Fl * d.e);
+  }
+  return s;
+}
+
+// Backward scratch.
+struct Work {
+  void *dz, *dyn, *dh1, *dctx, *dqkv;
+  float *dsum, *part;
+  void* recomputed;     // a Saved block when GX_RECOMPUTE is set
+};
+
+Work plan_work(const gx_layer_cfg& c, Arena& a) {
+  const Dims d = dims_of(c);
+  Work w;
+  memset(&w, 0, sizeof(w));
+  w.dyn = a.take(d.T * d.H * d.e);
+  if (c.flags & GX_PHASE_MLP) w.dz = a.take(d.T * d.Fl * d.e);
+  if ((c.flags & GX_PHASE_ATTN) && (c.flags & GX_PHASE_MLP)) w.dh1 = a.take(d.T * d.H * d.e);
+  if (c.flags & GX_PHASE_ATTN) {
+    w.dctx = a.take(d.T * d.Hl * d.e);
+    w.dqkv = a.take(d.T * 3 * d.Hl * d.e);
+    w.dsum = static_cast<float*>(a.take(d.B * d.nl * d.S * 4));
+  }
+  long widest = d.H;
+  if (3 * d.Hl > widest) widest = 3 * d.Hl;
+  if (d.Fl > widest) widest = d.Fl;
+  size_t part = (size_t)colsum_blocks((int)d.T) * widest;
+  const size_t lnpart = 2ul * ln_bwd_blocks((int)d.T) * d.H;
+  if (lnpart > part) part = lnpart;
+  w.part = static_cast<float*>(a.take(part * 4));
+  if (c.flags & GX_RECOMPUTE) {
+    Arena probe(nullptr);
+    plan_saved(c, probe);
+    w.recomputed = a.take(probe.off);
+  }
+  return w;
+}
+
+gx_status validate(const gx_layer_cfg* c) {
+  if (!c) return GX_ERR_NULL;
+  if (c->dtype != GX_F32 && c->dtype != GX_BF16) return GX_ERR_DTYPE;
+  if (c->hidden <= 0 || c->heads <= 0 || c->ffn <= 0 || c->tp_attn <= 0 || c->tp_ffn <= 0 || c->seq <= 0 ||
+      c->micro_batch <= 0 || !(c->ln_eps >= 0.f))
+    return GX_ERR_SHAPE;
+  if ((c->flags & ~ALL_FLAGS) || !(c->flags & (GX_PHASE_ATTN | GX_PHASE_MLP))) return GX_ERR_FLAGS;
+  if (c->hidden % c->heads || c->heads % c->tp_attn || c->ffn % c->tp_ffn) return GX_ERR_DIVIS;
+  const int tpmax = c->tp_attn > c->tp_ffn ? c->tp_attn : c->tp_ffn;
+  if (c->tp_rank < 0 || c->tp_rank >= tpmax) return GX_ERR_SHAPE;
+  const Dims d = dims_of(*c);
+  const int vec = d.bf ? 8 : 4;
+  if (d.H % vec || d.Fl % vec || d.Hl % vec) return GX_ERR_DIVIS;
+  if (d.bf) {
+    if (d.dh != 128 || d.H > 8192) return GX_ERR_SHAPE;
+  } else {
+    if (d.dh > 128 || d.H > 4096 || d.S > 8192) return GX_ERR_SHAPE;
+  }
+  long widest = d.H;
+  if (3 * d.Hl > widest) widest = 3 * d.Hl;
+  if (d.Fl > widest) widest = d.Fl;
+  if ((size_t)d.T * widest * d.e >= (1ul << 31)) return GX_ERR_SHAPE;
+  // weight shards are also addressed with 31-bit byte offsets
+  if ((size_t)d.H * 3 * d.Hl * d.e >= (1ul << 31) || (size_t)d.H * d.Fl * d.e >= (1ul << 31)) return GX_ERR_SHAPE;
+  return GX_OK;
+}
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
+
+gx_status check_arch() {
+  static int cached = -1;     // per process; the library targets a single architecture
+  if (cached < 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return GX_ERR_ARCH;
+    cached = (strncmp(prop.gcnArchName, "gfx950", 6) == 0) ? 1 : 0;
+  }
+  return cached == 1 ? GX_OK : GX_ERR_ARCH;
+}
+
+#define GX_TRY(expr)                              \
+  do {                                            \
+    if ((expr) != hipSuccess) return GX_ERR_LAUNCH; \
+  } while (0)
+
+hipError_t gemm(const Dims& d, Layout lay, Epilogue epi, const GemmArgs& g, hipStream_t s) {
+  return d.bf ? gemm_bf16(lay, epi, g, s) : gemm_f32(lay, epi, g, s);
+}
+
+GemmArgs gargs(const void* A, const void* B, void* C, long M, long N, long K, long lda, long ldb, long ldc) {
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  g.A = A; g.B = B; g.C = C;
+  g.M = (int)M; g.N = (int)N; g.K = (int)K;
+  g.lda = (int)lda; g.ldb = (int)ldb; g.ldc = (int)ldc;
+  return g;
+}
+
+__global__ void fill_zero_kernel(float* p, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+
+// Forward kernel sequence.  `for_backward_only` skips the products whose results the backward
+// pass does not need (used when recomputing activations).
+gx_status run_fwd(const gx_layer_cfg& c, const gx_params& p, const void* x, void* y, void* p_attn, void* p_mlp,
+                  const Saved& sv, bool for_backward_only, hipStream_t st) {
+  const Dims d = dims_of(c);
+  const bool attn = c.flags & GX_PHASE_ATTN, mlp = c.flags & GX_PHASE_MLP;
+  const void* h1 = x;
+  if (attn) {
+    GX_TRY(ln_fwd(d.bf, x, p.ln1_g, p.ln1_b, sv.y1, sv.mean1, sv.rstd1, (int)d.T, (int)d.H, c.ln_eps, st));
+    GemmArgs g = gargs(sv.y1, p.w_qkv, sv.qkv, d.T, 3 * d.Hl, d.H, d.H, 3 * d.Hl, 3 * d.Hl);
+    g.bias = p.b_qkv;
+    GX_TRY(gemm(d, LAY_NN, EPI_BIAS, g, st));
+    AttnArgs a;
+    memset(&a, 0, sizeof(a));
+    a.qkv = sv.qkv; a.ctx = sv.ctx; a.lse = sv.lse;
+    a.B = (int)d.B; a.S = (int)d.S; a.nl = (int)d.nl; a.dh = (int)d.dh;
+    GX_TRY(d.bf ? attn_fwd_bf16(a, st) : attn_fwd_f32(a, st));
+    if (mlp) {
+      GemmArgs o = gargs(sv.ctx, p.w_o, sv.h1, d.T, d.H, d.Hl, d.Hl, d.H, d.H);
+      o.bias = (c.flags & GX_ROW_BIAS_ATTN) ? p.b_o : nullptr;
+      o.resid = x;
+      o.aux = p_attn;
+      GX_TRY(gemm(d, LAY_NN, EPI_RESID, o, st));
+      h1 = sv.h1;
+    } else if (!for_backward_only) {
+      GemmArgs o = gargs(sv.ctx, p.w_o, p_attn, d.T, d.H, d.Hl, d.Hl, d.H, d.H);
+      o.bias = (c.flags & GX_ROW_BIAS_ATTN) ? p.b_o : nullptr;
+      GX_TRY(gemm(d, LAY_NN, EPI_BIAS, o, st));
+    }
+  }
+  if (mlp) {
+    GX_TRY(ln_fwd(d.bf, h1, p.ln2_g, p.ln2_b, sv.y2, sv.mean2, sv.rstd2, (int)d.T, (int)d.H, c.ln_eps, st));
+    GemmArgs f1 = gargs(sv.y2, p.w_fc1, sv.z, d.T, d.Fl, d.H, d.H, d.Fl, d.Fl);
+    f1.bias = p.b_fc1;
+    f1.aux = sv.act;
+    GX_TRY(gemm(d, LAY_NN, EPI_GELU, f1, st));
+    if (!for_backward_only) {
+      GemmArgs f2 = gargs(sv.act, p.w_fc2, attn ? y : p_mlp, d.T, d.H, d.Fl, d.Fl, d.H, d.H);
+      f2.bias = (c.flags & GX_ROW_BIAS_MLP) ? p.b_fc2 : nullptr;
+      if (attn) {
+        f2.resid = h1;
+        f2.aux = p_mlp;
+        GX_TRY(gemm(d, LAY_NN, EPI_RESID, f2, st));
+      } else {
+        GX_TRY(gemm(d, LAY_NN, EPI_BIAS, f2, st));
+      }
+    }
+  }
+  return GX_OK;
+}
+
+gx_status bias_grad(const Dims& d, const gx_layer_cfg& c, bool enabled, const void* src, long cols, float* part,
+                    float* out, hipStream_t st) {
+  const bool acc = c.flags & GX_ACCUM_WGRAD;
+  if (enabled) {
+    GX_TRY(colsum(d.bf, src, (int)d.T, (int)cols, (int)cols, part, out, acc, st));
+  } else if (!acc) {
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(cdiv(cols, 256)), dim3(256), 0, st, out, (int)cols);
+    GX_TRY(hipGetLastError());
+  }
+  return GX_OK;
+}
+
+gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, const void* dy, void* dx,
+                  const gx_grads& gr, const Saved& sv, const Work& w, hipStream_t st) {
+  const Dims d = dims_of(c);
+  const bool attn = c.flags & GX_PHASE_ATTN, mlp = c.flags & GX_PHASE_MLP;
+  const Epilogue wg = (c.flags & GX_ACCUM_WGRAD) ? EPI_F32_ACC : EPI_F32;
+  const bool acc = c.flags & GX_ACCUM_WGRAD;
+  const void* dcur = dy;           // gradient arriving at the attention half's output
+  if (mlp) {
+    const void* h1 = attn ? sv.h1 : x;
+    // row-parallel FC2: weight gradient, bias gradient, input gradient fused with GELU'
+    GemmArgs w2 = gargs(sv.act, dy, gr.w_fc2, d.Fl, d.H, d.T, d.Fl, d.H, d.H);
+    GX_TRY(gemm(d, LAY_TN, wg, w2, st));
+    gx_status s = bias_grad(d, c, c.flags & GX_ROW_BIAS_MLP, dy, d.H, w.part, gr.b_fc2, st);
+    if (s != GX_OK) return s;
+    GemmArgs dz = gargs(dy, p.w_fc2, w.dz, d.T, d.Fl, d.H, d.H, d.H, d.Fl);
+    dz.z = sv.z;
+    GX_TRY(gemm(d, LAY_NT, EPI_DGELU, dz, st));
+    GX_TRY(colsum(d.bf, w.dz, (int)d.T, (int)d.Fl, (int)d.Fl, w.part, gr.b_fc1, acc, st));
+    // column-parallel FC1
+    GemmArgs w1 = gargs(sv.y2, w.dz, gr.w_fc1, d.H, d.Fl, d.T, d.H, d.Fl, d.Fl);
+    GX_TRY(gemm(d, LAY_TN, wg, w1, st));
+    GemmArgs dy2 = gargs(w.dz, p.w_fc1, w.dyn, d.T, d.H, d.Fl, d.Fl, d.Fl, d.H);
+    GX_TRY(gemm(d, LAY_NT, EPI_STORE, dy2, st));
+    // LayerNorm 2; with both phases the residual branch adds dy
+    void* out = attn ? w.dh1 : dx;
+    GX_TRY(ln_bwd(d.bf, w.dyn, h1, p.ln2_g, sv.mean2, sv.rstd2, attn ? dy : nullptr, out, w.part, (int)d.T, (int)d.H,
+                  st));
+    const int nb = ln_bwd_blocks((int)d.T);
+    GX_TRY(colsum_finish(w.part, nb, (int)d.H, gr.ln2_g, acc, st));
+    GX_TRY(colsum_finish(w.part + (size_t)nb * d.H, nb, (int)d.H, gr.ln2_b, acc, st));
+    dcur = w.dh1;
+  }
+  if (attn) {
+    // row-parallel output projection
+    GemmArgs wo = gargs(sv.ctx, dcur, gr.w_o, d.Hl, d.H, d.T, d.Hl, d.H, d.H);
+    GX_TRY(gemm(d, LAY_TN, wg, wo, st));
+    gx_status s = bias_grad(d, c, c.flags & GX_ROW_BIAS_ATTN, dcur, d.H, w.part, gr.b_o, st);
+    if (s != GX_OK) return s;
+    GemmArgs dc = gargs(dcur, p.w_o, w.dctx, d.T, d.Hl, d.H, d.H, d.H, d.Hl);
+    GX_TRY(gemm(d, LAY_NT, EPI_STORE, dc, st));
+    AttnArgs a;
+    memset(&a, 0, sizeof(a));
+    a.qkv = sv.qkv; a.ctx = sv.ctx; a.lse = sv.lse; a.dctx = w.dctx; a.dqkv = w.dqkv; a.dsum = w.dsum;
+    a.B = (int)d.B; a.S = (int)d.S; a.nl = (int)d.nl; a.dh = (int)d.dh;
+    GX_TRY(d.bf ? attn_bwd_bf16(a, st) : attn_bwd_f32(a, st));
+    // column-parallel QKV
+    GX_TRY(colsum(d.bf, w.dqkv, (int)d.T, (int)(3 * d.Hl), (int)(3 * d.Hl), w.part, gr.b_qkv, acc, st));
+    GemmArgs wq = gargs(sv.y1, w.dqkv, gr.w_qkv, d.H, 3 * d.Hl, d.T, d.H, 3 * d.Hl, 3 * d.Hl);
+    GX_TRY(gemm(d, LAY_TN, wg, wq, st));
+    GemmArgs dy1 = gargs(w.dqkv, p.w_qkv, w.dyn, d.T, d.H, 3 * d.Hl, 3 * d.Hl, 3 * d.Hl, d.H);
+    GX_TRY(gemm(d, LAY_NT, EPI_STORE, dy1, st));
+    GX_TRY(ln_bwd(d.bf, w.dyn, x, p.ln1_g, sv.mean1, sv.rstd1, mlp ? dcur : nullptr, dx, w.part, (int)d.T, (int)d.H,
+                  st));
+    const int nb = ln_bwd_blocks((int)d.T);
+    GX_TRY(colsum_finish(w.part, nb, (int)d.H, gr.ln1_g, acc, st));
+    GX_TRY(colsum_finish(w.part + (size_t)nb * d.H, nb, (int)d.H, gr.ln1_b, acc, st));
+  }
+  return GX_OK;
+}
+
+gx_status check_params(const gx_layer_cfg& c, const gx_params& p) {
+  const void* a[] = {p.ln1_g, p.ln1_b, p.w_qkv, p.b_qkv, p.w_o, p.b_o};
+  const void* m[] = {p.ln2_g, p.ln2_b, p.w_fc1, p.b_fc1, p.w_fc2, p.b_fc2};
+  if (c.flags & GX_PHASE_ATTN)
+    for (const void* q : a) {
+      if (!q) return GX_ERR_NULL;
+      if (misaligned(q)) return GX_ERR_ALIGN;
+    }
+  if (c.flags & GX_PHASE_MLP)
+    for (const void* q : m) {
+      if (!q) return GX_ERR_NULL;
+      if (misaligned(q)) return GX_ERR_ALIGN;
+    }
+  return GX_OK;
+}
+
+gx_status check_grads(const gx_layer_cfg& c, const gx_grads& g) {
+  const float* a[] = {g.ln1_g, g.ln1_b, g.w_qkv, g.b_qkv, g.w_o, g.b_o};
+  const float* m[] = {g.ln2_g, g.ln2_b, g.w_fc1, g.b_fc1, g.w_fc2, g.b_fc2};
+  if (c.flags & GX_PHASE_ATTN)
+    for (const float* q : a) {
+      if (!q) return GX_ERR_NULL;
+      if (misaligned(q)) return GX_ERR_ALIGN;
+    }
+  if (c.flags & GX_PHASE_MLP)
+    for (const float* q : m) {
+      if (!q) return GX_ERR_NULL;
+      if (misaligned(q)) return GX_ERR_ALIGN;
+    }
+  return GX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+gx_status gx_layer_validate(const gx_layer_cfg* cfg) { return validate(cfg); }
+
+size_t gx_layer_saved_bytes(const gx_layer_cfg* cfg) {
+  if (validate(cfg) != GX_OK) return 0;
+  Arena a(nullptr);
+  plan_saved(*cfg, a);
+  return a.off;
+}
+
+size_t gx_layer_workspace_bytes(const gx_layer_cfg* cfg, int is_backward) {
+  if (validate(cfg) != GX_OK || !is_backward) return 0;
+  Arena a(nullptr);
+  plan_work(*cfg, a);
+  return a.off;
+}
+
+gx_status gx_layer_fwd(const gx_layer_cfg* cfg, const gx_params* params, const void* x, void* y, void* p_attn,
+                       void* p_mlp, void* saved, void* workspace, void* hip_stream) {
+  (void)workspace;
+  gx_status s = validate(cfg);
+  if (s != GX_OK) return s;
+  if (!params || !x || !saved) return GX_ERR_NULL;
+  const bool attn = cfg->flags & GX_PHASE_ATTN, mlp = cfg->flags & GX_PHASE_MLP;
+  if (attn && mlp && !y) return GX_ERR_NULL;
+  if (attn && !mlp && !p_attn) return GX_ERR_NULL;
+  if (!attn && mlp && !p_mlp) return GX_ERR_NULL;
+  if (misaligned(x) || misaligned(y) || misaligned(p_attn) || misaligned(p_mlp) || misaligned(saved))
+    return GX_ERR_ALIGN;
+  if ((s = check_params(*cfg, *params)) != GX_OK) return s;
+  if ((s = check_arch()) != GX_OK) return s;
+  Arena a(saved);
+  const Saved sv = plan_saved(*cfg, a);
+  return run_fwd(*cfg, *params, x, y, p_attn, p_mlp, sv, false, static_cast<hipStream_t>(hip_stream));
+}
+
+gx_status gx_layer_bwd(const gx_layer_cfg* cfg, const gx_params* params, const void* x, const void* dy, void* dx,
+                       const gx_grads* grads, const void* saved, void* workspace, void* hip_stream) {
+  gx_status s = validate(cfg);
+  if (s != GX_OK) return s;
+  const bool recompute = cfg->flags & GX_RECOMPUTE;
+  if (!params || !x || !dy || !dx || !grads || !workspace || (!recompute && !saved)) return GX_ERR_NULL;
+  if (misaligned(x) || misaligned(dy) || misaligned(dx) || misaligned(workspace) || (!recompute && misaligned(saved)))
+    return GX_ERR_ALIGN;
+  if ((s = check_params(*cfg, *params)) != GX_OK) return s;
+  if ((s = check_grads(*cfg, *grads)) != GX_OK) return s;
+  if ((s = check_arch()) != GX_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  Arena wa(workspace);
+  const Work w = plan_work(*cfg, wa);
+  Arena sa(recompute ? w.recomputed : const_cast<void*>(saved));
+  const Saved sv = plan_saved(*cfg, sa);
+  if (recompute) {
+    s = run_fwd(*cfg, *params, x, nullptr, nullptr, nullptr, sv, true, st);
+    if (s != GX_OK) return s;
+  }
+  return run_bwd(*cfg, *params, x, dy, dx, *grads, sv, w, st);
+}
+
+const char* gx_status_str(gx_status s) {
+  switch (s) {
+    case GX_OK: return "ok";
+    case GX_ERR_NULL: return "a required pointer is NULL";
+    case GX_ERR_SHAPE: return "a size is non-positive or outside the supported range";
+    case GX_ERR_DIVIS: return "sizes are not divisible as the sharding or vector width requires";
+    case GX_ERR_DTYPE: return "unknown dtype";
+    case GX_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+    case GX_ERR_FLAGS: return "no phase selected or unknown flag bits";
+    case GX_ERR_ARCH: return "the current device is not gfx950";
+    case GX_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+  }
+  return "unknown status";
+}
+
+const char* gx_version(void) { return "gx 0.1 (gfx950)"; }
+
+}  // extern "C"

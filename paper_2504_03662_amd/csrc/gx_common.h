@@ -1,0 +1,46 @@
+// Internal helpers shared by the HIP translation units of the library (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gx {
+
+typedef __bf16 bf16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+
+#define GX_DEVINL __device__ __forceinline__
+
+GX_DEVINL float to_f32(float v) { return v; }
+GX_DEVINL float to_f32(bf16 v) { return (float)v; }
+template <typename T> GX_DEVINL T from_f32(float v);
+template <> GX_DEVINL float from_f32<float>(float v) { return v; }
+template <> GX_DEVINL bf16 from_f32<bf16>(float v) { return (bf16)v; }   // round to nearest even
+
+// exact (erf) GELU and its derivative, fp32
+GX_DEVINL float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f)); }
+GX_DEVINL float gelu_grad_f(float z) {
+  float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752440f));
+  float pdf = 0.39894228040143267794f * __expf(-0.5f * z * z);
+  return cdf + z * pdf;
+}
+
+GX_DEVINL float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+GX_DEVINL float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
+
+}  // namespace gx

@@ -1,0 +1,70 @@
+// Internal launcher interface between the layer driver and the kernel translation units.
+#pragma once
+#include "gx_common.h"
+
+namespace gx {
+
+// C[M,N] = op(A) * op(B), all matrices row-major with leading dimensions in elements.
+//   NN: A is [M,K], B is [K,N]      (forward: activations times "in x out" weights)
+//   NT: A is [M,K], B is [N,K]      (input gradient: dY times W^T, reduction over W's columns)
+//   TN: A is [K,M], B is [K,N]      (weight gradient: X^T times dY, reduction over tokens)
+enum Layout { LAY_NN = 0, LAY_NT = 1, LAY_TN = 2 };
+
+enum Epilogue {
+  EPI_STORE = 0,   // C = acc                                   (storage type)
+  EPI_BIAS,        // C = acc + bias[n]            (bias may be null)
+  EPI_RESID,       // p = acc + bias[n]; aux = p if aux; C = resid + p
+  EPI_GELU,        // z = acc + bias[n]; C = z; aux = gelu(z)
+  EPI_DGELU,       // C = acc * gelu'(z[m,n])
+  EPI_F32,         // C (fp32) = acc
+  EPI_F32_ACC      // C (fp32) += acc
+};
+
+struct GemmArgs {
+  const void* A;
+  const void* B;
+  void* C;
+  int M, N, K;
+  int lda, ldb, ldc;
+  const void* bias;    // [N], storage type
+  const void* resid;   // [M, ldc], storage type
+  void* aux;           // [M, ldc], storage type
+  const void* z;       // [M, ldc], storage type
+};
+
+hipError_t gemm_bf16(Layout lay, Epilogue epi, const GemmArgs& g, hipStream_t s);
+hipError_t gemm_f32(Layout lay, Epilogue epi, const GemmArgs& g, hipStream_t s);
+
+// Causal attention over the local heads.  qkv is [T, 3*Hl] with column blocks [Q | K | V], each
+// head's dh columns contiguous; ctx / dctx are [T, Hl]; lse and dsum are [B, nl, S] fp32.
+struct AttnArgs {
+  const void* qkv;
+  void* ctx;          // fwd out / bwd in
+  float* lse;         // fwd out / bwd in: log-sum-exp of the scaled, masked scores per row
+  const void* dctx;   // bwd in
+  void* dqkv;         // bwd out, same layout as qkv
+  float* dsum;        // bwd scratch: rowsum(dctx * ctx)
+  int B, S, nl, dh;
+};
+hipError_t attn_fwd_bf16(const AttnArgs& a, hipStream_t s);
+hipError_t attn_bwd_bf16(const AttnArgs& a, hipStream_t s);
+hipError_t attn_fwd_f32(const AttnArgs& a, hipStream_t s);
+hipError_t attn_bwd_f32(const AttnArgs& a, hipStream_t s);
+
+// Row-wise and column-sum kernels, templated on storage type through the `bf16` switch.
+// LayerNorm forward: y = g * (x - mean) * rstd + b; writes mean/rstd per row.
+hipError_t ln_fwd(bool bf16, const void* x, const void* g, const void* b, void* y, float* mean, float* rstd,
+                  int rows, int cols, float eps, hipStream_t s);
+// LayerNorm backward: dx = (resid ? resid : 0) + LNbwd(dy); per-block partial sums of dg/db go
+// to part[2][nblk][cols]; returns nblk through the sizing helper below.
+hipError_t ln_bwd(bool bf16, const void* dy, const void* x, const void* g, const float* mean, const float* rstd,
+                  const void* resid, void* dx, float* part, int rows, int cols, hipStream_t s);
+int ln_bwd_blocks(int rows);
+// Finish a two-stage column reduction: out[c] (=|+=) sum_b part[b][c].
+hipError_t colsum_finish(const float* part, int nblk, int cols, float* out, bool accumulate, hipStream_t s);
+// Column sums of a [rows, cols] matrix into fp32 out[cols] (two-stage, fixed order).
+hipError_t colsum(bool bf16, const void* a, int rows, int cols, int ld, float* part, float* out, bool accumulate,
+                  hipStream_t s);
+int colsum_blocks(int rows);
+
+}  // namespace gx

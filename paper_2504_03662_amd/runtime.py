@@ -1,0 +1,87 @@
+"""Device-buffer plumbing around the binding: torch supplies device memory and the stream, the
+library does all the compute.  Used by the GPU tests, the smoke check and the benchmark."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as gx
+from .inputs import PARAM_NAMES, LayerShape, bf16_bits, bf16_from_bits
+
+_FLAG_OF_PHASE = {"both": gx.GX_PHASE_ATTN | gx.GX_PHASE_MLP, "attn": gx.GX_PHASE_ATTN, "mlp": gx.GX_PHASE_MLP}
+
+
+def cfg_of(shape: LayerShape, phase="both", row_bias_attn=True, row_bias_mlp=True, accumulate=False,
+           recompute=False):
+    flags = _FLAG_OF_PHASE[phase]
+    flags |= gx.GX_ROW_BIAS_ATTN if row_bias_attn else 0
+    flags |= gx.GX_ROW_BIAS_MLP if row_bias_mlp else 0
+    flags |= gx.GX_ACCUM_WGRAD if accumulate else 0
+    flags |= gx.GX_RECOMPUTE if recompute else 0
+    return gx.make_cfg(shape.hidden, shape.heads, shape.ffn, shape.tp_attn, shape.tp_ffn, shape.tp_rank, shape.seq,
+                       shape.micro_batch, gx.GX_BF16 if shape.dtype == "bf16" else gx.GX_F32, flags, shape.ln_eps)
+
+
+def to_device(a, dtype, device="cuda:0"):
+    """fp32 NumPy array (already holding storage-representable values) -> device tensor."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if dtype == "bf16":
+        t = torch.from_numpy(bf16_bits(a).view(np.int16)).to(device)
+        return t.view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)
+
+
+def to_host(t):
+    """Device tensor (fp32 or bf16) -> fp32 NumPy array, exactly."""
+    if t.dtype == torch.bfloat16:
+        return bf16_from_bits(t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)).reshape(t.shape)
+    return t.detach().cpu().numpy()
+
+
+class DeviceLayer:
+    """One rank's share of one block on the GPU: owns parameter, gradient, saved-activation and
+    workspace buffers and forwards calls to gx_layer_fwd / gx_layer_bwd."""
+
+    def __init__(self, shape: LayerShape, params, device="cuda:0"):
+        gx.lib()                                   # fail loudly if the library is not built
+        self.shape = shape
+        self.device = device
+        self.tdtype = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+        self.params = {n: to_device(params[n], shape.dtype, device) for n in PARAM_NAMES}
+        self.grads = {n: torch.zeros(self.params[n].shape, dtype=torch.float32, device=device) for n in PARAM_NAMES}
+        self._bufs = {}
+
+    def _buf(self, key, nbytes):
+        b = self._bufs.get(key)
+        if b is None or b.numel() < nbytes:
+            b = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
+            self._bufs[key] = b
+        return b
+
+    def empty_act(self):
+        return torch.empty((self.shape.tokens, self.shape.hidden), dtype=self.tdtype, device=self.device)
+
+    def forward(self, x, phase="both", row_bias_attn=True, row_bias_mlp=True, want_partials=False, saved_key="saved",
+                out=None):
+        cfg = cfg_of(self.shape, phase, row_bias_attn, row_bias_mlp)
+        saved = self._buf(saved_key, gx.layer_saved_bytes(cfg))
+        y = p_attn = p_mlp = None
+        if phase == "both":
+            y = out if out is not None else self.empty_act()
+            if want_partials:
+                p_attn, p_mlp = self.empty_act(), self.empty_act()
+        elif phase == "attn":
+            p_attn = out if out is not None else self.empty_act()
+        else:
+            p_mlp = out if out is not None else self.empty_act()
+        gx.layer_fwd(cfg, self.params, x, y, p_attn, p_mlp, saved, None, torch.cuda.current_stream().cuda_stream)
+        return dict(y=y, p_attn=p_attn, p_mlp=p_mlp)
+
+    def backward(self, x, dy, phase="both", row_bias_attn=True, row_bias_mlp=True, accumulate=False, recompute=False,
+                 saved_key="saved", out=None):
+        cfg = cfg_of(self.shape, phase, row_bias_attn, row_bias_mlp, accumulate, recompute)
+        ws = self._buf("work", gx.layer_workspace_bytes(cfg, True))
+        saved = None if recompute else self._bufs[saved_key]
+        dx = out if out is not None else self.empty_act()
+        gx.layer_bwd(cfg, self.params, x, dy, dx, self.grads, saved, ws, torch.cuda.current_stream().cuda_stream)
+        return dx

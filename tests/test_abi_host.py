@@ -1,0 +1,82 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every declared
+symbol, and validates configurations and sizes as the header documents."""
+import os
+import re
+
+import pytest
+
+from paper_2504_03662_amd import binding as gx
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(gx.LIB_PATH):
+        from paper_2504_03662_amd.build import build
+        build(verbose=False)
+    return gx.lib()
+
+
+def test_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "gx.h")).read()
+    declared = set(re.findall(r"\b(gx_[a-z_]+)\s*\(", header))
+    assert declared == set(gx.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert gx.version().startswith("gx ")
+    assert gx.status_str(0) == "ok" and "NULL" in gx.status_str(1)
+
+
+def _cfg(**kw):
+    d = dict(hidden=4096, heads=32, ffn=16384, tp_attn=4, tp_ffn=4, tp_rank=0, seq=2048, micro_batch=2,
+             dtype=gx.GX_BF16, flags=gx.GX_PHASE_ATTN | gx.GX_PHASE_MLP)
+    d.update(kw)
+    return gx.make_cfg(**d)
+
+
+def test_validate_accepts_the_graded_workloads(lib):
+    from paper_2504_03662_amd.inputs import WORKLOADS
+    from paper_2504_03662_amd.runtime import cfg_of
+    for name, (shape, _, _) in WORKLOADS.items():
+        assert gx.layer_validate(cfg_of(shape)) == gx.GX_OK, name
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(hidden=0), 2), (dict(seq=-1), 2), (dict(dtype=7), 4), (dict(flags=0), 6), (dict(flags=3 | 1024), 6),
+    (dict(heads=33), 3), (dict(tp_attn=3), 3), (dict(ffn=16385), 3), (dict(tp_rank=4), 2),
+    (dict(hidden=2048, heads=32), 2),                 # bf16 head dim 64 is not supported
+    (dict(hidden=16384, heads=128), 2),               # beyond the LayerNorm kernels' width
+    (dict(dtype=gx.GX_F32, hidden=256, heads=4, ffn=1022, tp_attn=1, tp_ffn=1), 3),
+    (dict(micro_batch=128), 2),                       # activation tensor beyond 2 GiB
+])
+def test_validate_rejects(lib, kw, status):
+    assert gx.layer_validate(_cfg(**kw)) == status
+
+
+def test_size_queries(lib):
+    c = _cfg()
+    T, H, Hl, Fl, nl, S, B = 4096, 4096, 1024, 4096, 8, 2048, 2
+    saved = gx.layer_saved_bytes(c)
+    expect = 4 * T * 4 + B * nl * S * 4 + 2 * (T * H * 3 + T * 3 * Hl + T * Hl + 2 * T * Fl)
+    assert saved == expect                              # every piece is already a multiple of 256
+    assert gx.layer_workspace_bytes(c, 0) == 0
+    w = gx.layer_workspace_bytes(c, 1)
+    assert w > 2 * (2 * T * H + T * Fl + T * Hl + T * 3 * Hl)
+    c2 = _cfg(flags=3 | gx.GX_RECOMPUTE)
+    assert gx.layer_workspace_bytes(c2, 1) == w + saved
+    assert gx.layer_saved_bytes(_cfg(flags=0)) == 0
+    a = gx.layer_saved_bytes(_cfg(flags=gx.GX_PHASE_ATTN))
+    m = gx.layer_saved_bytes(_cfg(flags=gx.GX_PHASE_MLP))
+    assert a + m + 2 * T * H == saved                   # h1 is kept only when both halves run
+
+
+def test_entry_points_check_pointers_before_touching_the_gpu(lib):
+    c = _cfg()
+    assert gx.layer_fwd(c, {}, None, None, None, None, None, None, check=False) == 1       # NULL x
+    assert gx.layer_fwd(c, {}, 4096, 4096, None, None, 4096, None, check=False) == 1       # NULL params
+    ptrs = {n: 4096 for n in gx.PARAM_NAMES}
+    assert gx.layer_fwd(c, ptrs, 4096 + 4, 4096, None, None, 4096, None, check=False) == 5  # misaligned x
+    assert gx.layer_bwd(c, ptrs, 4096, 4096, 4096, {}, 4096, 4096, check=False) == 1        # NULL grads
+    with pytest.raises(gx.GxError):
+        gx.layer_fwd(_cfg(flags=0), ptrs, 4096, 4096, None, None, 4096, None)

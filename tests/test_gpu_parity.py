@@ -1,0 +1,171 @@
+"""GPU parity: the HIP library against the fp64 CPU oracle, element by element, on seeded
+inputs, through the C ABI.  Tolerances: max relative error 1e-4 (fp32) and 2e-2 (bf16), taken
+per tensor as max|diff| / max|ref| and as the relative L2 error."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer as O
+from paper_2504_03662_amd import inputs as I
+from paper_2504_03662_amd.runtime import DeviceLayer, to_device, to_host
+from parity import TOL, check, compare, run_both
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(shape, case, random_affine=True):
+    full = I.full_params(shape.with_(tp_attn=1, tp_ffn=1), case=case, random_affine=random_affine)
+    params = I.shard_params(shape, full)
+    x, dy = I.activations(shape, case=case)
+    return params, x, dy
+
+
+# fp32: the graded small configuration and ragged / sharded variants -----------------------------
+
+def test_c1_fp32_block():
+    shape, _, _ = I.WORKLOADS["C1"]
+    params = I.rank_params(shape, case=1)
+    x, dy = I.activations(shape, case=1)
+    gpu, ref, _ = run_both(shape, params, x, dy, want_partials=True)
+    compare(gpu, ref, TOL["f32"], want_partials=True)
+
+
+@pytest.mark.parametrize("phase", ["both", "attn", "mlp"])
+@pytest.mark.parametrize("a,f,rank", [(1, 1, 0), (3, 2, 1)])
+def test_fp32_ragged_shapes_and_phases(phase, a, f, rank):
+    # hidden 192 = 3 heads x 64, seq 100 (ragged against every tile), batch 3, odd FFN split
+    shape = I.LayerShape(192, 3, 328, a, f, rank, 100, 3, "f32")
+    params, x, dy = _case(shape, 20 + a)
+    rb = (rank == 0)
+    gpu, ref, _ = run_both(shape, params, x, dy, phase, rb, not rb)
+    compare(gpu, ref, TOL["f32"], phase)
+
+
+def test_fp32_head_dim_32_and_128():
+    for heads, case in ((8, 31), (2, 32)):
+        shape = I.LayerShape(256, heads, 512, 1, 1, 0, 70, 2, "f32")
+        params, x, dy = _case(shape, case)
+        gpu, ref, _ = run_both(shape, params, x, dy)
+        compare(gpu, ref, TOL["f32"])
+
+
+# bf16: tile-spanning, ragged, sharded -----------------------------------------------------------
+
+@pytest.mark.parametrize("phase", ["both", "attn", "mlp"])
+@pytest.mark.parametrize("a,f,rank,seq,batch", [(1, 1, 0, 200, 2), (2, 3, 1, 333, 1)])
+def test_bf16_ragged_shapes_and_phases(phase, a, f, rank, seq, batch):
+    # hidden 512 = 4 heads x 128, FFN 1536; T = 400 / 333 spans two 256-row tiles with a tail
+    shape = I.LayerShape(512, 4, 1536, a, f, rank, seq, batch, "bf16")
+    params, x, dy = _case(shape, 40 + a)
+    rb = (rank == 0)
+    gpu, ref, _ = run_both(shape, params, x, dy, phase, rb, not rb, want_partials=(phase == "both"))
+    compare(gpu, ref, TOL["bf16"], phase, want_partials=(phase == "both"))
+
+
+def test_bf16_multi_tile_block():
+    # 3 x 3 GEMM tiles with ragged edges, 5 query tiles per head
+    shape = I.LayerShape(640, 5, 1928, 1, 1, 0, 600, 1, "bf16")
+    params, x, dy = _case(shape, 50)
+    report = {}
+    gpu, ref, _ = run_both(shape, params, x, dy)
+    compare(gpu, ref, TOL["bf16"], report=report)
+    print({k: f"{v[0]:.2e}" for k, v in report.items()})
+
+
+def test_bf16_degenerate_sizes():
+    # one token per sample (attention is the identity on V), and a single sample of 2 tokens
+    for seq, batch, case in ((1, 5, 61), (2, 1, 62)):
+        shape = I.LayerShape(256, 2, 264, 1, 1, 0, seq, batch, "bf16")
+        params, x, dy = _case(shape, case)
+        gpu, ref, _ = run_both(shape, params, x, dy)
+        compare(gpu, ref, TOL["bf16"])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_recompute_and_accumulate_flags(dtype):
+    hidden, heads = (256, 2) if dtype == "bf16" else (128, 2)
+    shape = I.LayerShape(hidden, heads, 512, 1, 1, 0, 150, 2, dtype)
+    params, x, dy = _case(shape, 70)
+    gpu, ref, layer = run_both(shape, params, x, dy)
+    xd, dyd = to_device(x, dtype), to_device(dy, dtype)
+    # recomputation reproduces the saved-activation path bit for bit
+    for n in I.PARAM_NAMES:
+        layer.grads[n].fill_(float("nan"))
+    dx2 = layer.backward(xd, dyd, recompute=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(dx2), gpu["dx"])
+    for n in I.PARAM_NAMES:
+        assert np.array_equal(to_host(layer.grads[n]), gpu["grads"][n]), n
+    # accumulation: a second backward with the flag doubles every parameter gradient
+    layer.backward(xd, dyd, accumulate=True)
+    torch.cuda.synchronize()
+    for n in I.PARAM_NAMES:
+        check("acc d" + n, to_host(layer.grads[n]), 2.0 * ref["grads"][n], TOL[dtype])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_rank_partials_add_up_to_the_unsharded_block(dtype):
+    """Simulated ranks run one after another on the GPU; their partial sums, added on the host,
+    must reproduce the unsharded oracle block (outputs, input gradient, replicated-parameter
+    gradients), and their column-shard gradients must tile the full gradient."""
+    if dtype == "bf16":
+        base = I.LayerShape(512, 4, 1024, 1, 1, 0, 96, 2, "bf16")
+    else:
+        base = I.LayerShape(128, 4, 256, 1, 1, 0, 50, 2, "f32")
+    a, f = 2, 4
+    full = I.full_params(base, case=80, random_affine=True)
+    x, dy = I.activations(base, case=80)
+    ref = O.layer_fwd(base, full, x)
+    dx_ref, g_ref = O.layer_bwd(base, full, dy, ref["cache"])
+    tol = TOL[dtype]
+    sh = base.with_(tp_attn=a, tp_ffn=f)
+    xd = to_device(x, dtype)
+    # the harness plays the all-reduce in fp64 on the host and rounds what the next half reads
+    attn_layers, p_sum = [], np.zeros_like(ref["h1"])
+    for r in range(a):
+        L = DeviceLayer(sh.with_(tp_rank=r), I.shard_params(sh, full, rank_attn=r, rank_ffn=0))
+        p_sum += to_host(L.forward(xd, "attn", row_bias_attn=(r == 0))["p_attn"])
+        attn_layers.append(L)
+    h1 = x + p_sum
+    check("h1", h1, ref["h1"], tol)
+    h1s = I.bf16_round(h1.astype(np.float32)) if dtype == "bf16" else h1.astype(np.float32)
+    h1d, dyd = to_device(h1s, dtype), to_device(dy, dtype)
+    mlp_layers, m_sum = [], np.zeros_like(ref["y"])
+    for r in range(f):
+        L = DeviceLayer(sh.with_(tp_rank=r), I.shard_params(sh, full, rank_attn=0, rank_ffn=r))
+        m_sum += to_host(L.forward(h1d, "mlp", row_bias_mlp=(r == 0))["p_mlp"])
+        mlp_layers.append(L)
+    check("y", h1 + m_sum, ref["y"], tol)
+    dh1 = dy.astype(np.float64).copy()
+    for r, L in enumerate(mlp_layers):
+        dh1 += to_host(L.backward(h1d, dyd, "mlp", row_bias_mlp=(r == 0)))
+    dh1s = I.bf16_round(dh1.astype(np.float32)) if dtype == "bf16" else dh1.astype(np.float32)
+    dh1d = to_device(dh1s, dtype)
+    dx = dh1.copy()
+    for r, L in enumerate(attn_layers):
+        dx += to_host(L.backward(xd, dh1d, "attn", row_bias_attn=(r == 0)))
+    torch.cuda.synchronize()
+    check("dx", dx, dx_ref, tol)
+    G = lambda layers, n: [to_host(L.grads[n]).astype(np.float64) for L in layers]
+    for n in ("ln1_g", "ln1_b", "b_o"):
+        check("d" + n, sum(G(attn_layers, n)), g_ref[n], tol)
+    for n in ("ln2_g", "ln2_b", "b_fc2"):
+        check("d" + n, sum(G(mlp_layers, n)), g_ref[n], tol)
+    check("dw_o", np.concatenate(G(attn_layers, "w_o"), axis=0), g_ref["w_o"], tol)
+    check("dw_fc2", np.concatenate(G(mlp_layers, "w_fc2"), axis=0), g_ref["w_fc2"], tol)
+    check("dw_fc1", np.concatenate(G(mlp_layers, "w_fc1"), axis=1), g_ref["w_fc1"], tol)
+    check("db_fc1", np.concatenate(G(mlp_layers, "b_fc1")), g_ref["b_fc1"], tol)
+    Hl, H = sh.hidden_local, sh.hidden
+    for i in range(3):
+        cat = np.concatenate([g[:, i * Hl:(i + 1) * Hl] for g in G(attn_layers, "w_qkv")], axis=1)
+        check(f"dw_qkv[{i}]", cat, g_ref["w_qkv"][:, i * H:(i + 1) * H], tol)
+
+
+def test_bitwise_reproducible():
+    shape = I.LayerShape(512, 4, 1024, 2, 2, 0, 300, 2, "bf16")
+    params, x, dy = _case(shape, 90)
+    a, _, _ = run_both(shape, params, x, dy)
+    b, _, _ = run_both(shape, params, x, dy)
+    assert np.array_equal(a["y"], b["y"]) and np.array_equal(a["dx"], b["dx"])
+    for n in I.PARAM_NAMES:
+        assert np.array_equal(a["grads"][n], b["grads"][n]), n
