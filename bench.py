@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of one GPU's share of a transformer layer's training step (forward + backward)
+through libgx on MI355X.  Prints one JSON line.
+
+A step is one pass of the whole hot path over one batch of seeded synthetic input already
+resident in HBM: all blocks and micro-batches of the chosen workload, forward and backward.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 matrix peak (published)
+PEAK_F32_TFLOPS = 157.3
+
+
+def model_flops(sh, blocks, mbs):
+    """Model FLOPs of forward + backward: the four projections plus causal attention counted on
+    the unmasked pairs; backward is twice the forward; recomputation is not counted."""
+    T, H, Hl, Fl = sh.tokens, sh.hidden, sh.hidden_local, sh.ffn_local
+    fwd = 2.0 * T * H * 3 * Hl + 2.0 * T * Hl * H + 4.0 * T * H * Fl
+    fwd += 4.0 * sh.micro_batch * sh.local_heads * sh.head_dim * sh.seq * (sh.seq + 1) / 2.0
+    return 3.0 * fwd * blocks * mbs
+
+
+def gemm_flops_by_class(sh, accumulate):
+    """Kernel class -> list of 2*M*N*K for the GEMM launches of one layer pass (fwd + bwd)."""
+    T, H, Hl, Fl = sh.tokens, sh.hidden, sh.hidden_local, sh.ffn_local
+    f = lambda m, n, k: 2.0 * m * n * k
+    wg = 126 if accumulate else 125
+    return {101: [f(T, 3 * Hl, H)], 102: [f(T, H, Hl), f(T, H, Fl)], 103: [f(T, Fl, H)],
+            wg: [f(Fl, H, T), f(H, Fl, T), f(Hl, H, T), f(H, 3 * Hl, T)],
+            114: [f(T, Fl, H)], 110: [f(T, H, Fl), f(T, Hl, H), f(T, H, 3 * Hl)]}
+
+
+CLASS_NAMES = {1: "ln_fwd", 2: "ln_bwd", 3: "attn_fwd", 4: "attn_bwd", 5: "colsum",
+               101: "gemm_nn_bias", 102: "gemm_nn_resid", 103: "gemm_nn_gelu", 110: "gemm_nt_store",
+               114: "gemm_nt_dgelu", 125: "gemm_tn_f32", 126: "gemm_tn_f32_acc"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU's share on one GPU: run it with --gpus 1 "
+                 "(the library runs no collective; there is no multi-GPU path to time)")
+
+    import torch
+    from paper_2504_03662_amd import binding as gx
+    from paper_2504_03662_amd import inputs as I
+    from paper_2504_03662_amd.runtime import DeviceStack, one_f_one_b, to_device
+
+    gx.lib()                                         # fails loudly when the HIP library is missing
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs an MI355X: no GPU is visible")
+    shape, blocks, mbs = I.WORKLOADS[args.workload]
+    case = {"C1": 1, "C2": 2, "C3": 3, "C4": 4, "C5": 5}[args.workload]
+    plist = [I.rank_params(shape, case=case, block=k) for k in range(blocks)]
+    stack = DeviceStack(shape, plist)
+    del plist
+    acts = [I.activations(shape, case=case, micro_batch_index=m) for m in range(mbs)]
+    xs = [to_device(a[0], shape.dtype) for a in acts]
+    dys = [to_device(a[1], shape.dtype) for a in acts]
+    pipelined = mbs > 1
+    schedule = one_f_one_b(mbs, 3) if pipelined else [("F", 0), ("B", 0)]
+
+    def step():
+        seen = False
+        for kind, m in schedule:
+            if kind == "F":
+                stack.forward(xs[m], mb=m, keep_saved=not pipelined)
+            else:
+                # pipelined stage: full activation recomputation, gradients summed over micro-batches
+                stack.backward(dys[m], mb=m, recompute=pipelined, accumulate=pipelined and seen)
+                seen = True
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    flops = model_flops(shape, blocks, mbs)
+    tflops = flops / (ms * 1e-3) / 1e12
+    peak = PEAK_BF16_TFLOPS if shape.dtype == "bf16" else PEAK_F32_TFLOPS
+
+    # per-kernel-class durations from HIP events on the launch stream, same work repeated
+    gx.prof_enable(True)
+    launches_per_step = None
+    rec = []
+    for _ in range(max(1, min(args.steps, 8))):
+        step()
+        got = gx.prof_collect()
+        launches_per_step = len(got)
+        rec += got
+    gx.prof_enable(False)
+    by = {}
+    for c, t in rec:
+        by.setdefault(c, []).append(t)
+    total_ms = sum(sum(v) for v in by.values())
+    kernels = {CLASS_NAMES.get(c, str(c)): {"launches_per_step": len(v) * launches_per_step // len(rec),
+                                            "avg_ms": sum(v) / len(v), "share": sum(v) / total_ms}
+               for c, v in sorted(by.items(), key=lambda kv: -sum(kv[1]))}
+    gemm_fl = gemm_flops_by_class(shape, pipelined)
+    dom = max((c for c in by if c >= 100), key=lambda c: sum(by[c]))
+    fl = gemm_fl.get(dom) or gemm_fl.get(125 if dom == 126 else 126)     # first micro-batch overwrites
+    avg_ms = sum(by[dom]) / len(by[dom])
+    if dom in (125, 126) and pipelined:
+        both = by.get(125, []) + by.get(126, [])
+        avg_ms = sum(both) / len(both)
+    flops_per_launch = sum(fl) / len(fl)
+    achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12
+    gemm_ms = sum(sum(v) for c, v in by.items() if c >= 100)
+    gemm_tflops = sum(sum(v) for v in gemm_fl.values()) * blocks * mbs * (len(rec) / launches_per_step) \
+        / (gemm_ms * 1e-3) / 1e12 if not pipelined else None
+    roofline = {"bound": "mfma", "kernel": CLASS_NAMES.get(dom, str(dom)), "achieved": achieved, "peak": peak,
+                "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None, "avg_launch_ms": avg_ms,
+                "flops_per_launch": flops_per_launch, "all_gemms_tflops": gemm_tflops}
+
+    out = {"metric": "layer fwd+bwd TFLOP/s per GPU", "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
+           "config": {"workload": args.workload, "hidden": shape.hidden, "heads": shape.heads, "ffn": shape.ffn,
+                      "tp_attn": shape.tp_attn, "tp_ffn": shape.tp_ffn, "tp_rank": shape.tp_rank, "seq": shape.seq,
+                      "micro_batch": shape.micro_batch, "blocks": blocks, "micro_batches": mbs,
+                      "schedule": "1F1B, full recompute" if pipelined else "fwd then bwd"},
+           "frac_of_mfma_peak": tflops / peak,
+           "tokens_per_s_per_layer": shape.tokens * blocks * mbs / (ms * 1e-3),
+           "model_tflop_per_step": flops / 1e12,
+           "roofline": roofline, "kernels": kernels}
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape, case)
+    print(json.dumps(out))
+
+
+def cpu_baseline(shape, case):
+    """The fp64 NumPy oracle, as it stands, timed on the host on a bounded sample of the same
+    workload: one block, forward + backward, on the first sample's first 1024 tokens."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import layer as O
+    from paper_2504_03662_amd import inputs as I
+
+    seq = min(shape.seq, 1024)
+    sample = shape.with_(seq=seq, micro_batch=1)
+    params = I.rank_params(shape, case=case, block=0)
+    x, dy = I.activations(sample, case=case)
+    t0 = time.perf_counter()
+    fwd = O.layer_fwd(sample, params, x)
+    O.layer_bwd(sample, params, dy, fwd["cache"])
+    dt = time.perf_counter() - t0
+    fl = O.model_flops(sample)
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"one block of the same shard shape at seq {seq}, micro-batch 1, fwd+bwd once, "
+                      f"fp64 NumPy ({fl / 1e9:.0f} GFLOP in {dt:.1f} s)",
+            "seconds": dt, "host_cpus": os.cpu_count()}
+
+
+if __name__ == "__main__":
+    main()

@@ -38,7 +38,8 @@
  *   - Activations and parameters have the element type cfg->dtype (fp32, or bf16 with fp32
  *     accumulation); parameter gradients are always fp32.
  *   - Calls only enqueue work on `hip_stream` (a hipStream_t, or NULL for the default stream); they
- *     never allocate, free or synchronise, and results are bitwise reproducible run to run.
+ *     never allocate, free or synchronise, and results are bitwise reproducible run to run.  The
+ *     only process-global state is the optional timing record of gx_prof_*.
  *   - Errors are returned as gx_status; nothing is thrown across the boundary.  Configuration and
  *     pointer checks happen before anything is enqueued.
  */
@@ -130,6 +131,26 @@ gx_status gx_layer_fwd(const gx_layer_cfg* cfg, const gx_params* params, const v
  * alias x or dy. */
 gx_status gx_layer_bwd(const gx_layer_cfg* cfg, const gx_params* params, const void* x, const void* dy, void* dx,
                        const gx_grads* grads, const void* saved, void* workspace, void* hip_stream);
+
+/* Optional per-launch timing, for benchmarks and cost tables (the paper's section 3 "Profilers"
+ * feed per-layer costs to the strategy selector; this is the per-kernel source of such costs).
+ * While enabled, every kernel launch site inside gx_layer_fwd / gx_layer_bwd is bracketed by a
+ * pair of HIP events on the call's stream and tagged with a kernel class:
+ *   GX_KC_LN_FWD, GX_KC_LN_BWD (incl. its two finishing sums), GX_KC_ATTN_FWD, GX_KC_ATTN_BWD (its
+ *   three kernels together), GX_KC_COLSUM (both stages), and GX_KC_GEMM + 10 * layout + epilogue
+ *   with layout 0 = A[M,K] B[K,N], 1 = A[M,K] B[N,K], 2 = A[K,M] B[K,N] and epilogue 0 = store,
+ *   1 = +bias, 2 = +bias +residual, 3 = +bias then GELU, 4 = times GELU', 5 = fp32 store,
+ *   6 = fp32 accumulate.
+ * gx_prof_enable(1) creates the events on first use (the only allocation the library ever makes)
+ * and clears the record; gx_prof_enable(0) stops recording.  gx_prof_collect waits for the
+ * recorded events, writes up to `capacity` (class, milliseconds) pairs to HOST arrays in launch
+ * order, clears the record and returns the count (-1 on a HIP error).  At most 8192 launches are
+ * recorded between collects; later ones are silently not timed.  Process-global state, not
+ * thread-safe; leave it off in production loops (the event records perturb timing slightly). */
+enum { GX_KC_LN_FWD = 1, GX_KC_LN_BWD = 2, GX_KC_ATTN_FWD = 3, GX_KC_ATTN_BWD = 4, GX_KC_COLSUM = 5,
+       GX_KC_GEMM = 100 };
+gx_status gx_prof_enable(int on);
+int gx_prof_collect(int* kernel_class, float* ms, int capacity);
 
 /* Static strings; never NULL. */
 const char* gx_status_str(gx_status s);

@@ -156,8 +156,54 @@ gx_status check_arch() {
     if ((expr) != hipSuccess) return GX_ERR_LAUNCH; \
   } while (0)
 
+// Optional per-kernel-class timing: when enabled, every launch site is bracketed by a pair of
+// HIP events on the caller's stream.  Process-global, not thread-safe, off by default.
+constexpr int PROF_MAX = 8192;
+struct Prof {
+  bool on = false;
+  int n = 0;
+  hipEvent_t* ev = nullptr;      // 2 * PROF_MAX events, created on first enable
+  int cls[PROF_MAX];
+} g_prof;
+
+struct ProfScope {
+  hipStream_t st;
+  int slot;
+  ProfScope(int cls, hipStream_t s) : st(s), slot(-1) {
+    if (g_prof.on && g_prof.n < PROF_MAX) {
+      slot = g_prof.n++;
+      g_prof.cls[slot] = cls;
+      (void)hipEventRecord(g_prof.ev[2 * slot], st);
+    }
+  }
+  ~ProfScope() {
+    if (slot >= 0) (void)hipEventRecord(g_prof.ev[2 * slot + 1], st);
+  }
+};
+
+int gemm_class(Layout lay, Epilogue epi) { return GX_KC_GEMM + 10 * (int)lay + (int)epi; }
+
 hipError_t gemm(const Dims& d, Layout lay, Epilogue epi, const GemmArgs& g, hipStream_t s) {
+  ProfScope ps(gemm_class(lay, epi), s);
   return d.bf ? gemm_bf16(lay, epi, g, s) : gemm_f32(lay, epi, g, s);
+}
+
+hipError_t colsum_p(bool bf, const void* a, int rows, int cols, float* part, float* out, bool acc, hipStream_t s) {
+  ProfScope ps(GX_KC_COLSUM, s);
+  return colsum(bf, a, rows, cols, cols, part, out, acc, s);
+}
+
+// LayerNorm backward plus the finishing sums of its two parameter gradients
+hipError_t ln_bwd_p(bool bf, const void* dy, const void* x, const void* g, const float* mean, const float* rstd,
+                    const void* resid, void* dx, float* part, int rows, int cols, float* dg, float* db, bool acc,
+                    hipStream_t s) {
+  ProfScope ps(GX_KC_LN_BWD, s);
+  hipError_t e = ln_bwd(bf, dy, x, g, mean, rstd, resid, dx, part, rows, cols, s);
+  if (e != hipSuccess) return e;
+  const int nb = ln_bwd_blocks(rows);
+  e = colsum_finish(part, nb, cols, dg, acc, s);
+  if (e != hipSuccess) return e;
+  return colsum_finish(part + (size_t)nb * cols, nb, cols, db, acc, s);
 }
 
 GemmArgs gargs(const void* A, const void* B, void* C, long M, long N, long K, long lda, long ldb, long ldc) {
@@ -182,7 +228,8 @@ gx_status run_fwd(const gx_layer_cfg& c, const gx_params& p, const void* x, void
   const bool attn = c.flags & GX_PHASE_ATTN, mlp = c.flags & GX_PHASE_MLP;
   const void* h1 = x;
   if (attn) {
-    GX_TRY(ln_fwd(d.bf, x, p.ln1_g, p.ln1_b, sv.y1, sv.mean1, sv.rstd1, (int)d.T, (int)d.H, c.ln_eps, st));
+    { ProfScope ps(GX_KC_LN_FWD, st);
+    GX_TRY(ln_fwd(d.bf, x, p.ln1_g, p.ln1_b, sv.y1, sv.mean1, sv.rstd1, (int)d.T, (int)d.H, c.ln_eps, st)); }
     GemmArgs g = gargs(sv.y1, p.w_qkv, sv.qkv, d.T, 3 * d.Hl, d.H, d.H, 3 * d.Hl, 3 * d.Hl);
     g.bias = p.b_qkv;
     GX_TRY(gemm(d, LAY_NN, EPI_BIAS, g, st));
@@ -190,7 +237,8 @@ gx_status run_fwd(const gx_layer_cfg& c, const gx_params& p, const void* x, void
     memset(&a, 0, sizeof(a));
     a.qkv = sv.qkv; a.ctx = sv.ctx; a.lse = sv.lse;
     a.B = (int)d.B; a.S = (int)d.S; a.nl = (int)d.nl; a.dh = (int)d.dh;
-    GX_TRY(d.bf ? attn_fwd_bf16(a, st) : attn_fwd_f32(a, st));
+    { ProfScope ps(GX_KC_ATTN_FWD, st);
+    GX_TRY(d.bf ? attn_fwd_bf16(a, st) : attn_fwd_f32(a, st)); }
     if (mlp) {
       GemmArgs o = gargs(sv.ctx, p.w_o, sv.h1, d.T, d.H, d.Hl, d.Hl, d.H, d.H);
       o.bias = (c.flags & GX_ROW_BIAS_ATTN) ? p.b_o : nullptr;
@@ -205,7 +253,8 @@ gx_status run_fwd(const gx_layer_cfg& c, const gx_params& p, const void* x, void
     }
   }
   if (mlp) {
-    GX_TRY(ln_fwd(d.bf, h1, p.ln2_g, p.ln2_b, sv.y2, sv.mean2, sv.rstd2, (int)d.T, (int)d.H, c.ln_eps, st));
+    { ProfScope ps(GX_KC_LN_FWD, st);
+    GX_TRY(ln_fwd(d.bf, h1, p.ln2_g, p.ln2_b, sv.y2, sv.mean2, sv.rstd2, (int)d.T, (int)d.H, c.ln_eps, st)); }
     GemmArgs f1 = gargs(sv.y2, p.w_fc1, sv.z, d.T, d.Fl, d.H, d.H, d.Fl, d.Fl);
     f1.bias = p.b_fc1;
     f1.aux = sv.act;
@@ -229,7 +278,7 @@ gx_status bias_grad(const Dims& d, const gx_layer_cfg& c, bool enabled, const vo
                     float* out, hipStream_t st) {
   const bool acc = c.flags & GX_ACCUM_WGRAD;
   if (enabled) {
-    GX_TRY(colsum(d.bf, src, (int)d.T, (int)cols, (int)cols, part, out, acc, st));
+    GX_TRY(colsum_p(d.bf, src, (int)d.T, (int)cols, part, out, acc, st));
   } else if (!acc) {
     hipLaunchKernelGGL(fill_zero_kernel, dim3(cdiv(cols, 256)), dim3(256), 0, st, out, (int)cols);
     GX_TRY(hipGetLastError());
@@ -254,7 +303,7 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     GemmArgs dz = gargs(dy, p.w_fc2, w.dz, d.T, d.Fl, d.H, d.H, d.H, d.Fl);
     dz.z = sv.z;
     GX_TRY(gemm(d, LAY_NT, EPI_DGELU, dz, st));
-    GX_TRY(colsum(d.bf, w.dz, (int)d.T, (int)d.Fl, (int)d.Fl, w.part, gr.b_fc1, acc, st));
+    GX_TRY(colsum_p(d.bf, w.dz, (int)d.T, (int)d.Fl, w.part, gr.b_fc1, acc, st));
     // column-parallel FC1
     GemmArgs w1 = gargs(sv.y2, w.dz, gr.w_fc1, d.H, d.Fl, d.T, d.H, d.Fl, d.Fl);
     GX_TRY(gemm(d, LAY_TN, wg, w1, st));
@@ -262,11 +311,8 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     GX_TRY(gemm(d, LAY_NT, EPI_STORE, dy2, st));
     // LayerNorm 2; with both phases the residual branch adds dy
     void* out = attn ? w.dh1 : dx;
-    GX_TRY(ln_bwd(d.bf, w.dyn, h1, p.ln2_g, sv.mean2, sv.rstd2, attn ? dy : nullptr, out, w.part, (int)d.T, (int)d.H,
-                  st));
-    const int nb = ln_bwd_blocks((int)d.T);
-    GX_TRY(colsum_finish(w.part, nb, (int)d.H, gr.ln2_g, acc, st));
-    GX_TRY(colsum_finish(w.part + (size_t)nb * d.H, nb, (int)d.H, gr.ln2_b, acc, st));
+    GX_TRY(ln_bwd_p(d.bf, w.dyn, h1, p.ln2_g, sv.mean2, sv.rstd2, attn ? dy : nullptr, out, w.part, (int)d.T,
+                    (int)d.H, gr.ln2_g, gr.ln2_b, acc, st));
     dcur = w.dh1;
   }
   if (attn) {
@@ -281,18 +327,16 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     memset(&a, 0, sizeof(a));
     a.qkv = sv.qkv; a.ctx = sv.ctx; a.lse = sv.lse; a.dctx = w.dctx; a.dqkv = w.dqkv; a.dsum = w.dsum;
     a.B = (int)d.B; a.S = (int)d.S; a.nl = (int)d.nl; a.dh = (int)d.dh;
-    GX_TRY(d.bf ? attn_bwd_bf16(a, st) : attn_bwd_f32(a, st));
+    { ProfScope ps(GX_KC_ATTN_BWD, st);
+    GX_TRY(d.bf ? attn_bwd_bf16(a, st) : attn_bwd_f32(a, st)); }
     // column-parallel QKV
-    GX_TRY(colsum(d.bf, w.dqkv, (int)d.T, (int)(3 * d.Hl), (int)(3 * d.Hl), w.part, gr.b_qkv, acc, st));
+    GX_TRY(colsum_p(d.bf, w.dqkv, (int)d.T, (int)(3 * d.Hl), w.part, gr.b_qkv, acc, st));
     GemmArgs wq = gargs(sv.y1, w.dqkv, gr.w_qkv, d.H, 3 * d.Hl, d.T, d.H, 3 * d.Hl, 3 * d.Hl);
     GX_TRY(gemm(d, LAY_TN, wg, wq, st));
     GemmArgs dy1 = gargs(w.dqkv, p.w_qkv, w.dyn, d.T, d.H, 3 * d.Hl, 3 * d.Hl, 3 * d.Hl, d.H);
     GX_TRY(gemm(d, LAY_NT, EPI_STORE, dy1, st));
-    GX_TRY(ln_bwd(d.bf, w.dyn, x, p.ln1_g, sv.mean1, sv.rstd1, mlp ? dcur : nullptr, dx, w.part, (int)d.T, (int)d.H,
-                  st));
-    const int nb = ln_bwd_blocks((int)d.T);
-    GX_TRY(colsum_finish(w.part, nb, (int)d.H, gr.ln1_g, acc, st));
-    GX_TRY(colsum_finish(w.part + (size_t)nb * d.H, nb, (int)d.H, gr.ln1_b, acc, st));
+    GX_TRY(ln_bwd_p(d.bf, w.dyn, x, p.ln1_g, sv.mean1, sv.rstd1, mlp ? dcur : nullptr, dx, w.part, (int)d.T,
+                    (int)d.H, gr.ln1_g, gr.ln1_b, acc, st));
   }
   return GX_OK;
 }
@@ -407,5 +451,29 @@ const char* gx_status_str(gx_status s) {
 }
 
 const char* gx_version(void) { return "gx 0.1 (gfx950)"; }
+
+gx_status gx_prof_enable(int on) {
+  if (on && !g_prof.ev) {
+    g_prof.ev = new hipEvent_t[2 * PROF_MAX];
+    for (int i = 0; i < 2 * PROF_MAX; i++)
+      if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) return GX_ERR_LAUNCH;
+  }
+  g_prof.on = on != 0;
+  g_prof.n = 0;
+  return GX_OK;
+}
+
+int gx_prof_collect(int* kernel_class, float* ms, int capacity) {
+  const int n = g_prof.n < capacity ? g_prof.n : capacity;
+  for (int i = 0; i < n; i++) {
+    if (hipEventSynchronize(g_prof.ev[2 * i + 1]) != hipSuccess) return -1;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]) != hipSuccess) return -1;
+    kernel_class[i] = g_prof.cls[i];
+    ms[i] = t;
+  }
+  g_prof.n = 0;
+  return n;
+}
 
 }  // extern "C"

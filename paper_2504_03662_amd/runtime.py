@@ -85,3 +85,51 @@ class DeviceLayer:
         dx = out if out is not None else self.empty_act()
         gx.layer_bwd(cfg, self.params, x, dy, dx, self.grads, saved, ws, torch.cuda.current_stream().cuda_stream)
         return dx
+
+
+class DeviceStack:
+    """Consecutive blocks of one pipeline stage on the GPU.  Each block keeps its own saved
+    activations per in-flight micro-batch, or, with recomputation, only its input."""
+
+    def __init__(self, shape: LayerShape, params_list, device="cuda:0"):
+        self.shape = shape
+        self.layers = [DeviceLayer(shape, p, device) for p in params_list]
+        self.inputs = {}          # micro-batch id -> per-block input tensors
+
+    def forward(self, x, mb=0, keep_saved=True):
+        ins = self.inputs.get(mb)
+        if ins is None:
+            ins = [None] + [self.layers[0].empty_act() for _ in self.layers[1:]] + [self.layers[0].empty_act()]
+            self.inputs[mb] = ins
+        ins[0] = x
+        for k, layer in enumerate(self.layers):
+            layer.forward(ins[k], saved_key=("saved", mb) if keep_saved else "saved_scratch", out=ins[k + 1])
+        return ins[-1]
+
+    def backward(self, dy, mb=0, recompute=False, accumulate=False):
+        ins = self.inputs[mb]
+        cur = dy
+        for k in reversed(range(len(self.layers))):
+            layer = self.layers[k]
+            dx = layer._bufs.get(("dx", k % 2))
+            if dx is None:
+                dx = layer._bufs[("dx", k % 2)] = layer.empty_act()
+            cur = layer.backward(ins[k], cur, recompute=recompute, accumulate=accumulate, saved_key=("saved", mb),
+                                 out=dx)
+        return cur
+
+
+def one_f_one_b(n_micro, depth_ahead):
+    """Order of forward (F, m) and backward (B, m) passes of one pipeline stage that runs
+    `depth_ahead` forward passes before its first backward pass, then alternates."""
+    order, f, b = [], 0, 0
+    while f < min(depth_ahead, n_micro):
+        order.append(("F", f))
+        f += 1
+    while b < n_micro:
+        if f < n_micro:
+            order.append(("F", f))
+            f += 1
+        order.append(("B", b))
+        b += 1
+    return order
