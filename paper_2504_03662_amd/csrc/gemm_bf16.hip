@@ -158,50 +158,79 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
       for (int mi = 0; mi < 4; mi++)
 #pragma unroll
         for (int ni = 0; ni < 2; ni++)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ni], af[mi], acc[mi][ni], 0, 0, 0);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
   }
 
-  // epilogue: accumulator register v of lane l is C[8*(v/4) + 4*(l/32) + v%4][l%32] of its tile
+  // epilogue.  The MFMAs were issued with the B fragment as the row operand, so accumulator
+  // register v of lane l holds C[m = tile row l%32][n = 8*(v/4) + 4*(l/32) + v%4]: runs of 4
+  // consecutive columns.  Each wavefront passes its 128 x 64 block through a private 16 KB LDS
+  // region, 32 rows at a time (row stride 68 floats keeps the 16 B writes conflict-free), and
+  // reads it back so that 16 lanes cover one 64-column row: every global access of the epilogue
+  // (C, residual, pre-activation, second output) is a 16 B or 8 B vector in fully used lines.
   const bf16* bias = static_cast<const bf16*>(g.bias);
   const bf16* resid = static_cast<const bf16*>(g.resid);
   const bf16* zin = static_cast<const bf16*>(g.z);
   bf16* aux = static_cast<bf16*>(g.aux);
+  constexpr int EPAD = 68;
+  float* stage = reinterpret_cast<float*>(smem + wave * 16384);
+  const int ecol = n0 + wn * 64 + 4 * (lane & 15);
+  float bv[4] = {0.f, 0.f, 0.f, 0.f};
+  if ((EPI == EPI_BIAS || EPI == EPI_RESID || EPI == EPI_GELU) && bias && ecol < g.N) {
+    const bf16x4 b4 = *reinterpret_cast<const bf16x4*>(bias + ecol);
 #pragma unroll
-  for (int ni = 0; ni < 2; ni++) {
-    const int col = n0 + wn * 64 + ni * 32 + l32;
-    if (col >= g.N) continue;
-    float bv = 0.f;
-    if ((EPI == EPI_BIAS || EPI == EPI_RESID || EPI == EPI_GELU) && bias) bv = (float)bias[col];
+    for (int e = 0; e < 4; e++) bv[e] = (float)b4[e];
+  }
 #pragma unroll
-    for (int mi = 0; mi < 4; mi++) {
+  for (int mi = 0; mi < 4; mi++) {
 #pragma unroll
-      for (int v = 0; v < 16; v++) {
-        const int row = m0 + wm * 128 + mi * 32 + 8 * (v >> 2) + 4 * grp + (v & 3);
-        if (row >= g.M) continue;
-        const size_t idx = (size_t)row * g.ldc + col;
-        float x = acc[mi][ni][v];
-        if (EPI == EPI_STORE) {
-          static_cast<bf16*>(g.C)[idx] = (bf16)x;
-        } else if (EPI == EPI_BIAS) {
-          static_cast<bf16*>(g.C)[idx] = (bf16)(x + bv);
-        } else if (EPI == EPI_RESID) {
-          x += bv;
-          if (aux) aux[idx] = (bf16)x;
-          static_cast<bf16*>(g.C)[idx] = (bf16)(x + (float)resid[idx]);
+    for (int ni = 0; ni < 2; ni++)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; q4++) {
+        const f32x16& a = acc[mi][ni];
+        *reinterpret_cast<f32x4*>(stage + l32 * EPAD + ni * 32 + 8 * q4 + 4 * grp) =
+            f32x4{a[4 * q4], a[4 * q4 + 1], a[4 * q4 + 2], a[4 * q4 + 3]};
+      }
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+      const int r = 4 * j + (lane >> 4);
+      const f32x4 xv = *reinterpret_cast<const f32x4*>(stage + r * EPAD + 4 * (lane & 15));
+      const int row = m0 + wm * 128 + mi * 32 + r;
+      if (row >= g.M || ecol >= g.N) continue;            // N is a multiple of 4: whole run in or out
+      const size_t idx = (size_t)row * g.ldc + ecol;
+      float x[4] = {xv[0] + bv[0], xv[1] + bv[1], xv[2] + bv[2], xv[3] + bv[3]};
+      if (EPI == EPI_F32) {
+        *reinterpret_cast<f32x4*>(static_cast<float*>(g.C) + idx) = f32x4{x[0], x[1], x[2], x[3]};
+      } else if (EPI == EPI_F32_ACC) {
+        f32x4* cp = reinterpret_cast<f32x4*>(static_cast<float*>(g.C) + idx);
+        const f32x4 old = *cp;
+        *cp = f32x4{old[0] + x[0], old[1] + x[1], old[2] + x[2], old[3] + x[3]};
+      } else {
+        bf16x4 o;
+        if (EPI == EPI_RESID) {
+          if (aux) {
+#pragma unroll
+            for (int e = 0; e < 4; e++) o[e] = (bf16)x[e];
+            *reinterpret_cast<bf16x4*>(aux + idx) = o;
+          }
+          const bf16x4 rv = *reinterpret_cast<const bf16x4*>(resid + idx);
+#pragma unroll
+          for (int e = 0; e < 4; e++) x[e] += (float)rv[e];
         } else if (EPI == EPI_GELU) {
-          x += bv;
-          static_cast<bf16*>(g.C)[idx] = (bf16)x;
-          aux[idx] = (bf16)gelu_f(x);
+          bf16x4 ga;
+#pragma unroll
+          for (int e = 0; e < 4; e++) ga[e] = (bf16)gelu_fast(x[e]);
+          *reinterpret_cast<bf16x4*>(aux + idx) = ga;
         } else if (EPI == EPI_DGELU) {
-          static_cast<bf16*>(g.C)[idx] = (bf16)(x * gelu_grad_f((float)zin[idx]));
-        } else if (EPI == EPI_F32) {
-          static_cast<float*>(g.C)[idx] = x;
-        } else {
-          static_cast<float*>(g.C)[idx] += x;
+          const bf16x4 zv = *reinterpret_cast<const bf16x4*>(zin + idx);
+#pragma unroll
+          for (int e = 0; e < 4; e++) x[e] *= gelu_grad_fast((float)zv[e]);
         }
+#pragma unroll
+        for (int e = 0; e < 4; e++) o[e] = (bf16)x[e];
+        *reinterpret_cast<bf16x4*>(static_cast<bf16*>(g.C) + idx) = o;
       }
     }
   }
@@ -245,6 +274,8 @@ hipError_t gemm_bf16(Layout lay, Epilogue epi, const GemmArgs& g, hipStream_t s)
   if (lay != LAY_TN && (g.K & 7)) return hipErrorInvalidValue;
   if (lay == LAY_TN && (g.M & 7)) return hipErrorInvalidValue;
   if (lay != LAY_NT && (g.N & 7)) return hipErrorInvalidValue;
+  // the epilogue moves runs of 4 columns as one vector
+  if ((g.N & 3) || (g.ldc & 3) || (reinterpret_cast<uintptr_t>(g.C) & 15)) return hipErrorInvalidValue;
   if (a_rows * g.lda * 2 >= (1L << 31) || b_rows * g.ldb * 2 >= (1L << 31)) return hipErrorInvalidValue;
   if ((reinterpret_cast<uintptr_t>(g.A) | reinterpret_cast<uintptr_t>(g.B)) & 15) return hipErrorInvalidValue;
   switch (lay) {

@@ -30,6 +30,29 @@ GX_DEVINL float gelu_grad_f(float z) {
   return cdf + z * pdf;
 }
 
+// erf by Abramowitz & Stegun 7.1.26 (|error| <= 1.5e-7): one reciprocal, one exponential and a
+// degree-5 polynomial; returns erf(|x|) and exp(-x^2) so that the GELU derivative can share them.
+GX_DEVINL float erf_abs_as(float ax, float& e) {
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  e = __expf(-ax * ax);
+  return fmaf(-p * t, e, 1.0f);
+}
+// GELU and its derivative on that erf; accurate to ~2e-7 absolute, for bf16 outputs
+GX_DEVINL float gelu_fast(float z) {
+  float e;
+  const float r = erf_abs_as(fabsf(z) * 0.70710678118654752440f, e);
+  return 0.5f * z * (1.0f + copysignf(r, z));
+}
+GX_DEVINL float gelu_grad_fast(float z) {
+  float e;
+  const float r = erf_abs_as(fabsf(z) * 0.70710678118654752440f, e);
+  return fmaf(z * 0.39894228040143267794f, e, 0.5f * (1.0f + copysignf(r, z)));
+}
+
 GX_DEVINL float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
