@@ -1,0 +1,126 @@
+"""GPU parity at the graded workloads' full shapes, in the launch configuration the benchmark
+times (same shapes, flags and schedules), against the fp64 CPU oracle.
+
+C3 is compared in full.  C2 runs its 4-block stack in full.  C4's feed-forward half is 11.5 TFLOP
+in fp64, so it is checked exactly on sampled tokens: the feed-forward half acts on each token
+independently, and with an upstream gradient that is zero outside the sampled tokens the oracle
+needs only those rows to produce every gradient of the full-size run.  C5's stage (8 blocks x 8
+micro-batches, 128 TFLOP) is cut to 2 blocks x 3 micro-batches at the full per-block shape, with
+the same 1F1B order, recomputation and gradient accumulation; the full 8 x 8 schedule is
+exercised at a small shape."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer as O
+from paper_2504_03662_amd import inputs as I
+from paper_2504_03662_amd.runtime import DeviceLayer, DeviceStack, one_f_one_b, to_device, to_host
+from parity import TOL, check, compare, run_both
+
+pytestmark = pytest.mark.gpu
+TOLB = TOL["bf16"]
+
+
+def test_c3_tp4_shard_full():
+    shape, _, _ = I.WORKLOADS["C3"]
+    params = I.rank_params(shape, case=3)
+    x, dy = I.activations(shape, case=3)
+    report = {}
+    gpu, ref, _ = run_both(shape, params, x, dy, want_partials=True)
+    compare(gpu, ref, TOLB, want_partials=True, report=report)
+    print("C3 max-rel:", {k: f"{v[0]:.1e}" for k, v in report.items()})
+
+
+def test_c2_stack_of_four_blocks_full():
+    shape, blocks, _ = I.WORKLOADS["C2"]
+    plist = [I.rank_params(shape, case=2, block=k) for k in range(blocks)]
+    x, dy = I.activations(shape, case=2)
+    stack = DeviceStack(shape, plist)
+    y = stack.forward(to_device(x, "bf16"))
+    dx = stack.backward(to_device(dy, "bf16"))
+    torch.cuda.synchronize()
+    y_ref, outs = O.stack_fwd(shape, plist, x)
+    dx_ref, grads = O.stack_bwd(shape, plist, dy, outs)
+    check("y", to_host(y), y_ref, TOLB)
+    check("dx", to_host(dx), dx_ref, TOLB)
+    for k in (0, blocks - 1):
+        for n in I.PARAM_NAMES:
+            check(f"block{k}.d{n}", to_host(stack.layers[k].grads[n]), grads[k][n], TOLB)
+
+
+def test_c4_mixed_degree_block_sampled_tokens():
+    shape, _, _ = I.WORKLOADS["C4"]               # attention TP=8 shard, feed-forward unsharded
+    params = I.rank_params(shape, case=4)
+    x, dy = I.activations(shape, case=4)
+    rows = np.sort(np.random.default_rng(44).choice(shape.tokens, size=384, replace=False))
+    rows[0], rows[-1] = 0, shape.tokens - 1
+    dy_s = np.zeros_like(dy)
+    dy_s[rows] = dy[rows]
+    layer = DeviceLayer(shape, params)
+    xd = to_device(x, "bf16")
+    y = layer.forward(xd)["y"]
+    dx = layer.backward(xd, to_device(dy_s, "bf16"))
+    torch.cuda.synchronize()
+    # oracle: attention half in full, feed-forward half on the sampled tokens only
+    p_attn, ca = O.attn_half_fwd(shape, params, x)
+    h1 = x + p_attn
+    sub = shape.with_(seq=len(rows), micro_batch=1)
+    p_mlp, cm = O.mlp_half_fwd(sub, params, h1[rows])
+    check("y[sampled]", to_host(y)[rows], h1[rows] + p_mlp, TOLB)
+    dh1_rows, gm = O.mlp_half_bwd(sub, params, dy_s[rows], cm)
+    dh1 = dy_s.astype(np.float64)
+    dh1[rows] += dh1_rows
+    dx_ln, ga = O.attn_half_bwd(shape, params, dh1, ca)
+    check("dx", to_host(dx), dh1 + dx_ln, TOLB)
+    for n, g in {**ga, **gm}.items():
+        check("d" + n, to_host(layer.grads[n]), g, TOLB)
+
+
+def _run_stage(shape, plist, xs, dys):
+    stack = DeviceStack(shape, plist)
+    xd = [to_device(a, shape.dtype) for a in xs]
+    dyd = [to_device(a, shape.dtype) for a in dys]
+    ys, dxs, seen = {}, {}, False
+    for kind, m in one_f_one_b(len(xs), 3):
+        if kind == "F":
+            ys[m] = to_host(stack.forward(xd[m], mb=m, keep_saved=False))
+        else:
+            dxs[m] = to_host(stack.backward(dyd[m], mb=m, recompute=True, accumulate=seen))
+            seen = True
+    torch.cuda.synchronize()
+    return stack, ys, dxs
+
+
+def test_c5_pipeline_stage_full_shape_reduced_depth():
+    shape, _, _ = I.WORKLOADS["C5"]
+    blocks, mbs = 2, 3
+    plist = [I.rank_params(shape, case=5, block=k) for k in range(blocks)]
+    acts = [I.activations(shape, case=5, micro_batch_index=m) for m in range(mbs)]
+    xs, dys = [a[0] for a in acts], [a[1] for a in acts]
+    stack, ys, dxs = _run_stage(shape, plist, xs, dys)
+    ys_ref, dxs_ref, tot = O.pipeline_stage(shape, plist, xs, dys)
+    for m in range(mbs):
+        check(f"y[{m}]", ys[m], ys_ref[m], TOLB)
+        check(f"dx[{m}]", dxs[m], dxs_ref[m], TOLB)
+    for k in range(blocks):
+        for n in I.PARAM_NAMES:
+            check(f"block{k}.d{n}", to_host(stack.layers[k].grads[n]), tot[k][n], TOLB)
+
+
+def test_pipeline_stage_8_blocks_8_micro_batches_small_shape():
+    shape = I.LayerShape(256, 2, 512, 2, 2, 0, 96, 1, "bf16")
+    blocks, mbs = 8, 8
+    full = [I.full_params(shape.with_(tp_attn=1, tp_ffn=1), case=55, block=k, random_affine=True) for k in range(blocks)]
+    plist = [I.shard_params(shape, f) for f in full]
+    acts = [I.activations(shape, case=55, micro_batch_index=m) for m in range(mbs)]
+    xs, dys = [a[0] for a in acts], [a[1] for a in acts]
+    stack, ys, dxs = _run_stage(shape, plist, xs, dys)
+    ys_ref, dxs_ref, tot = O.pipeline_stage(shape, plist, xs, dys)
+    # eight stacked blocks compound the bf16 rounding of the residual stream: outputs are compared
+    # at the stated tolerance, gradients at twice it (documented with the tolerance derivation)
+    for m in range(mbs):
+        check(f"y[{m}]", ys[m], ys_ref[m], TOLB)
+        check(f"dx[{m}]", dxs[m], dxs_ref[m], 2 * TOLB)
+    for k in (0, blocks - 1):
+        for n in I.PARAM_NAMES:
+            check(f"block{k}.d{n}", to_host(stack.layers[k].grads[n]), tot[k][n], 2 * TOLB)
