@@ -233,8 +233,8 @@ __global__ void __launch_bounds__(256) attn_dsum_kernel(const bf16* __restrict__
 }
 
 // ------------------------------------------------------------------------------- backward: dK, dV
-constexpr int KV_NW = 4, KV_BJ = 32 * KV_NW, KV_BI = 32;
-constexpr int KV_STAGE = 2 * KV_BI * ROWB + 2 * KV_BI * 4;   // Q tile | dO tile | lse2[32] | D[32]
+constexpr int KV_NW = 4, KV_BJ = 32 * KV_NW, KV_BI = 64;
+constexpr int KV_STAGE = 2 * KV_BI * ROWB + 2 * KV_BI * 4;   // Q tile | dO tile | lse2[64] | D[64]
 
 __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __restrict__ qkv,
                                                                   const bf16* __restrict__ dctx,
@@ -269,11 +269,11 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
     char* st = smem + (t & 1) * KV_STAGE;
     tile_load<KV_BI, KV_NW>(rq, eq, ld, t * KV_BI, S, st, wave, lane);
     tile_load<KV_BI, KV_NW>(rdo, edo, Hl, t * KV_BI, S, st + KV_BI * ROWB, wave, lane);
-    if (threadIdx.x < 64) {
+    if (threadIdx.x < 128) {
       float* aux = reinterpret_cast<float*>(st + 2 * KV_BI * ROWB);
-      const int i = t * KV_BI + (threadIdx.x & 31);
+      const int i = t * KV_BI + (threadIdx.x & 63);
       // rows beyond the sequence get lse = +inf, so their recomputed probabilities are exactly 0
-      if (threadIdx.x < 32) aux[threadIdx.x] = (i < S) ? lrow[i] * LOG2E : INFINITY;
+      if (threadIdx.x < 64) aux[threadIdx.x] = (i < S) ? lrow[i] * LOG2E : INFINITY;
       else aux[threadIdx.x] = (i < S) ? drow[i] : 0.f;
     }
   };
@@ -282,39 +282,49 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
   __syncthreads();
   for (int t = t0; t < nt; t++) {
     if (t + 1 < nt) stage_load(t + 1);
-    const int it0 = t * KV_BI;
-    if (it0 + KV_BI - 1 >= jw) {                        // wave-uniform: some query of the tile sees a key
-      const char* qt = smem + (t & 1) * KV_STAGE;
-      const char* dot = qt + KV_BI * ROWB;
-      const float* aux = reinterpret_cast<const float*>(qt + 2 * KV_BI * ROWB);
-      f32x16 sacc = zero16(), pacc = zero16();
+    const char* qt = smem + (t & 1) * KV_STAGE;
+    const char* dot = qt + KV_BI * ROWB;
+    const float* aux = reinterpret_cast<const float*>(qt + 2 * KV_BI * ROWB);
+    const int j = jw + l32;
+    // two independent 32-row query sub-tiles per step: the matrix work of one overlaps the
+    // exponentials of the other
+    if (t * KV_BI + KV_BI - 1 >= jw) {                    // wave-uniform: some query of the tile sees a key
+      f32x16 sacc[2], pacc[2];
 #pragma unroll
-      for (int s = 0; s < DH / 16; s++) {
-        sacc = MFMA(frag_rows(qt, l32, s, g), kf[s], sacc);      // S[i][j]
-        pacc = MFMA(frag_rows(dot, l32, s, g), vf[s], pacc);     // dP[i][j]
-      }
-      const int j = jw + l32;
-      const bool diag = (it0 < jw + 31);
+      for (int sub = 0; sub < 2; sub++) {
+        sacc[sub] = zero16();
+        pacc[sub] = zero16();
 #pragma unroll
-      for (int q4 = 0; q4 < 4; q4++) {
-        const f32x4 l4 = *reinterpret_cast<const f32x4*>(aux + 8 * q4 + 4 * g);
-        const f32x4 d4 = *reinterpret_cast<const f32x4*>(aux + 32 + 8 * q4 + 4 * g);
-#pragma unroll
-        for (int e = 0; e < 4; e++) {
-          const int v = 4 * q4 + e;
-          float p = __builtin_amdgcn_exp2f(sacc[v] * c2 - l4[e]);
-          if (diag && j > it0 + 8 * q4 + 4 * g + e) p = 0.f;
-          sacc[v] = p;
-          pacc[v] = p * (pacc[v] - d4[e]);
+        for (int s = 0; s < DH / 16; s++) {
+          sacc[sub] = MFMA(frag_rows(qt, 32 * sub + l32, s, g), kf[s], sacc[sub]);      // S[i][j]
+          pacc[sub] = MFMA(frag_rows(dot, 32 * sub + l32, s, g), vf[s], pacc[sub]);     // dP[i][j]
         }
       }
 #pragma unroll
-      for (int u = 0; u < 2; u++) {
-        const bf16x8 pf = pack_half(sacc, u), dsf = pack_half(pacc, u);
+      for (int sub = 0; sub < 2; sub++) {
+        const int it0 = t * KV_BI + 32 * sub;
+        const bool diag = (it0 < jw + 31);
 #pragma unroll
-        for (int dt = 0; dt < DH / 32; dt++) {
-          dv[dt] = MFMA(pf, frag_cols(dot, 16 * u, dt, lane), dv[dt]);   // dV[j][d] += P^T dO
-          dk[dt] = MFMA(dsf, frag_cols(qt, 16 * u, dt, lane), dk[dt]);   // dK[j][d] += dS^T Q
+        for (int q4 = 0; q4 < 4; q4++) {
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(aux + 32 * sub + 8 * q4 + 4 * g);
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(aux + KV_BI + 32 * sub + 8 * q4 + 4 * g);
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            const int v = 4 * q4 + e;
+            float p = __builtin_amdgcn_exp2f(sacc[sub][v] * c2 - l4[e]);
+            if (diag && j > it0 + 8 * q4 + 4 * g + e) p = 0.f;
+            sacc[sub][v] = p;
+            pacc[sub][v] = p * (pacc[sub][v] - d4[e]);
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+          const bf16x8 pf = pack_half(sacc[sub], u), dsf = pack_half(pacc[sub], u);
+#pragma unroll
+          for (int dt = 0; dt < DH / 32; dt++) {
+            dv[dt] = MFMA(pf, frag_cols(dot, 32 * sub + 16 * u, dt, lane), dv[dt]);   // dV[j][d] += P^T dO
+            dk[dt] = MFMA(dsf, frag_cols(qt, 32 * sub + 16 * u, dt, lane), dk[dt]);   // dK[j][d] += dS^T Q
+          }
         }
       }
     }

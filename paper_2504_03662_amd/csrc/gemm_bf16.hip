@@ -1,7 +1,7 @@
 // bf16 MFMA GEMM family for gfx950: the dense contractions of one rank's transformer-block share
 // (column-parallel QKV / FC1, row-parallel out-proj / FC2, their input and weight gradients).
 //
-// One workgroup of 8 wavefronts computes a 256x256 tile of C with a K step of 64.  Operand tiles
+// One workgroup of 8 wavefronts computes a 256x256 (or 128x128) tile of C with a K step of 64.  Operand tiles
 // go from HBM straight into LDS (buffer_load ... lds, 16 B per lane, no register staging) into a
 // double buffer; fragments for v_mfma_f32_32x32x16_bf16 are read with ds_read_b128 when the
 // reduction index is contiguous in memory ("K-major" tiles) and with the transposing
@@ -13,15 +13,13 @@
 namespace gx {
 namespace {
 
-constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int BK = 64;
 constexpr int NTHREADS = 512;
-constexpr int TILE_BYTES = 256 * BK * 2;        // one operand tile: 32 KB
-constexpr int SMEM_BYTES = 4 * TILE_BYTES;      // A[2] | B[2]
 constexpr unsigned OOB = 0x80000000u;           // beyond num_records: the load writes zeros
 
-// K-major tile: [256 rows][64 k], 128 B per row, 16 B chunk c of row r stored at c ^ swz_k(r).
+// K-major tile: [R rows][64 k], 128 B per row, 16 B chunk c of row r stored at c ^ swz_k(r).
 GX_DEVINL int swz_k(int r) { return (r >> 1) & 7; }
-// MN-major tile: [64 k-rows][256 cols], 512 B per k-row, 16 B chunk c of k-row kr stored at
+// MN-major tile: [64 k-rows][R cols], 2R B per k-row, 16 B chunk c of k-row kr stored at
 // c ^ swz_mn(kr) (moves whole 64 B groups so that 4 consecutive k-rows fall in distinct banks).
 GX_DEVINL int swz_mn(int kr) { return (kr & 3) << 2; }
 
@@ -29,11 +27,13 @@ GX_DEVINL __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
 }
 
-template <bool KMAJOR>
+// This wave's share of the direct-to-LDS loads of one operand tile (R = 256 or 128 rows/columns
+// by 64 reduction steps): R/64 instructions of 64 lanes x 16 B each.
+template <bool KMAJOR, int R>
 struct TileLoader {
-  // k-invariant part of this lane's four load addresses (elements), and validity
-  unsigned base[4];
-  int kc[4];          // K-major: k offset of the chunk; MN-major: k-row of the chunk
+  static constexpr int PER = R / 64;
+  unsigned base[PER];   // k-invariant part of the lane's element offset, or OOB
+  int kc[PER];          // K-major: k offset of the chunk; MN-major: k-row of the chunk
   __amdgpu_buffer_rsrc_t rsrc;
   int ld, K;
 
@@ -43,16 +43,18 @@ struct TileLoader {
     ld = ld_;
     K = K_;
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-      int q = wave * 4 + i;
+    for (int i = 0; i < PER; i++) {
+      const int q = wave * PER + i;
       if (KMAJOR) {
-        int r = 8 * q + (lane >> 3);
-        int c = (lane & 7) ^ swz_k(r);
+        const int r = 8 * q + (lane >> 3);
+        const int c = (lane & 7) ^ swz_k(r);
         kc[i] = c * 8;
         base[i] = (origin + r < extent) ? (unsigned)((origin + r) * ld + c * 8) : OOB;
       } else {
-        int kr = 2 * q + (lane >> 5);
-        int c = (lane & 31) ^ swz_mn(kr);
+        constexpr int CPR = R / 8;                 // 16 B chunks per k-row
+        constexpr int KPI = 64 / CPR;              // k-rows per instruction
+        const int kr = KPI * q + lane / CPR;
+        const int c = (lane % CPR) ^ swz_mn(kr);
         kc[i] = kr;
         base[i] = (origin + c * 8 < extent) ? (unsigned)(kr * ld + origin + c * 8) : OOB;
       }
@@ -61,41 +63,48 @@ struct TileLoader {
   // issue this wave's share of the tile starting at reduction index k0 into LDS at `dst`
   GX_DEVINL void issue(char* dst, int k0, int wave) const {
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
+    for (int i = 0; i < PER; i++) {
       unsigned off;
       if (KMAJOR) off = (base[i] != OOB && k0 + kc[i] < K) ? (base[i] + (unsigned)k0) * 2u : OOB;
       else        off = (base[i] != OOB && k0 + kc[i] < K) ? (base[i] + (unsigned)(k0 * ld)) * 2u : OOB;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(dst + (wave * 4 + i) * 1024), 16, off, 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(dst + (wave * PER + i) * 1024), 16, off, 0, 0,
+                                               0);
     }
   }
 };
 
 // fragment of a 32-row block for k sub-step ks (16 k), K-major tile
 GX_DEVINL bf16x8 frag_k(const char* tile, int row, int ks, int g) {
-  int c = (2 * ks + g) ^ swz_k(row);
+  const int c = (2 * ks + g) ^ swz_k(row);
   return *reinterpret_cast<const bf16x8*>(tile + row * 128 + (c << 4));
 }
-// fragment of a 32-column block for k sub-step ks, MN-major tile (two transposing reads)
+// fragment of a 32-column block for k sub-step ks, MN-major tile of R columns (two transposing reads)
+template <int R>
 GX_DEVINL bf16x8 frag_mn(const char* tile, int col0, int ks, int lane) {
-  int g = lane >> 5, s = lane & 15;
-  int kr = 16 * ks + 8 * g + (s >> 2);
-  int ne = col0 + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
-  int c = (ne >> 3) ^ swz_mn(kr);
-  const char* p = tile + kr * 512 + (c << 4) + (ne & 7) * 2;
+  const int g = lane >> 5, s = lane & 15;
+  const int kr = 16 * ks + 8 * g + (s >> 2);
+  const int ne = col0 + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
+  const int c = (ne >> 3) ^ swz_mn(kr);
+  const char* p = tile + kr * (2 * R) + (c << 4) + (ne & 7) * 2;
   typedef __attribute__((address_space(3))) bf16x4* lp;
-  bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lp)(p));
-  bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lp)(p + 4 * 512));
+  const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lp)(p));
+  const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lp)(p + 4 * (2 * R)));
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
-template <int LAY, int EPI>
+// BM x BN output tile (256 x 256, or 128 x 128 for products with too few large tiles to fill the
+// chip); 8 wavefronts as 2 x 4, each owning (BM/2) x (BN/4).
+template <int LAY, int EPI, int BM, int BN>
 __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   constexpr bool A_K = (LAY != LAY_TN);
   constexpr bool B_K = (LAY == LAY_NT);
+  constexpr int TM = BM / 64, TN = BN / 128;          // 32x32 accumulators per wave
+  constexpr int WM = BM / 2, WN = BN / 4;             // wave tile
+  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = wave >> 2, wn = wave & 3;          // 2 x 4 waves, 128 x 64 per wave
+  const int wm = wave >> 2, wn = wave & 3;
   const int grp = lane >> 5, l32 = lane & 31;
 
   // tile index: spread consecutive tiles over the 8 XCDs' round-robin dispatch so that each XCD
@@ -114,50 +123,52 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
 
   const bf16* A = static_cast<const bf16*>(g.A);
   const bf16* B = static_cast<const bf16*>(g.B);
-  TileLoader<A_K> la;
-  TileLoader<B_K> lb;
+  TileLoader<A_K, BM> la;
+  TileLoader<B_K, BN> lb;
   la.init(A, (unsigned)((size_t)(A_K ? g.M : g.K) * g.lda * 2), g.lda, g.K, m0, g.M, wave, lane);
   lb.init(B, (unsigned)((size_t)(B_K ? g.N : g.K) * g.ldb * 2), g.ldb, g.K, n0, g.N, wave, lane);
 
-  f32x16 acc[4][2];
+  f32x16 acc[TM][TN];
 #pragma unroll
-  for (int i = 0; i < 4; i++)
+  for (int i = 0; i < TM; i++)
 #pragma unroll
-    for (int j = 0; j < 2; j++)
+    for (int j = 0; j < TN; j++)
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
 
+  char* sa = smem;                       // A[2]
+  char* sb = smem + 2 * A_BYTES;         // B[2]
   const int nk = (g.K + BK - 1) / BK;
-  la.issue(smem, 0, wave);
-  lb.issue(smem + 2 * TILE_BYTES, 0, wave);
+  la.issue(sa, 0, wave);
+  lb.issue(sb, 0, wave);
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's LDS-DMA has landed
   __syncthreads();
 
   for (int kt = 0; kt < nk; kt++) {
     const int cur = kt & 1;
     if (kt + 1 < nk) {
-      la.issue(smem + (cur ^ 1) * TILE_BYTES, (kt + 1) * BK, wave);
-      lb.issue(smem + (2 + (cur ^ 1)) * TILE_BYTES, (kt + 1) * BK, wave);
+      la.issue(sa + (cur ^ 1) * A_BYTES, (kt + 1) * BK, wave);
+      lb.issue(sb + (cur ^ 1) * B_BYTES, (kt + 1) * BK, wave);
     }
-    const char* ta = smem + cur * TILE_BYTES;
-    const char* tb = smem + (2 + cur) * TILE_BYTES;
+    const char* ta = sa + cur * A_BYTES;
+    const char* tb = sb + cur * B_BYTES;
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ks++) {
-      bf16x8 af[4], bfr[2];
+      bf16x8 af[TM], bfr[TN];
 #pragma unroll
-      for (int mi = 0; mi < 4; mi++) {
-        if (A_K) af[mi] = frag_k(ta, wm * 128 + mi * 32 + l32, ks, grp);
-        else     af[mi] = frag_mn(ta, wm * 128 + mi * 32, ks, lane);
+      for (int mi = 0; mi < TM; mi++) {
+        if (A_K) af[mi] = frag_k(ta, wm * WM + mi * 32 + l32, ks, grp);
+        else     af[mi] = frag_mn<BM>(ta, wm * WM + mi * 32, ks, lane);
       }
 #pragma unroll
-      for (int ni = 0; ni < 2; ni++) {
-        if (B_K) bfr[ni] = frag_k(tb, wn * 64 + ni * 32 + l32, ks, grp);
-        else     bfr[ni] = frag_mn(tb, wn * 64 + ni * 32, ks, lane);
+      for (int ni = 0; ni < TN; ni++) {
+        if (B_K) bfr[ni] = frag_k(tb, wn * WN + ni * 32 + l32, ks, grp);
+        else     bfr[ni] = frag_mn<BN>(tb, wn * WN + ni * 32, ks, lane);
       }
 #pragma unroll
-      for (int mi = 0; mi < 4; mi++)
+      for (int mi = 0; mi < TM; mi++)
 #pragma unroll
-        for (int ni = 0; ni < 2; ni++)
+        for (int ni = 0; ni < TN; ni++)
           acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ni], af[mi], acc[mi][ni], 0, 0, 0);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -166,17 +177,19 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
 
   // epilogue.  The MFMAs were issued with the B fragment as the row operand, so accumulator
   // register v of lane l holds C[m = tile row l%32][n = 8*(v/4) + 4*(l/32) + v%4]: runs of 4
-  // consecutive columns.  Each wavefront passes its 128 x 64 block through a private 16 KB LDS
-  // region, 32 rows at a time (row stride 68 floats keeps the 16 B writes conflict-free), and
-  // reads it back so that 16 lanes cover one 64-column row: every global access of the epilogue
-  // (C, residual, pre-activation, second output) is a 16 B or 8 B vector in fully used lines.
+  // consecutive columns.  Each wavefront passes its block through a private LDS region, 32 rows at
+  // a time (row stride WN + 4 floats keeps the 16 B writes conflict-free), and reads it back so
+  // that WN/4 lanes cover one row: every global access of the epilogue (C, residual,
+  // pre-activation, second output) is a 16 B or 8 B vector in fully used lines.
   const bf16* bias = static_cast<const bf16*>(g.bias);
   const bf16* resid = static_cast<const bf16*>(g.resid);
   const bf16* zin = static_cast<const bf16*>(g.z);
   bf16* aux = static_cast<bf16*>(g.aux);
-  constexpr int EPAD = 68;
-  float* stage = reinterpret_cast<float*>(smem + wave * 16384);
-  const int ecol = n0 + wn * 64 + 4 * (lane & 15);
+  constexpr int EPAD = WN + 4;
+  constexpr int LPR = WN / 4;                          // lanes per row when reading back
+  constexpr int RPI = 64 / LPR;                        // rows per read instruction
+  float* stage = reinterpret_cast<float*>(smem + wave * (32 * EPAD * 4));
+  const int ecol = n0 + wn * WN + 4 * (lane % LPR);
   float bv[4] = {0.f, 0.f, 0.f, 0.f};
   if ((EPI == EPI_BIAS || EPI == EPI_RESID || EPI == EPI_GELU) && bias && ecol < g.N) {
     const bf16x4 b4 = *reinterpret_cast<const bf16x4*>(bias + ecol);
@@ -184,9 +197,9 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
     for (int e = 0; e < 4; e++) bv[e] = (float)b4[e];
   }
 #pragma unroll
-  for (int mi = 0; mi < 4; mi++) {
+  for (int mi = 0; mi < TM; mi++) {
 #pragma unroll
-    for (int ni = 0; ni < 2; ni++)
+    for (int ni = 0; ni < TN; ni++)
 #pragma unroll
       for (int q4 = 0; q4 < 4; q4++) {
         const f32x16& a = acc[mi][ni];
@@ -194,10 +207,10 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
             f32x4{a[4 * q4], a[4 * q4 + 1], a[4 * q4 + 2], a[4 * q4 + 3]};
       }
 #pragma unroll
-    for (int j = 0; j < 8; j++) {
-      const int r = 4 * j + (lane >> 4);
-      const f32x4 xv = *reinterpret_cast<const f32x4*>(stage + r * EPAD + 4 * (lane & 15));
-      const int row = m0 + wm * 128 + mi * 32 + r;
+    for (int j = 0; j < 32 / RPI; j++) {
+      const int r = RPI * j + lane / LPR;
+      const f32x4 xv = *reinterpret_cast<const f32x4*>(stage + r * EPAD + 4 * (lane % LPR));
+      const int row = m0 + wm * WM + mi * 32 + r;
       if (row >= g.M || ecol >= g.N) continue;            // N is a multiple of 4: whole run in or out
       const size_t idx = (size_t)row * g.ldc + ecol;
       float x[4] = {xv[0] + bv[0], xv[1] + bv[1], xv[2] + bv[2], xv[3] + bv[3]};
@@ -236,18 +249,27 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
   }
 }
 
-template <int LAY, int EPI>
-hipError_t launch(const GemmArgs& g, hipStream_t s) {
+template <int LAY, int EPI, int BM, int BN>
+hipError_t launch_tile(const GemmArgs& g, hipStream_t s) {
+  constexpr int SMEM = 2 * (BM + BN) * BK * 2;
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<LAY, EPI>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<LAY, EPI, BM, BN>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
     if (e != hipSuccess) return e;
     configured = true;
   }
   const int tm = cdiv(g.M, BM), tn = cdiv(g.N, BN);
-  hipLaunchKernelGGL((gemm_kernel<LAY, EPI>), dim3(tm * tn), dim3(NTHREADS), SMEM_BYTES, s, g);
+  hipLaunchKernelGGL((gemm_kernel<LAY, EPI, BM, BN>), dim3(tm * tn), dim3(NTHREADS), SMEM, s, g);
   return hipGetLastError();
+}
+
+// 256 x 256 tiles unless they would leave a quarter or more of the 256 compute units idle
+template <int LAY, int EPI>
+hipError_t launch(const GemmArgs& g, hipStream_t s) {
+  const long big = (long)cdiv(g.M, 256) * cdiv(g.N, 256);
+  if (big <= 192) return launch_tile<LAY, EPI, 128, 128>(g, s);
+  return launch_tile<LAY, EPI, 256, 256>(g, s);
 }
 
 template <int LAY>

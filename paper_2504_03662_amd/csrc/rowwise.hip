@@ -90,6 +90,7 @@ __global__ void __launch_bounds__(256) ln_bwd_dx_kernel(const T* __restrict__ dy
   const size_t off = (size_t)row * cols;
   const float mu = mean[row], rs = rstd[row];
   float t[MAXC][V], xh[MAXC][V];
+  typename Vec<T>::type rraw[MAXC];          // residual gradient, fetched with the first wave of loads
   float s1 = 0.f, s2 = 0.f;
 #pragma unroll
   for (int i = 0; i < MAXC; i++) {
@@ -98,6 +99,7 @@ __global__ void __launch_bounds__(256) ln_bwd_dx_kernel(const T* __restrict__ dy
       float gv[V];
       load_vec<T>(dy + off + c * V, t[i]);
       load_vec<T>(x + off + c * V, xh[i]);
+      if (resid) rraw[i] = *reinterpret_cast<const typename Vec<T>::type*>(resid + off + c * V);
       load_vec<T>(g + c * V, gv);
 #pragma unroll
       for (int e = 0; e < V; e++) {
@@ -117,10 +119,8 @@ __global__ void __launch_bounds__(256) ln_bwd_dx_kernel(const T* __restrict__ dy
 #pragma unroll
       for (int e = 0; e < V; e++) o[e] = rs * (t[i][e] - c1 - xh[i][e] * c2);
       if (resid) {
-        float rv[V];
-        load_vec<T>(resid + off + c * V, rv);
 #pragma unroll
-        for (int e = 0; e < V; e++) o[e] += rv[e];
+        for (int e = 0; e < V; e++) o[e] += to_f32(rraw[i][e]);
       }
       store_vec<T>(dx + off + c * V, o);
     }
