@@ -78,18 +78,27 @@ GX_DEVINL bf16x8 frag_k(const char* tile, int row, int ks, int g) {
   const int c = (2 * ks + g) ^ swz_k(row);
   return *reinterpret_cast<const bf16x8*>(tile + row * 128 + (c << 4));
 }
-// fragment of a 32-column block for k sub-step ks, MN-major tile of R columns (two transposing reads)
+// A fragment being fetched: either complete (K-major tile, one ds_read_b128 the compiler tracks)
+// or two untracked transposing reads of an MN-major tile that lds_wait_all() must cover.
+struct Frag {
+  bf16x8 full;
+  bf16x4 lo, hi;
+};
+// fragment of a 32-column block for k sub-step ks, MN-major tile of R columns: issue only
 template <int R>
-GX_DEVINL bf16x8 frag_mn(const char* tile, int col0, int ks, int lane) {
+GX_DEVINL void frag_mn_issue(const char* tile, int col0, int ks, int lane, Frag& f) {
   const int g = lane >> 5, s = lane & 15;
   const int kr = 16 * ks + 8 * g + (s >> 2);
   const int ne = col0 + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
   const int c = (ne >> 3) ^ swz_mn(kr);
-  const char* p = tile + kr * (2 * R) + (c << 4) + (ne & 7) * 2;
-  typedef __attribute__((address_space(3))) bf16x4* lp;
-  const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lp)(p));
-  const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lp)(p + 4 * (2 * R)));
-  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  const unsigned addr = lds_addr(tile + kr * (2 * R) + (c << 4) + (ne & 7) * 2);
+  f.lo = lds_read_tr_issue<0>(addr);
+  f.hi = lds_read_tr_issue<4 * (2 * R)>(addr);
+}
+GX_DEVINL bf16x8 frag_mn_finish(Frag& f) {
+  lds_pin(f.lo);
+  lds_pin(f.hi);
+  return __builtin_shufflevector(f.lo, f.hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
 // BM x BN output tile (256 x 256, or 128 x 128 for products with too few large tiles to fill the
@@ -152,19 +161,31 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
     }
     const char* ta = sa + cur * A_BYTES;
     const char* tb = sb + cur * B_BYTES;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ks++) {
-      bf16x8 af[TM], bfr[TN];
+    // fragments of sub-step ks+1 are requested before the products of sub-step ks are issued
+    Frag fa[2][TM], fb[2][TN];
+    auto request = [&](int ks, int buf) {
 #pragma unroll
       for (int mi = 0; mi < TM; mi++) {
-        if (A_K) af[mi] = frag_k(ta, wm * WM + mi * 32 + l32, ks, grp);
-        else     af[mi] = frag_mn<BM>(ta, wm * WM + mi * 32, ks, lane);
+        if (A_K) fa[buf][mi].full = frag_k(ta, wm * WM + mi * 32 + l32, ks, grp);
+        else     frag_mn_issue<BM>(ta, wm * WM + mi * 32, ks, lane, fa[buf][mi]);
       }
 #pragma unroll
       for (int ni = 0; ni < TN; ni++) {
-        if (B_K) bfr[ni] = frag_k(tb, wn * WN + ni * 32 + l32, ks, grp);
-        else     bfr[ni] = frag_mn<BN>(tb, wn * WN + ni * 32, ks, lane);
+        if (B_K) fb[buf][ni].full = frag_k(tb, wn * WN + ni * 32 + l32, ks, grp);
+        else     frag_mn_issue<BN>(tb, wn * WN + ni * 32, ks, lane, fb[buf][ni]);
       }
+    };
+    request(0, 0);
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ks++) {
+      const int buf = ks & 1;
+      bf16x8 af[TM], bfr[TN];
+      if (!A_K || !B_K) lds_wait_all();
+#pragma unroll
+      for (int mi = 0; mi < TM; mi++) af[mi] = A_K ? fa[buf][mi].full : frag_mn_finish(fa[buf][mi]);
+#pragma unroll
+      for (int ni = 0; ni < TN; ni++) bfr[ni] = B_K ? fb[buf][ni].full : frag_mn_finish(fb[buf][ni]);
+      if (ks + 1 < BK / 16) request(ks + 1, buf ^ 1);
 #pragma unroll
       for (int mi = 0; mi < TM; mi++)
 #pragma unroll

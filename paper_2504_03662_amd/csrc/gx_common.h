@@ -64,6 +64,23 @@ GX_DEVINL float wave_max(float v) {
   return v;
 }
 
+// Transposing LDS read (ds_read_b64_tr_b16) issued through inline assembly.  The compiler cannot
+// tell that such a read does not touch the LDS region a direct-to-LDS load is still filling, and
+// makes the builtin form wait for every load in flight (vmcnt(0)), which serialises the global
+// prefetch with the matrix work.  The kernels already order tiles with explicit waits and
+// barriers, so the read is issued untracked here; its result may only be used after
+// lds_wait_all() and lds_pin() on the destination registers.
+typedef __attribute__((address_space(3))) const char* lds_cptr;
+GX_DEVINL unsigned lds_addr(const char* p) { return (unsigned)(unsigned long)(lds_cptr)p; }
+template <int OFF>
+GX_DEVINL bf16x4 lds_read_tr_issue(unsigned addr) {
+  bf16x4 r;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+  return r;
+}
+GX_DEVINL void lds_wait_all() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+GX_DEVINL void lds_pin(bf16x4& v) { asm volatile("" : "+v"(v)); }
+
 inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
 
 }  // namespace gx
