@@ -56,21 +56,17 @@ GX_DEVINL bf16x8 frag_rows(const char* tile, int r, int s, int g) {
 }
 // MFMA operand whose 32 rows are head-dim columns 32 dt .. 32 dt + 31 and whose reduction index
 // runs over 16 tile rows starting at rbase, in the slot order of an accumulator column
-// (slot (g, e) <-> row rbase + 8 (e / 4) + 4 g + e % 4).  Two transposing reads, issued untracked
-// (see lds_read_tr_issue): use the result only after lds_wait_all() and cols_finish().
-struct ColsFrag { bf16x4 lo, hi; };
-GX_DEVINL void cols_issue(const char* tile, int rbase, int dt, int lane, ColsFrag& f) {
+// (slot (g, e) <-> row rbase + 8 (e / 4) + 4 g + e % 4)
+GX_DEVINL bf16x8 frag_cols(const char* tile, int rbase, int dt, int lane) {
   const int g = lane >> 5, s = lane & 15, hb = (lane >> 4) & 1;
   const int r = rbase + 4 * g + (s >> 2);
   const int d0 = 32 * dt + 16 * hb + 4 * (s & 3);
   const int c = d0 >> 3, within = (d0 & 7) * 2;
-  f.lo = lds_read_tr_issue<0>(lds_addr(tile + r * ROWB + ((c ^ swz(r)) << 4) + within));
-  f.hi = lds_read_tr_issue<0>(lds_addr(tile + (r + 8) * ROWB + ((c ^ swz(r + 8)) << 4) + within));
-}
-GX_DEVINL bf16x8 cols_finish(ColsFrag& f) {
-  lds_pin(f.lo);
-  lds_pin(f.hi);
-  return __builtin_shufflevector(f.lo, f.hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+      (lds_bf16x4_ptr)(tile + r * ROWB + ((c ^ swz(r)) << 4) + within));
+  const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+      (lds_bf16x4_ptr)(tile + (r + 8) * ROWB + ((c ^ swz(r + 8)) << 4) + within));
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
 // registers v = 8 h .. 8 h + 7 of an accumulator, rounded to bf16, as an MFMA operand
@@ -102,7 +98,7 @@ GX_DEVINL void load_row_frags(const bf16* base, int ld, int row, int nrows, int 
 constexpr int F_NW = 4, F_BQ = 32 * F_NW, F_BKV = 64;
 constexpr int F_STAGE = 2 * F_BKV * ROWB;      // K tile | V tile
 
-__global__ void __launch_bounds__(64 * F_NW) attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ ctx,
+__global__ void __launch_bounds__(64 * F_NW, 2) attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ ctx,
                                                              float* __restrict__ lse, int S, int nl,
                                                              unsigned qkv_bytes) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -186,12 +182,8 @@ __global__ void __launch_bounds__(64 * F_NW) attn_fwd_kernel(const bf16* __restr
 #pragma unroll
       for (int u = 0; u < 4; u++) {
         const bf16x8 pf = pack_half(sacc[u >> 1], u & 1);
-        ColsFrag vfr[DH / 32];
 #pragma unroll
-        for (int dt = 0; dt < DH / 32; dt++) cols_issue(vt, 16 * u, dt, lane, vfr[dt]);
-        lds_wait_all();
-#pragma unroll
-        for (int dt = 0; dt < DH / 32; dt++) o[dt] = MFMA(cols_finish(vfr[dt]), pf, o[dt]);
+        for (int dt = 0; dt < DH / 32; dt++) o[dt] = MFMA(frag_cols(vt, 16 * u, dt, lane), pf, o[dt]);
       }
     }
     WAIT_VM0();
@@ -328,17 +320,10 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
 #pragma unroll
         for (int u = 0; u < 2; u++) {
           const bf16x8 pf = pack_half(sacc[sub], u), dsf = pack_half(pacc[sub], u);
-          ColsFrag dof[DH / 32], qfr[DH / 32];
 #pragma unroll
           for (int dt = 0; dt < DH / 32; dt++) {
-            cols_issue(dot, 32 * sub + 16 * u, dt, lane, dof[dt]);
-            cols_issue(qt, 32 * sub + 16 * u, dt, lane, qfr[dt]);
-          }
-          lds_wait_all();
-#pragma unroll
-          for (int dt = 0; dt < DH / 32; dt++) {
-            dv[dt] = MFMA(pf, cols_finish(dof[dt]), dv[dt]);    // dV[j][d] += P^T dO
-            dk[dt] = MFMA(dsf, cols_finish(qfr[dt]), dk[dt]);   // dK[j][d] += dS^T Q
+            dv[dt] = MFMA(pf, frag_cols(dot, 32 * sub + 16 * u, dt, lane), dv[dt]);   // dV[j][d] += P^T dO
+            dk[dt] = MFMA(dsf, frag_cols(qt, 32 * sub + 16 * u, dt, lane), dk[dt]);   // dK[j][d] += dS^T Q
           }
         }
       }
@@ -364,7 +349,7 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
 constexpr int Q_NW = 4, Q_BQ = 32 * Q_NW, Q_BKV = 64;
 constexpr int Q_STAGE = 2 * Q_BKV * ROWB;
 
-__global__ void __launch_bounds__(64 * Q_NW) attn_bwd_dq_kernel(const bf16* __restrict__ qkv,
+__global__ void __launch_bounds__(64 * Q_NW, 2) attn_bwd_dq_kernel(const bf16* __restrict__ qkv,
                                                                 const bf16* __restrict__ dctx,
                                                                 const float* __restrict__ lse,
                                                                 const float* __restrict__ dsum,
@@ -432,12 +417,8 @@ __global__ void __launch_bounds__(64 * Q_NW) attn_bwd_dq_kernel(const bf16* __re
 #pragma unroll
       for (int u = 0; u < 4; u++) {
         const bf16x8 dsf = pack_half(pacc[u >> 1], u & 1);
-        ColsFrag kfr[DH / 32];
 #pragma unroll
-        for (int dt = 0; dt < DH / 32; dt++) cols_issue(kt, 16 * u, dt, lane, kfr[dt]);
-        lds_wait_all();
-#pragma unroll
-        for (int dt = 0; dt < DH / 32; dt++) dq[dt] = MFMA(cols_finish(kfr[dt]), dsf, dq[dt]);
+        for (int dt = 0; dt < DH / 32; dt++) dq[dt] = MFMA(frag_cols(kt, 16 * u, dt, lane), dsf, dq[dt]);
       }
     }
     WAIT_VM0();
