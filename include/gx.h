@@ -37,9 +37,14 @@
  *     is the same index range of the rows of Wo / W2.
  *   - Activations and parameters have the element type cfg->dtype (fp32, or bf16 with fp32
  *     accumulation); parameter gradients are always fp32.
- *   - Calls only enqueue work on `hip_stream` (a hipStream_t, or NULL for the default stream); they
- *     never allocate, free or synchronise, and results are bitwise reproducible run to run.  The
- *     only process-global state is the optional timing record of gx_prof_*.
+ *   - Calls only enqueue work (a hipStream_t, or NULL for the default stream); they never allocate
+ *     device memory, free or synchronise the host, and results are bitwise reproducible run to
+ *     run.  gx_layer_bwd forks part of its work (bias / LayerNorm parameter gradients, one small
+ *     weight gradient) onto a second stream that the library creates on first use (default
+ *     priority, non-blocking) and joins it back with events before returning: to the caller
+ *     everything is ordered on `hip_stream` as if it had run there.  That stream and the optional
+ *     timing record of gx_prof_* are the only process-global state; because of them, calls from
+ *     several host threads must not overlap.
  *   - Errors are returned as gx_status; nothing is thrown across the boundary.  Configuration and
  *     pointer checks happen before anything is enqueued.
  */

@@ -79,8 +79,8 @@ Saved plan_saved(const gx_layer_cfg& c, Arena& a) {
 
 // Backward scratch.
 struct Work {
-  void *dz, *dyn, *dh1, *dctx, *dqkv;
-  float *dsum, *part;
+  void *dz, *dy2, *dy1, *dh1, *dctx, *dqkv;
+  float *dsum, *part;   // part: partial sums of the column reductions (used on the side stream, in order)
   void* recomputed;     // a Saved block when GX_RECOMPUTE is set
 };
 
@@ -88,8 +88,11 @@ Work plan_work(const gx_layer_cfg& c, Arena& a) {
   const Dims d = dims_of(c);
   Work w;
   memset(&w, 0, sizeof(w));
-  w.dyn = a.take(d.T * d.H * d.e);
-  if (c.flags & GX_PHASE_MLP) w.dz = a.take(d.T * d.Fl * d.e);
+  if (c.flags & GX_PHASE_MLP) {
+    w.dz = a.take(d.T * d.Fl * d.e);
+    w.dy2 = a.take(d.T * d.H * d.e);
+  }
+  if (c.flags & GX_PHASE_ATTN) w.dy1 = a.take(d.T * d.H * d.e);
   if ((c.flags & GX_PHASE_ATTN) && (c.flags & GX_PHASE_MLP)) w.dh1 = a.take(d.T * d.H * d.e);
   if (c.flags & GX_PHASE_ATTN) {
     w.dctx = a.take(d.T * d.Hl * d.e);
@@ -193,18 +196,60 @@ hipError_t colsum_p(bool bf, const void* a, int rows, int cols, float* part, flo
   return colsum(bf, a, rows, cols, cols, part, out, acc, s);
 }
 
-// LayerNorm backward plus the finishing sums of its two parameter gradients
-hipError_t ln_bwd_p(bool bf, const void* dy, const void* x, const void* g, const float* mean, const float* rstd,
-                    const void* resid, void* dx, float* part, int rows, int cols, float* dg, float* db, bool acc,
-                    hipStream_t s) {
+hipError_t ln_params_p(bool bf, const void* dy, const void* x, const float* mean, const float* rstd, float* part,
+                       int rows, int cols, float* dg, float* db, bool acc, hipStream_t s) {
   ProfScope ps(GX_KC_LN_BWD, s);
-  hipError_t e = ln_bwd(bf, dy, x, g, mean, rstd, resid, dx, part, rows, cols, s);
-  if (e != hipSuccess) return e;
-  const int nb = ln_bwd_blocks(rows);
-  e = colsum_finish(part, nb, cols, dg, acc, s);
-  if (e != hipSuccess) return e;
-  return colsum_finish(part + (size_t)nb * cols, nb, cols, db, acc, s);
+  return ln_bwd_params(bf, dy, x, mean, rstd, part, rows, cols, dg, db, acc, s);
 }
+
+// The backward pass has bandwidth-bound column reductions (bias and LayerNorm parameter
+// gradients) and one small weight-gradient product whose inputs are ready long before anything
+// consumes their results.  They run on a second, library-owned stream so that they overlap the
+// MFMA-bound products and the attention kernels on the caller's stream: fork with an event after
+// the producer, join once at the end of the call.  Created on first use, default priority,
+// shared by all calls of the process (calls from several host threads must not overlap).
+struct SideStream {
+  bool tried = false, ok = false;
+  hipStream_t s = nullptr;
+  hipEvent_t fork[8];
+  hipEvent_t join;
+} g_side;
+
+bool side_ready() {
+  if (!g_side.tried) {
+    g_side.tried = true;
+    bool ok = hipStreamCreateWithFlags(&g_side.s, hipStreamNonBlocking) == hipSuccess;
+    for (int i = 0; ok && i < 8; i++) ok = hipEventCreateWithFlags(&g_side.fork[i], hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&g_side.join, hipEventDisableTiming) == hipSuccess;
+    g_side.ok = ok;
+  }
+  return g_side.ok;
+}
+
+// Work queued on the side stream after everything queued so far on the caller's stream.
+struct Fork {
+  hipStream_t main, side;
+  int n = 0;
+  bool used = false;
+  explicit Fork(hipStream_t m) : main(m), side(side_ready() ? g_side.s : m) {}
+  // stream for a task that depends on what `main` holds now
+  hipStream_t branch() {
+    if (side != main && n < 8) {
+      (void)hipEventRecord(g_side.fork[n], main);
+      (void)hipStreamWaitEvent(side, g_side.fork[n], 0);
+      n++;
+      used = true;
+      return side;
+    }
+    return main;
+  }
+  hipError_t join() {
+    if (!used) return hipSuccess;
+    hipError_t e = hipEventRecord(g_side.join, side);
+    if (e != hipSuccess) return e;
+    return hipStreamWaitEvent(main, g_side.join, 0);
+  }
+};
 
 GemmArgs gargs(const void* A, const void* B, void* C, long M, long N, long K, long lda, long ldb, long ldc) {
   GemmArgs g;
@@ -292,35 +337,44 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
   const bool attn = c.flags & GX_PHASE_ATTN, mlp = c.flags & GX_PHASE_MLP;
   const Epilogue wg = (c.flags & GX_ACCUM_WGRAD) ? EPI_F32_ACC : EPI_F32;
   const bool acc = c.flags & GX_ACCUM_WGRAD;
+  Fork fk(st);
+  gx_status s;
   const void* dcur = dy;           // gradient arriving at the attention half's output
   if (mlp) {
     const void* h1 = attn ? sv.h1 : x;
-    // row-parallel FC2: weight gradient, bias gradient, input gradient fused with GELU'
+    // side: db2 needs only dy
+    if ((s = bias_grad(d, c, c.flags & GX_ROW_BIAS_MLP, dy, d.H, w.part, gr.b_fc2, fk.branch())) != GX_OK) return s;
+    // row-parallel FC2: weight gradient, then input gradient fused with GELU'
     GemmArgs w2 = gargs(sv.act, dy, gr.w_fc2, d.Fl, d.H, d.T, d.Fl, d.H, d.H);
     GX_TRY(gemm(d, LAY_TN, wg, w2, st));
-    gx_status s = bias_grad(d, c, c.flags & GX_ROW_BIAS_MLP, dy, d.H, w.part, gr.b_fc2, st);
-    if (s != GX_OK) return s;
     GemmArgs dz = gargs(dy, p.w_fc2, w.dz, d.T, d.Fl, d.H, d.H, d.H, d.Fl);
     dz.z = sv.z;
     GX_TRY(gemm(d, LAY_NT, EPI_DGELU, dz, st));
-    GX_TRY(colsum_p(d.bf, w.dz, (int)d.T, (int)d.Fl, w.part, gr.b_fc1, acc, st));
+    GX_TRY(colsum_p(d.bf, w.dz, (int)d.T, (int)d.Fl, w.part, gr.b_fc1, acc, fk.branch()));      // side: db1
     // column-parallel FC1
     GemmArgs w1 = gargs(sv.y2, w.dz, gr.w_fc1, d.H, d.Fl, d.T, d.H, d.Fl, d.Fl);
     GX_TRY(gemm(d, LAY_TN, wg, w1, st));
-    GemmArgs dy2 = gargs(w.dz, p.w_fc1, w.dyn, d.T, d.H, d.Fl, d.Fl, d.Fl, d.H);
+    GemmArgs dy2 = gargs(w.dz, p.w_fc1, w.dy2, d.T, d.H, d.Fl, d.Fl, d.Fl, d.H);
     GX_TRY(gemm(d, LAY_NT, EPI_STORE, dy2, st));
-    // LayerNorm 2; with both phases the residual branch adds dy
+    // LayerNorm 2: parameter gradients on the side; input gradient (plus dy through the residual
+    // branch when both phases run) on the caller's stream
+    GX_TRY(ln_params_p(d.bf, w.dy2, h1, sv.mean2, sv.rstd2, w.part, (int)d.T, (int)d.H, gr.ln2_g, gr.ln2_b, acc,
+                       fk.branch()));
     void* out = attn ? w.dh1 : dx;
-    GX_TRY(ln_bwd_p(d.bf, w.dyn, h1, p.ln2_g, sv.mean2, sv.rstd2, attn ? dy : nullptr, out, w.part, (int)d.T,
-                    (int)d.H, gr.ln2_g, gr.ln2_b, acc, st));
+    {
+      ProfScope ps(GX_KC_LN_BWD, st);
+      GX_TRY(ln_bwd_dx(d.bf, w.dy2, h1, p.ln2_g, sv.mean2, sv.rstd2, attn ? dy : nullptr, out, (int)d.T, (int)d.H,
+                       st));
+    }
     dcur = w.dh1;
   }
   if (attn) {
-    // row-parallel output projection
+    // row-parallel output projection: bias and weight gradients on the side (the weight gradient
+    // has few tiles and overlaps the attention kernels), input gradient on the caller's stream
+    hipStream_t sd = fk.branch();
+    if ((s = bias_grad(d, c, c.flags & GX_ROW_BIAS_ATTN, dcur, d.H, w.part, gr.b_o, sd)) != GX_OK) return s;
     GemmArgs wo = gargs(sv.ctx, dcur, gr.w_o, d.Hl, d.H, d.T, d.Hl, d.H, d.H);
-    GX_TRY(gemm(d, LAY_TN, wg, wo, st));
-    gx_status s = bias_grad(d, c, c.flags & GX_ROW_BIAS_ATTN, dcur, d.H, w.part, gr.b_o, st);
-    if (s != GX_OK) return s;
+    GX_TRY(gemm(d, LAY_TN, wg, wo, sd));
     GemmArgs dc = gargs(dcur, p.w_o, w.dctx, d.T, d.Hl, d.H, d.H, d.H, d.Hl);
     GX_TRY(gemm(d, LAY_NT, EPI_STORE, dc, st));
     AttnArgs a;
@@ -330,14 +384,20 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     { ProfScope ps(GX_KC_ATTN_BWD, st);
     GX_TRY(d.bf ? attn_bwd_bf16(a, st) : attn_bwd_f32(a, st)); }
     // column-parallel QKV
-    GX_TRY(colsum_p(d.bf, w.dqkv, (int)d.T, (int)(3 * d.Hl), w.part, gr.b_qkv, acc, st));
+    GX_TRY(colsum_p(d.bf, w.dqkv, (int)d.T, (int)(3 * d.Hl), w.part, gr.b_qkv, acc, fk.branch()));   // side: dbqkv
     GemmArgs wq = gargs(sv.y1, w.dqkv, gr.w_qkv, d.H, 3 * d.Hl, d.T, d.H, 3 * d.Hl, 3 * d.Hl);
     GX_TRY(gemm(d, LAY_TN, wg, wq, st));
-    GemmArgs dy1 = gargs(w.dqkv, p.w_qkv, w.dyn, d.T, d.H, 3 * d.Hl, 3 * d.Hl, 3 * d.Hl, d.H);
+    GemmArgs dy1 = gargs(w.dqkv, p.w_qkv, w.dy1, d.T, d.H, 3 * d.Hl, 3 * d.Hl, 3 * d.Hl, d.H);
     GX_TRY(gemm(d, LAY_NT, EPI_STORE, dy1, st));
-    GX_TRY(ln_bwd_p(d.bf, w.dyn, x, p.ln1_g, sv.mean1, sv.rstd1, mlp ? dcur : nullptr, dx, w.part, (int)d.T,
-                    (int)d.H, gr.ln1_g, gr.ln1_b, acc, st));
+    GX_TRY(ln_params_p(d.bf, w.dy1, x, sv.mean1, sv.rstd1, w.part, (int)d.T, (int)d.H, gr.ln1_g, gr.ln1_b, acc,
+                       fk.branch()));
+    {
+      ProfScope ps(GX_KC_LN_BWD, st);
+      GX_TRY(ln_bwd_dx(d.bf, w.dy1, x, p.ln1_g, sv.mean1, sv.rstd1, mlp ? dcur : nullptr, dx, (int)d.T, (int)d.H,
+                       st));
+    }
   }
+  GX_TRY(fk.join());
   return GX_OK;
 }
 

@@ -55,10 +55,13 @@ hipError_t attn_bwd_f32(const AttnArgs& a, hipStream_t s);
 // LayerNorm forward: y = g * (x - mean) * rstd + b; writes mean/rstd per row.
 hipError_t ln_fwd(bool bf16, const void* x, const void* g, const void* b, void* y, float* mean, float* rstd,
                   int rows, int cols, float eps, hipStream_t s);
-// LayerNorm backward: dx = (resid ? resid : 0) + LNbwd(dy); per-block partial sums of dg/db go
-// to part[2][nblk][cols]; returns nblk through the sizing helper below.
-hipError_t ln_bwd(bool bf16, const void* dy, const void* x, const void* g, const float* mean, const float* rstd,
-                  const void* resid, void* dx, float* part, int rows, int cols, hipStream_t s);
+// LayerNorm backward, input gradient: dx = (resid ? resid : 0) + LNbwd(dy).
+hipError_t ln_bwd_dx(bool bf16, const void* dy, const void* x, const void* g, const float* mean, const float* rstd,
+                     const void* resid, void* dx, int rows, int cols, hipStream_t s);
+// LayerNorm backward, parameter gradients: dg (=|+=) sum_rows dy * xhat, db (=|+=) sum_rows dy, through
+// per-block partial sums in part[2][ln_bwd_blocks(rows)][cols] and a fixed-order finish.
+hipError_t ln_bwd_params(bool bf16, const void* dy, const void* x, const float* mean, const float* rstd, float* part,
+                         int rows, int cols, float* dg, float* db, bool accumulate, hipStream_t s);
 int ln_bwd_blocks(int rows);
 // Finish a two-stage column reduction: out[c] (=|+=) sum_b part[b][c].
 hipError_t colsum_finish(const float* part, int nblk, int cols, float* out, bool accumulate, hipStream_t s);

@@ -225,28 +225,42 @@ hipError_t ln_fwd(bool is_bf16, const void* x, const void* g, const void* b, voi
   return hipGetLastError();
 }
 
-hipError_t ln_bwd(bool is_bf16, const void* dy, const void* x, const void* g, const float* mean, const float* rstd,
-                  const void* resid, void* dx, float* part, int rows, int cols, hipStream_t s) {
+hipError_t ln_bwd_dx(bool is_bf16, const void* dy, const void* x, const void* g, const float* mean,
+                     const float* rstd, const void* resid, void* dx, int rows, int cols, hipStream_t s) {
   const int vec = is_bf16 ? 8 : 4;
   if (rows <= 0 || cols <= 0 || cols % vec || cols / vec > 64 * LN_MAXC) return hipErrorInvalidValue;
-  const int nblk = ln_bwd_blocks(rows);
-  const int rpb = cdiv(rows, nblk);
-  dim3 gdx(cdiv(rows, 4)), gpar(cdiv(cols / vec, 256), nblk), block(256);
+  dim3 gdx(cdiv(rows, 4)), block(256);
   const int per_lane = cdiv(cols / vec, 64);
 #define GX_LN_DX(T, C)                                                                                            \
   hipLaunchKernelGGL((ln_bwd_dx_kernel<T, C>), gdx, block, 0, s, (const T*)dy, (const T*)x, (const T*)g, mean, rstd, \
                      (const T*)resid, (T*)dx, rows, cols)
   if (is_bf16) {
     if (per_lane <= 4) GX_LN_DX(bf16, 4); else if (per_lane <= 8) GX_LN_DX(bf16, 8); else GX_LN_DX(bf16, 16);
-    hipLaunchKernelGGL(ln_bwd_param_kernel<bf16>, gpar, block, 0, s, (const bf16*)dy, (const bf16*)x, mean, rstd, rows,
-                       cols, rpb, part);
   } else {
     if (per_lane <= 4) GX_LN_DX(float, 4); else if (per_lane <= 8) GX_LN_DX(float, 8); else GX_LN_DX(float, 16);
-    hipLaunchKernelGGL(ln_bwd_param_kernel<float>, gpar, block, 0, s, (const float*)dy, (const float*)x, mean, rstd,
-                       rows, cols, rpb, part);
   }
 #undef GX_LN_DX
   return hipGetLastError();
+}
+
+hipError_t ln_bwd_params(bool is_bf16, const void* dy, const void* x, const float* mean, const float* rstd,
+                         float* part, int rows, int cols, float* dg, float* db, bool accumulate, hipStream_t s) {
+  const int vec = is_bf16 ? 8 : 4;
+  if (rows <= 0 || cols <= 0 || cols % vec) return hipErrorInvalidValue;
+  const int nblk = ln_bwd_blocks(rows);
+  const int rpb = cdiv(rows, nblk);
+  dim3 gpar(cdiv(cols / vec, 256), nblk), block(256);
+  if (is_bf16)
+    hipLaunchKernelGGL(ln_bwd_param_kernel<bf16>, gpar, block, 0, s, (const bf16*)dy, (const bf16*)x, mean, rstd, rows,
+                       cols, rpb, part);
+  else
+    hipLaunchKernelGGL(ln_bwd_param_kernel<float>, gpar, block, 0, s, (const float*)dy, (const float*)x, mean, rstd,
+                       rows, cols, rpb, part);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  e = colsum_finish(part, nblk, cols, dg, accumulate, s);
+  if (e != hipSuccess) return e;
+  return colsum_finish(part + (size_t)nblk * cols, nblk, cols, db, accumulate, s);
 }
 
 hipError_t colsum_finish(const float* part, int nblk, int cols, float* out, bool accumulate, hipStream_t s) {
