@@ -467,7 +467,11 @@ hipError_t attn_fwd_bf16(const AttnArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t attn_bwd_bf16(const AttnArgs& a, hipStream_t s) {
+// dK/dV and dQ are independent once D is known, and both are short of workgroups near the ends of
+// the causal triangle (heavy key blocks come first in one, heavy query blocks last in the other):
+// with a second stream the dQ kernel runs beside the dK/dV kernel and fills the compute units
+// the other leaves idle.  `fork` / `join` are events owned by the caller of this function.
+hipError_t attn_bwd_bf16(const AttnArgs& a, hipStream_t s, hipStream_t s_dq, hipEvent_t fork, hipEvent_t join) {
   if (!attn_shape_ok(a)) return hipErrorInvalidValue;
   static bool configured = false;
   if (!configured) {
@@ -483,14 +487,23 @@ hipError_t attn_bwd_bf16(const AttnArgs& a, hipStream_t s) {
                      (const bf16*)a.dctx, a.dsum, a.B, a.S, a.nl);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  const bool two = (s_dq != s);
+  if (two) {
+    if ((e = hipEventRecord(fork, s)) != hipSuccess) return e;
+    if ((e = hipStreamWaitEvent(s_dq, fork, 0)) != hipSuccess) return e;
+  }
   hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3(cdiv(a.S, KV_BJ), a.nl, a.B), dim3(64 * KV_NW), 2 * KV_STAGE, s,
                      (const bf16*)a.qkv, (const bf16*)a.dctx, a.lse, a.dsum, (bf16*)a.dqkv, a.S, a.nl, qkv_bytes,
                      dctx_bytes);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(cdiv(a.S, Q_BQ), a.nl, a.B), dim3(64 * Q_NW), 2 * Q_STAGE, s,
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(cdiv(a.S, Q_BQ), a.nl, a.B), dim3(64 * Q_NW), 2 * Q_STAGE, s_dq,
                      (const bf16*)a.qkv, (const bf16*)a.dctx, a.lse, a.dsum, (bf16*)a.dqkv, a.S, a.nl, qkv_bytes);
-  return hipGetLastError();
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (two) {
+    if ((e = hipEventRecord(join, s_dq)) != hipSuccess) return e;
+    if ((e = hipStreamWaitEvent(s, join, 0)) != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 }  // namespace gx

@@ -111,6 +111,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
   constexpr int TM = BM / 64, TN = BN / 128;          // 32x32 accumulators per wave
   constexpr int WM = BM / 2, WN = BN / 4;             // wave tile
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+  constexpr int SPLIT_KS = (LAY == LAY_NT) ? 1 : 0;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 2, wn = wave & 3;
@@ -155,10 +156,9 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
 
   for (int kt = 0; kt < nk; kt++) {
     const int cur = kt & 1;
-    if (kt + 1 < nk) {
-      la.issue(sa + (cur ^ 1) * A_BYTES, (kt + 1) * BK, wave);
-      lb.issue(sb + (cur ^ 1) * B_BYTES, (kt + 1) * BK, wave);
-    }
+    // the prefetch of the next tile goes out in two halves (A now, B one sub-step later) so that
+    // the wavefronts of a SIMD do not all sit in the load issue queue at the top of the step
+    if (kt + 1 < nk) la.issue(sa + (cur ^ 1) * A_BYTES, (kt + 1) * BK, wave);
     const char* ta = sa + cur * A_BYTES;
     const char* tb = sb + cur * B_BYTES;
     // fragments of sub-step ks+1 are requested before the products of sub-step ks are issued
@@ -186,6 +186,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int ni = 0; ni < TN; ni++) bfr[ni] = B_K ? fb[buf][ni].full : frag_mn_finish(fb[buf][ni]);
       if (ks + 1 < BK / 16) request(ks + 1, buf ^ 1);
+      if (ks == SPLIT_KS && kt + 1 < nk) lb.issue(sb + (cur ^ 1) * B_BYTES, (kt + 1) * BK, wave);
 #pragma unroll
       for (int mi = 0; mi < TM; mi++)
 #pragma unroll

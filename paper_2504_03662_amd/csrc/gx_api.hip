@@ -212,7 +212,7 @@ struct SideStream {
   bool tried = false, ok = false;
   hipStream_t s = nullptr;
   hipEvent_t fork[8];
-  hipEvent_t join;
+  hipEvent_t join, attn_fork, attn_join;
 } g_side;
 
 bool side_ready() {
@@ -221,6 +221,8 @@ bool side_ready() {
     bool ok = hipStreamCreateWithFlags(&g_side.s, hipStreamNonBlocking) == hipSuccess;
     for (int i = 0; ok && i < 8; i++) ok = hipEventCreateWithFlags(&g_side.fork[i], hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&g_side.join, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&g_side.attn_fork, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&g_side.attn_join, hipEventDisableTiming) == hipSuccess;
     g_side.ok = ok;
   }
   return g_side.ok;
@@ -382,7 +384,8 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     a.qkv = sv.qkv; a.ctx = sv.ctx; a.lse = sv.lse; a.dctx = w.dctx; a.dqkv = w.dqkv; a.dsum = w.dsum;
     a.B = (int)d.B; a.S = (int)d.S; a.nl = (int)d.nl; a.dh = (int)d.dh;
     { ProfScope ps(GX_KC_ATTN_BWD, st);
-    GX_TRY(d.bf ? attn_bwd_bf16(a, st) : attn_bwd_f32(a, st)); }
+    GX_TRY(d.bf ? attn_bwd_bf16(a, st, fk.side, g_side.attn_fork, g_side.attn_join) : attn_bwd_f32(a, st));
+    if (d.bf && fk.side != st) fk.used = true; }
     // column-parallel QKV
     GX_TRY(colsum_p(d.bf, w.dqkv, (int)d.T, (int)(3 * d.Hl), w.part, gr.b_qkv, acc, fk.branch()));   // side: dbqkv
     GemmArgs wq = gargs(sv.y1, w.dqkv, gr.w_qkv, d.H, 3 * d.Hl, d.T, d.H, 3 * d.Hl, 3 * d.Hl);

@@ -47,7 +47,9 @@ struct AttnArgs {
   int B, S, nl, dh;
 };
 hipError_t attn_fwd_bf16(const AttnArgs& a, hipStream_t s);
-hipError_t attn_bwd_bf16(const AttnArgs& a, hipStream_t s);
+// s_dq may equal s (everything in order on one stream); otherwise the dQ kernel runs on s_dq between
+// the two caller-owned events: fork (recorded on s after D is known) and join (s waits for it).
+hipError_t attn_bwd_bf16(const AttnArgs& a, hipStream_t s, hipStream_t s_dq, hipEvent_t fork, hipEvent_t join);
 hipError_t attn_fwd_f32(const AttnArgs& a, hipStream_t s);
 hipError_t attn_bwd_f32(const AttnArgs& a, hipStream_t s);
 
