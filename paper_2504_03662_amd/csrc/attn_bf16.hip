@@ -95,20 +95,26 @@ GX_DEVINL void load_row_frags(const bf16* base, int ld, int row, int nrows, int 
 #define WAIT_VM0() __builtin_amdgcn_s_waitcnt(0x0F70)
 
 // ------------------------------------------------------------------------------- forward
-constexpr int F_NW = 4, F_BQ = 32 * F_NW, F_BKV = 64;
-constexpr int F_STAGE = 2 * F_BKV * ROWB;      // K tile | V tile
+constexpr int F_BQ = 128, F_BKV = 64;
 
-__global__ void __launch_bounds__(64 * F_NW, 2) attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ ctx,
-                                                             float* __restrict__ lse, int S, int nl,
-                                                             unsigned qkv_bytes) {
+// SPLIT = 1: 4 wavefronts, one 64-row K/V tile per step.  SPLIT = 2 (few (sample, head) pairs, so
+// the longest query block is the critical path): 8 wavefronts, two tiles per step; wavefronts w
+// and w + 4 share 32 query rows, take alternate tiles, and merge their (max, sum, O) through LDS.
+template <int SPLIT>
+__global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_fwd_kernel(const bf16* __restrict__ qkv,
+                                                                          bf16* __restrict__ ctx,
+                                                                          float* __restrict__ lse, int S, int nl,
+                                                                          unsigned qkv_bytes) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
+  constexpr int NW = 4 * SPLIT, ROWS = F_BKV * SPLIT, STAGE = 2 * ROWS * ROWB;   // K rows | V rows
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int qs = wave & 3, half = wave >> 2;
   const int g = lane >> 5, l32 = lane & 31;
   const int nq = (S + F_BQ - 1) / F_BQ;
   const int qt = nq - 1 - blockIdx.x;                 // longest rows first
   const int h = blockIdx.y, b = blockIdx.z;
   const int Hl = nl * DH, ld = 3 * Hl;
-  const int i0 = qt * F_BQ, iw = i0 + wave * 32;      // this wave's first query row
+  const int i0 = qt * F_BQ, iw = i0 + qs * 32;        // this wave's first query row
   const unsigned eq = (unsigned)((size_t)b * S * ld + h * DH);
   const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(qkv), 0, qkv_bytes,
                                                                         0x00020000);
@@ -122,21 +128,21 @@ __global__ void __launch_bounds__(64 * F_NW, 2) attn_fwd_kernel(const bf16* __re
   const float c2 = rsqrtf((float)DH) * LOG2E;
 
   const int jend = min(S, i0 + F_BQ);                 // keys 0 .. jend-1 can be visible
-  const int nt = (jend + F_BKV - 1) / F_BKV;
-  tile_load<F_BKV, F_NW>(rsrc, eq + Hl, ld, 0, S, smem, wave, lane);
-  tile_load<F_BKV, F_NW>(rsrc, eq + 2 * Hl, ld, 0, S, smem + F_BKV * ROWB, wave, lane);
+  const int nt = (jend + ROWS - 1) / ROWS;
+  tile_load<ROWS, NW>(rsrc, eq + Hl, ld, 0, S, smem, wave, lane);
+  tile_load<ROWS, NW>(rsrc, eq + 2 * Hl, ld, 0, S, smem + ROWS * ROWB, wave, lane);
   WAIT_VM0();
   __syncthreads();
   for (int t = 0; t < nt; t++) {
-    const int j0 = t * F_BKV;
     if (t + 1 < nt) {
-      char* nxt = smem + ((t + 1) & 1) * F_STAGE;
-      tile_load<F_BKV, F_NW>(rsrc, eq + Hl, ld, j0 + F_BKV, S, nxt, wave, lane);
-      tile_load<F_BKV, F_NW>(rsrc, eq + 2 * Hl, ld, j0 + F_BKV, S, nxt + F_BKV * ROWB, wave, lane);
+      char* nxt = smem + ((t + 1) & 1) * STAGE;
+      tile_load<ROWS, NW>(rsrc, eq + Hl, ld, (t + 1) * ROWS, S, nxt, wave, lane);
+      tile_load<ROWS, NW>(rsrc, eq + 2 * Hl, ld, (t + 1) * ROWS, S, nxt + ROWS * ROWB, wave, lane);
     }
+    const int j0 = t * ROWS + half * F_BKV;            // this wave's 64 keys of the step
     if (j0 <= iw + 31) {                               // wave-uniform: some key of the tile is visible
-      const char* kt = smem + (t & 1) * F_STAGE;
-      const char* vt = kt + F_BKV * ROWB;
+      const char* kt = smem + (t & 1) * STAGE + half * F_BKV * ROWB;
+      const char* vt = kt + ROWS * ROWB;
       f32x16 sacc[2];
 #pragma unroll
       for (int jt = 0; jt < 2; jt++) {
@@ -188,6 +194,30 @@ __global__ void __launch_bounds__(64 * F_NW, 2) attn_fwd_kernel(const bf16* __re
     }
     WAIT_VM0();
     __syncthreads();
+  }
+  if (SPLIT == 2) {
+    // merge the two halves' partial softmax states; the tiles are no longer needed, so the upper
+    // half parks (m, l, O) in LDS as [query sub-tile][66 values][64 lanes] and the lower half folds it in
+    float* park = reinterpret_cast<float*>(smem) + qs * (66 * 64) + lane;
+    if (half == 1) {
+      park[0] = m;
+      park[64] = lsum;
+#pragma unroll
+      for (int dt = 0; dt < DH / 32; dt++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) park[(2 + 16 * dt + v) * 64] = o[dt][v];
+    }
+    __syncthreads();
+    if (half == 1) return;
+    const float m1 = park[0], l1 = park[64];
+    const float mm = fmaxf(m, m1);                    // the lower half always saw key 0: mm is finite
+    const float a0 = __builtin_amdgcn_exp2f(m - mm), a1 = __builtin_amdgcn_exp2f(m1 - mm);
+    lsum = lsum * a0 + l1 * a1;
+    m = mm;
+#pragma unroll
+    for (int dt = 0; dt < DH / 32; dt++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) o[dt][v] = o[dt][v] * a0 + park[(2 + 16 * dt + v) * 64] * a1;
   }
   lsum += __shfl_xor(lsum, 32, 64);
   const int i = iw + l32;
@@ -346,23 +376,27 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
 }
 
 // ------------------------------------------------------------------------------- backward: dQ
-constexpr int Q_NW = 4, Q_BQ = 32 * Q_NW, Q_BKV = 64;
-constexpr int Q_STAGE = 2 * Q_BKV * ROWB;
+constexpr int Q_BQ = 128, Q_BKV = 64;
 
-__global__ void __launch_bounds__(64 * Q_NW, 2) attn_bwd_dq_kernel(const bf16* __restrict__ qkv,
-                                                                const bf16* __restrict__ dctx,
-                                                                const float* __restrict__ lse,
-                                                                const float* __restrict__ dsum,
-                                                                bf16* __restrict__ dqkv, int S, int nl,
-                                                                unsigned qkv_bytes) {
+// SPLIT as in the forward kernel; the two halves' dQ partial sums are added through LDS in a
+// fixed order (lower half + upper half).
+template <int SPLIT>
+__global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_bwd_dq_kernel(const bf16* __restrict__ qkv,
+                                                                             const bf16* __restrict__ dctx,
+                                                                             const float* __restrict__ lse,
+                                                                             const float* __restrict__ dsum,
+                                                                             bf16* __restrict__ dqkv, int S, int nl,
+                                                                             unsigned qkv_bytes) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
+  constexpr int NW = 4 * SPLIT, ROWS = Q_BKV * SPLIT, STAGE = 2 * ROWS * ROWB;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int qs = wave & 3, half = wave >> 2;
   const int g = lane >> 5, l32 = lane & 31;
   const int nq = (S + Q_BQ - 1) / Q_BQ;
   const int qt = nq - 1 - blockIdx.x;
   const int h = blockIdx.y, b = blockIdx.z;
   const int Hl = nl * DH, ld = 3 * Hl;
-  const int i0 = qt * Q_BQ, iw = i0 + wave * 32;
+  const int i0 = qt * Q_BQ, iw = i0 + qs * 32;
   const unsigned eq = (unsigned)((size_t)b * S * ld + h * DH);
   const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(qkv), 0, qkv_bytes,
                                                                         0x00020000);
@@ -379,21 +413,21 @@ __global__ void __launch_bounds__(64 * Q_NW, 2) attn_bwd_dq_kernel(const bf16* _
   for (int dt = 0; dt < DH / 32; dt++) dq[dt] = zero16();
 
   const int jend = min(S, i0 + Q_BQ);
-  const int nt = (jend + Q_BKV - 1) / Q_BKV;
-  tile_load<Q_BKV, Q_NW>(rsrc, eq + Hl, ld, 0, S, smem, wave, lane);
-  tile_load<Q_BKV, Q_NW>(rsrc, eq + 2 * Hl, ld, 0, S, smem + Q_BKV * ROWB, wave, lane);
+  const int nt = (jend + ROWS - 1) / ROWS;
+  tile_load<ROWS, NW>(rsrc, eq + Hl, ld, 0, S, smem, wave, lane);
+  tile_load<ROWS, NW>(rsrc, eq + 2 * Hl, ld, 0, S, smem + ROWS * ROWB, wave, lane);
   WAIT_VM0();
   __syncthreads();
   for (int t = 0; t < nt; t++) {
-    const int j0 = t * Q_BKV;
     if (t + 1 < nt) {
-      char* nxt = smem + ((t + 1) & 1) * Q_STAGE;
-      tile_load<Q_BKV, Q_NW>(rsrc, eq + Hl, ld, j0 + Q_BKV, S, nxt, wave, lane);
-      tile_load<Q_BKV, Q_NW>(rsrc, eq + 2 * Hl, ld, j0 + Q_BKV, S, nxt + Q_BKV * ROWB, wave, lane);
+      char* nxt = smem + ((t + 1) & 1) * STAGE;
+      tile_load<ROWS, NW>(rsrc, eq + Hl, ld, (t + 1) * ROWS, S, nxt, wave, lane);
+      tile_load<ROWS, NW>(rsrc, eq + 2 * Hl, ld, (t + 1) * ROWS, S, nxt + ROWS * ROWB, wave, lane);
     }
+    const int j0 = t * ROWS + half * Q_BKV;
     if (j0 <= iw + 31) {
-      const char* kt = smem + (t & 1) * Q_STAGE;
-      const char* vt = kt + Q_BKV * ROWB;
+      const char* kt = smem + (t & 1) * STAGE + half * Q_BKV * ROWB;
+      const char* vt = kt + ROWS * ROWB;
       f32x16 sacc[2], pacc[2];
 #pragma unroll
       for (int jt = 0; jt < 2; jt++) {
@@ -424,6 +458,21 @@ __global__ void __launch_bounds__(64 * Q_NW, 2) attn_bwd_dq_kernel(const bf16* _
     WAIT_VM0();
     __syncthreads();
   }
+  if (SPLIT == 2) {
+    float* park = reinterpret_cast<float*>(smem) + qs * (64 * 64) + lane;
+    if (half == 1) {
+#pragma unroll
+      for (int dt = 0; dt < DH / 32; dt++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) park[(16 * dt + v) * 64] = dq[dt][v];
+    }
+    __syncthreads();
+    if (half == 1) return;
+#pragma unroll
+    for (int dt = 0; dt < DH / 32; dt++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) dq[dt][v] += park[(16 * dt + v) * 64];
+  }
   if (i < S) {
     bf16* row = dqkv + ((size_t)b * S + i) * ld + h * DH;
 #pragma unroll
@@ -452,18 +501,27 @@ bool attn_shape_ok(const AttnArgs& a) {
 
 }  // namespace
 
+// With few (sample, head) pairs the 128-row query blocks cannot fill the chip and the longest
+// block is the critical path: split its key range over two wavefronts.
+bool split_keys(const AttnArgs& a) { return (long)a.B * a.nl * cdiv(a.S, 128) <= 384; }
+
 hipError_t attn_fwd_bf16(const AttnArgs& a, hipStream_t s) {
   if (!attn_shape_ok(a)) return hipErrorInvalidValue;
   static bool configured = false;
   if (!configured) {
-    hipError_t e = set_smem(attn_fwd_kernel, 2 * F_STAGE);
+    hipError_t e = set_smem(attn_fwd_kernel<1>, 4 * F_BKV * ROWB);
+    if (e == hipSuccess) e = set_smem(attn_fwd_kernel<2>, 8 * F_BKV * ROWB);
     if (e != hipSuccess) return e;
     configured = true;
   }
   const unsigned qkv_bytes = (unsigned)((size_t)a.B * a.S * 3 * a.nl * DH * 2);
   dim3 grid(cdiv(a.S, F_BQ), a.nl, a.B);
-  hipLaunchKernelGGL(attn_fwd_kernel, grid, dim3(64 * F_NW), 2 * F_STAGE, s, (const bf16*)a.qkv, (bf16*)a.ctx, a.lse,
-                     a.S, a.nl, qkv_bytes);
+  if (split_keys(a))
+    hipLaunchKernelGGL(attn_fwd_kernel<2>, grid, dim3(512), 8 * F_BKV * ROWB, s, (const bf16*)a.qkv, (bf16*)a.ctx,
+                       a.lse, a.S, a.nl, qkv_bytes);
+  else
+    hipLaunchKernelGGL(attn_fwd_kernel<1>, grid, dim3(256), 4 * F_BKV * ROWB, s, (const bf16*)a.qkv, (bf16*)a.ctx,
+                       a.lse, a.S, a.nl, qkv_bytes);
   return hipGetLastError();
 }
 
@@ -476,7 +534,8 @@ hipError_t attn_bwd_bf16(const AttnArgs& a, hipStream_t s, hipStream_t s_dq, hip
   static bool configured = false;
   if (!configured) {
     hipError_t e = set_smem(attn_bwd_dkv_kernel, 2 * KV_STAGE);
-    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel, 2 * Q_STAGE);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<1>, 4 * Q_BKV * ROWB);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<2>, 8 * Q_BKV * ROWB);
     if (e != hipSuccess) return e;
     configured = true;
   }
@@ -496,8 +555,12 @@ hipError_t attn_bwd_bf16(const AttnArgs& a, hipStream_t s, hipStream_t s_dq, hip
                      (const bf16*)a.qkv, (const bf16*)a.dctx, a.lse, a.dsum, (bf16*)a.dqkv, a.S, a.nl, qkv_bytes,
                      dctx_bytes);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(cdiv(a.S, Q_BQ), a.nl, a.B), dim3(64 * Q_NW), 2 * Q_STAGE, s_dq,
-                     (const bf16*)a.qkv, (const bf16*)a.dctx, a.lse, a.dsum, (bf16*)a.dqkv, a.S, a.nl, qkv_bytes);
+  if (split_keys(a))
+    hipLaunchKernelGGL(attn_bwd_dq_kernel<2>, dim3(cdiv(a.S, Q_BQ), a.nl, a.B), dim3(512), 8 * Q_BKV * ROWB, s_dq,
+                       (const bf16*)a.qkv, (const bf16*)a.dctx, a.lse, a.dsum, (bf16*)a.dqkv, a.S, a.nl, qkv_bytes);
+  else
+    hipLaunchKernelGGL(attn_bwd_dq_kernel<1>, dim3(cdiv(a.S, Q_BQ), a.nl, a.B), dim3(256), 4 * Q_BKV * ROWB, s_dq,
+                       (const bf16*)a.qkv, (const bf16*)a.dctx, a.lse, a.dsum, (bf16*)a.dqkv, a.S, a.nl, qkv_bytes);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (two) {
     if ((e = hipEventRecord(join, s_dq)) != hipSuccess) return e;

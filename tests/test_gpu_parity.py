@@ -72,6 +72,15 @@ def test_bf16_multi_tile_block():
     print({k: f"{v[0]:.2e}" for k, v in report.items()})
 
 
+def test_bf16_many_query_blocks():
+    # 7 samples x 4 heads x 15 query blocks: enough blocks that attention takes its one-tile-per-step
+    # kernels (smaller cases above take the variants that split the key range over two wavefronts)
+    shape = I.LayerShape(512, 4, 1024, 1, 1, 0, 1800, 7, "bf16")
+    params, x, dy = _case(shape, 52)
+    gpu, ref, _ = run_both(shape, params, x, dy)
+    compare(gpu, ref, TOL["bf16"])
+
+
 def test_bf16_degenerate_sizes():
     # one token per sample (attention is the identity on V), and a single sample of 2 tokens
     for seq, batch, case in ((1, 5, 61), (2, 1, 62)):
