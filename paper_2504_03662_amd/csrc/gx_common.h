@@ -75,7 +75,7 @@ GX_DEVINL unsigned lds_addr(const char* p) { return (unsigned)(unsigned long)(ld
 template <int OFF>
 GX_DEVINL bf16x4 lds_read_tr_issue(unsigned addr) {
   bf16x4 r;
-  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF) : "memory");
   return r;
 }
 GX_DEVINL void lds_wait_all() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }

@@ -178,3 +178,29 @@ def test_bitwise_reproducible():
     assert np.array_equal(a["y"], b["y"]) and np.array_equal(a["dx"], b["dx"])
     for n in I.PARAM_NAMES:
         assert np.array_equal(a["grads"][n], b["grads"][n]), n
+
+
+def test_launch_timing_record():
+    """gx_prof_*: every launch site of one forward + backward shows up once, in launch order, with a
+    positive duration, and the record is cleared by the collect."""
+    from paper_2504_03662_amd import binding as gx
+    shape = I.LayerShape(256, 2, 512, 1, 1, 0, 64, 2, "bf16")
+    params, x, dy = _case(shape, 95)
+    layer = DeviceLayer(shape, params)
+    xd, dyd = to_device(x, "bf16"), to_device(dy, "bf16")
+    layer.forward(xd)
+    layer.backward(xd, dyd)
+    gx.prof_enable(True)
+    try:
+        layer.forward(xd)
+        fwd = gx.prof_collect()
+        layer.backward(xd, dyd)
+        bwd = gx.prof_collect()
+        assert gx.prof_collect() == []
+    finally:
+        gx.prof_enable(False)
+    G = gx.GX_KC_GEMM
+    assert [c for c, _ in fwd] == [gx.GX_KC_LN_FWD, G + 1, gx.GX_KC_ATTN_FWD, G + 2, gx.GX_KC_LN_FWD, G + 3, G + 2]
+    assert sorted(c for c, _ in bwd) == sorted([gx.GX_KC_COLSUM] * 4 + [gx.GX_KC_LN_BWD] * 4 + [gx.GX_KC_ATTN_BWD]
+                                               + [G + 25] * 4 + [G + 14] + [G + 10] * 3)
+    assert all(t > 0 for _, t in fwd + bwd)
