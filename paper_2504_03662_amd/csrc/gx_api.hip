@@ -210,7 +210,7 @@ hipError_t ln_params_p(bool bf, const void* dy, const void* x, const float* mean
 // shared by all calls of the process (calls from several host threads must not overlap).
 struct SideStream {
   bool tried = false, ok = false;
-  hipStream_t s = nullptr;
+  hipStream_t s = nullptr, s2 = nullptr;
   hipEvent_t fork[8];
   hipEvent_t join, attn_fork, attn_join;
 } g_side;
@@ -219,6 +219,7 @@ bool side_ready() {
   if (!g_side.tried) {
     g_side.tried = true;
     bool ok = hipStreamCreateWithFlags(&g_side.s, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipStreamCreateWithFlags(&g_side.s2, hipStreamNonBlocking) == hipSuccess;
     for (int i = 0; ok && i < 8; i++) ok = hipEventCreateWithFlags(&g_side.fork[i], hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&g_side.join, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&g_side.attn_fork, hipEventDisableTiming) == hipSuccess;
@@ -345,17 +346,20 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
   if (mlp) {
     const void* h1 = attn ? sv.h1 : x;
     // side: db2 needs only dy
-    if ((s = bias_grad(d, c, c.flags & GX_ROW_BIAS_MLP, dy, d.H, w.part, gr.b_fc2, fk.branch())) != GX_OK) return s;
-    // row-parallel FC2: weight gradient, then input gradient fused with GELU'
+    // row-parallel FC2: bias and weight gradients need only dy and saved activations: side
+    hipStream_t sd = fk.branch();
+    if ((s = bias_grad(d, c, c.flags & GX_ROW_BIAS_MLP, dy, d.H, w.part, gr.b_fc2, sd)) != GX_OK) return s;
     GemmArgs w2 = gargs(sv.act, dy, gr.w_fc2, d.Fl, d.H, d.T, d.Fl, d.H, d.H);
-    GX_TRY(gemm(d, LAY_TN, wg, w2, st));
+    GX_TRY(gemm(d, LAY_TN, wg, w2, sd));
+    // input gradient fused with GELU' on the caller's stream
     GemmArgs dz = gargs(dy, p.w_fc2, w.dz, d.T, d.Fl, d.H, d.H, d.H, d.Fl);
     dz.z = sv.z;
     GX_TRY(gemm(d, LAY_NT, EPI_DGELU, dz, st));
-    GX_TRY(colsum_p(d.bf, w.dz, (int)d.T, (int)d.Fl, w.part, gr.b_fc1, acc, fk.branch()));      // side: db1
-    // column-parallel FC1
+    // column-parallel FC1: bias and weight gradients on the side once dz exists
+    sd = fk.branch();
+    GX_TRY(colsum_p(d.bf, w.dz, (int)d.T, (int)d.Fl, w.part, gr.b_fc1, acc, sd));
     GemmArgs w1 = gargs(sv.y2, w.dz, gr.w_fc1, d.H, d.Fl, d.T, d.H, d.Fl, d.Fl);
-    GX_TRY(gemm(d, LAY_TN, wg, w1, st));
+    GX_TRY(gemm(d, LAY_TN, wg, w1, sd));
     GemmArgs dy2 = gargs(w.dz, p.w_fc1, w.dy2, d.T, d.H, d.Fl, d.Fl, d.Fl, d.H);
     GX_TRY(gemm(d, LAY_NT, EPI_STORE, dy2, st));
     // LayerNorm 2: parameter gradients on the side; input gradient (plus dy through the residual
@@ -384,12 +388,13 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     a.qkv = sv.qkv; a.ctx = sv.ctx; a.lse = sv.lse; a.dctx = w.dctx; a.dqkv = w.dqkv; a.dsum = w.dsum;
     a.B = (int)d.B; a.S = (int)d.S; a.nl = (int)d.nl; a.dh = (int)d.dh;
     { ProfScope ps(GX_KC_ATTN_BWD, st);
-    GX_TRY(d.bf ? attn_bwd_bf16(a, st, fk.side, g_side.attn_fork, g_side.attn_join) : attn_bwd_f32(a, st));
+    GX_TRY(d.bf ? attn_bwd_bf16(a, st, fk.side != st ? g_side.s2 : st, g_side.attn_fork, g_side.attn_join) : attn_bwd_f32(a, st));
     if (d.bf && fk.side != st) fk.used = true; }
     // column-parallel QKV
-    GX_TRY(colsum_p(d.bf, w.dqkv, (int)d.T, (int)(3 * d.Hl), w.part, gr.b_qkv, acc, fk.branch()));   // side: dbqkv
+    hipStream_t sq = fk.branch();
+    GX_TRY(colsum_p(d.bf, w.dqkv, (int)d.T, (int)(3 * d.Hl), w.part, gr.b_qkv, acc, sq));
     GemmArgs wq = gargs(sv.y1, w.dqkv, gr.w_qkv, d.H, 3 * d.Hl, d.T, d.H, 3 * d.Hl, 3 * d.Hl);
-    GX_TRY(gemm(d, LAY_TN, wg, wq, st));
+    GX_TRY(gemm(d, LAY_TN, wg, wq, sq));
     GemmArgs dy1 = gargs(w.dqkv, p.w_qkv, w.dy1, d.T, d.H, 3 * d.Hl, 3 * d.Hl, 3 * d.Hl, d.H);
     GX_TRY(gemm(d, LAY_NT, EPI_STORE, dy1, st));
     GX_TRY(ln_params_p(d.bf, w.dy1, x, sv.mean1, sv.rstd1, w.part, (int)d.T, (int)d.H, gr.ln1_g, gr.ln1_b, acc,
