@@ -41,7 +41,12 @@ def gemm_flops_by_class(sh, accumulate):
 # then WRITE_SIZE; commands and per-kernel readings in profiles/), scaled by what the same counters
 # read for --calibrate-copy's 256 MiB + 256 MiB elementwise copy.  The figure only holds for the
 # kernel source it was measured on: `source_sha256` is the hash of csrc/gemm_bf16.hip at that time.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # FETCH_SIZE x 1.9997 (copy calibration) + WRITE_SIZE x 1.0, averaged over the class's 4 launches per step:
+    # dW2, dW1 (256x256 tiles) 201.5 MB read + 67.1 MB written; dWo, dWqkv (128x128 tiles) 168.9 + 33.6 MB
+    ("C3", "gemm_tn_f32"): {"bytes_per_launch": 235.6e6, "algorithmic_bytes_per_launch": 109.1e6,
+                            "source_sha256": "f60e8b0c991d953b1bc987bf6eb3f4796594340f956b170a61d9b2b6d1b0241a"},
+}
 
 
 def measured_traffic(workload, kernel):
@@ -67,6 +72,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--serial", action="store_true",
+                    help="queue the backward pass on one stream (no side-stream overlap) in the timed region "
+                         "too; the per-kernel timing pass always runs that way")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain elementwise copy of 256 MiB (read) + 256 MiB (write), as the "
                          "known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -81,6 +89,7 @@ def main():
     from paper_2504_03662_amd.runtime import DeviceStack, one_f_one_b, to_device
 
     gx.lib()                                         # fails loudly when the HIP library is missing
+    gx.set_overlap(not args.serial)
     if not torch.cuda.is_available():
         sys.exit("bench.py needs an MI355X: no GPU is visible")
     shape, blocks, mbs = I.WORKLOADS[args.workload]
@@ -123,7 +132,12 @@ def main():
     tflops = flops / (ms * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if shape.dtype == "bf16" else PEAK_F32_TFLOPS
 
-    # per-kernel-class durations from HIP events on the launch stream, same work repeated
+    # per-kernel-class durations from HIP events on the launch stream, same work repeated with the
+    # backward pass queued serially: kernels that overlap share the chip, so only a kernel that has
+    # it alone can be held against the roofline
+    torch.cuda.synchronize()
+    gx.set_overlap(False)
+    step()
     gx.prof_enable(True)
     launches_per_step = None
     rec = []
@@ -133,6 +147,7 @@ def main():
         launches_per_step = len(got)
         rec += got
     gx.prof_enable(False)
+    gx.set_overlap(not args.serial)
     by = {}
     for c, t in rec:
         by.setdefault(c, []).append(t)
@@ -163,7 +178,8 @@ def main():
            "config": {"workload": args.workload, "hidden": shape.hidden, "heads": shape.heads, "ffn": shape.ffn,
                       "tp_attn": shape.tp_attn, "tp_ffn": shape.tp_ffn, "tp_rank": shape.tp_rank, "seq": shape.seq,
                       "micro_batch": shape.micro_batch, "blocks": blocks, "micro_batches": mbs,
-                      "schedule": "1F1B, full recompute" if pipelined else "fwd then bwd"},
+                      "schedule": "1F1B, full recompute" if pipelined else "fwd then bwd",
+                      "backward_overlap": not args.serial},
            "frac_of_mfma_peak": tflops / peak,
            "tokens_per_s_per_layer": shape.tokens * blocks * mbs / (ms * 1e-3),
            "model_tflop_per_step": flops / 1e12,

@@ -152,6 +152,12 @@ gx_status gx_layer_bwd(const gx_layer_cfg* cfg, const gx_params* params, const v
  * order, clears the record and returns the count (-1 on a HIP error).  At most 8192 launches are
  * recorded between collects; later ones are silently not timed.  Process-global state, not
  * thread-safe; leave it off in production loops (the event records perturb timing slightly). */
+/* gx_set_overlap(0) makes gx_layer_bwd queue everything on the caller's stream, in order, instead
+ * of forking part of it onto the library's side streams (the default, 1).  Results are identical
+ * either way; the serial form is for timing kernels one at a time (with gx_prof_* or a profiler),
+ * since kernels that overlap share the chip and their individual durations stretch. */
+gx_status gx_set_overlap(int on);
+
 enum { GX_KC_LN_FWD = 1, GX_KC_LN_BWD = 2, GX_KC_ATTN_FWD = 3, GX_KC_ATTN_BWD = 4, GX_KC_COLSUM = 5,
        GX_KC_GEMM = 100 };
 gx_status gx_prof_enable(int on);

@@ -21,7 +21,7 @@ GX_ACCUM_WGRAD, GX_RECOMPUTE = 16, 32
 PARAM_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
 EXPORTS = ("gx_layer_validate", "gx_layer_saved_bytes", "gx_layer_workspace_bytes", "gx_layer_fwd",
-           "gx_layer_bwd", "gx_status_str", "gx_version", "gx_prof_enable", "gx_prof_collect")
+           "gx_layer_bwd", "gx_status_str", "gx_version", "gx_prof_enable", "gx_prof_collect", "gx_set_overlap")
 GX_KC_LN_FWD, GX_KC_LN_BWD, GX_KC_ATTN_FWD, GX_KC_ATTN_BWD, GX_KC_COLSUM, GX_KC_GEMM = 1, 2, 3, 4, 5, 100
 
 
@@ -70,6 +70,8 @@ def lib():
         L.gx_status_str.restype = ctypes.c_char_p
         L.gx_version.argtypes = []
         L.gx_version.restype = ctypes.c_char_p
+        L.gx_set_overlap.argtypes = [ctypes.c_int]
+        L.gx_set_overlap.restype = ctypes.c_int
         L.gx_prof_enable.argtypes = [ctypes.c_int]
         L.gx_prof_enable.restype = ctypes.c_int
         L.gx_prof_collect.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float), ctypes.c_int]
@@ -152,3 +154,9 @@ def prof_collect(capacity=8192):
     if n < 0:
         raise RuntimeError("gx_prof_collect: HIP error")
     return [(int(cls[i]), float(ms[i])) for i in range(n)]
+
+
+def set_overlap(on):
+    st = lib().gx_set_overlap(int(bool(on)))
+    if st != GX_OK:
+        raise GxError(st, "gx_set_overlap")

@@ -215,7 +215,10 @@ struct SideStream {
   hipEvent_t join, attn_fork, attn_join;
 } g_side;
 
+bool g_overlap = true;     // gx_set_overlap
+
 bool side_ready() {
+  if (!g_overlap) return false;
   if (!g_side.tried) {
     g_side.tried = true;
     bool ok = hipStreamCreateWithFlags(&g_side.s, hipStreamNonBlocking) == hipSuccess;
@@ -519,6 +522,11 @@ const char* gx_status_str(gx_status s) {
 }
 
 const char* gx_version(void) { return "gx 0.1 (gfx950)"; }
+
+gx_status gx_set_overlap(int on) {
+  g_overlap = on != 0;
+  return GX_OK;
+}
 
 gx_status gx_prof_enable(int on) {
   if (on && !g_prof.ev) {
