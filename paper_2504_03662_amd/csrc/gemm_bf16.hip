@@ -111,7 +111,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
   constexpr int TM = BM / 64, TN = BN / 128;          // 32x32 accumulators per wave
   constexpr int WM = BM / 2, WN = BN / 4;             // wave tile
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
-  constexpr int SPLIT_KS = (LAY == LAY_NT) ? 1 : 0;
+  constexpr bool SPLIT_B = (LAY == LAY_NT);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 2, wn = wave & 3;
@@ -153,49 +153,70 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
   lb.issue(sb, 0, wave);
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's LDS-DMA has landed
   __syncthreads();
+  if (nk > 1) {
+    la.issue(sa + A_BYTES, BK, wave);
+    lb.issue(sb + B_BYTES, BK, wave);
+  }
+
+  // Fragments of sub-step ks+1 are requested before the products of sub-step ks are issued, also
+  // across tiles: the wait for the next tile's DMA and the workgroup barrier sit before the LAST
+  // sub-step's products, whose operands are already in registers, so the first fragments of the
+  // next tile are in flight while those products run and no wavefront starts a tile by waiting
+  // for LDS.  The tile after next is loaded into the buffer the barrier has just retired.
+  Frag fa[2][TM], fb[2][TN];
+  auto request = [&](const char* ta, const char* tb, int ks, int buf) {
+#pragma unroll
+    for (int mi = 0; mi < TM; mi++) {
+      if (A_K) fa[buf][mi].full = frag_k(ta, wm * WM + mi * 32 + l32, ks, grp);
+      else     frag_mn_issue<BM>(ta, wm * WM + mi * 32, ks, lane, fa[buf][mi]);
+    }
+#pragma unroll
+    for (int ni = 0; ni < TN; ni++) {
+      if (B_K) fb[buf][ni].full = frag_k(tb, wn * WN + ni * 32 + l32, ks, grp);
+      else     frag_mn_issue<BN>(tb, wn * WN + ni * 32, ks, lane, fb[buf][ni]);
+    }
+  };
+  request(sa, sb, 0, 0);
+  constexpr int KS = BK / 16;
+  static_assert(KS % 2 == 0, "fragment double buffer assumes an even number of sub-steps");
 
   for (int kt = 0; kt < nk; kt++) {
     const int cur = kt & 1;
-    // the prefetch of the next tile goes out in two halves (A now, B one sub-step later) so that
-    // the wavefronts of a SIMD do not all sit in the load issue queue at the top of the step
-    if (kt + 1 < nk) la.issue(sa + (cur ^ 1) * A_BYTES, (kt + 1) * BK, wave);
     const char* ta = sa + cur * A_BYTES;
     const char* tb = sb + cur * B_BYTES;
-    // fragments of sub-step ks+1 are requested before the products of sub-step ks are issued
-    Frag fa[2][TM], fb[2][TN];
-    auto request = [&](int ks, int buf) {
 #pragma unroll
-      for (int mi = 0; mi < TM; mi++) {
-        if (A_K) fa[buf][mi].full = frag_k(ta, wm * WM + mi * 32 + l32, ks, grp);
-        else     frag_mn_issue<BM>(ta, wm * WM + mi * 32, ks, lane, fa[buf][mi]);
-      }
-#pragma unroll
-      for (int ni = 0; ni < TN; ni++) {
-        if (B_K) fb[buf][ni].full = frag_k(tb, wn * WN + ni * 32 + l32, ks, grp);
-        else     frag_mn_issue<BN>(tb, wn * WN + ni * 32, ks, lane, fb[buf][ni]);
-      }
-    };
-    request(0, 0);
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ks++) {
+    for (int ks = 0; ks < KS; ks++) {
       const int buf = ks & 1;
       bf16x8 af[TM], bfr[TN];
-      if (!A_K || !B_K) lds_wait_all();
+      if (!A_K || !B_K || ks == KS - 1) lds_wait_all();
 #pragma unroll
       for (int mi = 0; mi < TM; mi++) af[mi] = A_K ? fa[buf][mi].full : frag_mn_finish(fa[buf][mi]);
 #pragma unroll
       for (int ni = 0; ni < TN; ni++) bfr[ni] = B_K ? fb[buf][ni].full : frag_mn_finish(fb[buf][ni]);
-      if (ks + 1 < BK / 16) request(ks + 1, buf ^ 1);
-      if (ks == SPLIT_KS && kt + 1 < nk) lb.issue(sb + (cur ^ 1) * B_BYTES, (kt + 1) * BK, wave);
+      if (ks + 1 < KS) {
+        request(ta, tb, ks + 1, buf ^ 1);
+      } else {
+        // every LDS read of this tile by this wavefront has completed (lds_wait_all above)
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        if (kt + 2 < nk) {
+          la.issue(sa + cur * A_BYTES, (kt + 2) * BK, wave);
+          if (!SPLIT_B) lb.issue(sb + cur * B_BYTES, (kt + 2) * BK, wave);
+        }
+        if (kt + 1 < nk) request(sa + (cur ^ 1) * A_BYTES, sb + (cur ^ 1) * B_BYTES, 0, buf ^ 1);
+      }
+      // the B half of a prefetch may go out one sub-step after the A half, so that the wavefronts
+      // of a SIMD do not all sit in the load issue queue at once
+      if (SPLIT_B && ks == 0 && kt >= 1 && kt + 1 < nk) lb.issue(sb + (cur ^ 1) * B_BYTES, (kt + 1) * BK, wave);
 #pragma unroll
       for (int mi = 0; mi < TM; mi++)
 #pragma unroll
         for (int ni = 0; ni < TN; ni++)
           acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ni], af[mi], acc[mi][ni], 0, 0, 0);
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    __syncthreads();
   }
+  // every wavefront passed the last barrier with all its LDS reads complete, so the tile buffers
+  // are free to serve as staging space below
 
   // epilogue.  The MFMAs were issued with the B fragment as the row operand, so accumulator
   // register v of lane l holds C[m = tile row l%32][n = 8*(v/4) + 4*(l/32) + v%4]: runs of 4

@@ -127,59 +127,86 @@ __global__ void __launch_bounds__(256) ln_bwd_dx_kernel(const T* __restrict__ dy
   }
 }
 
-// LayerNorm backward, parameter gradients, stage 1: block (bx, by) adds dy * xhat and dy over
-// rows [by*rpb, (by+1)*rpb) for 256 column chunks; partials go to part[0][by][col], part[1][by][col].
+// LayerNorm backward, parameter gradients, stage 1: workgroup (bx, by) adds dy * xhat and dy over
+// rows [by*rpb, (by+1)*rpb) for 64 column chunks of 16 B.  Its 4 wavefronts take every 4th row and
+// combine through LDS in wavefront order; partials go to part[0][by][col], part[1][by][col].
 template <typename T>
 __global__ void __launch_bounds__(256) ln_bwd_param_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                            const float* __restrict__ mean,
                                                            const float* __restrict__ rstd, int rows, int cols,
                                                            int rows_per_block, float* __restrict__ part) {
   constexpr int V = Vec<T>::N;
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c * V >= cols) return;
+  __shared__ float red[2][3][64][V + 1];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + lane;
+  const bool live = c * V < cols;
   const int r0 = blockIdx.y * rows_per_block, r1 = min(rows, r0 + rows_per_block);
   float dg[V], db[V];
 #pragma unroll
   for (int e = 0; e < V; e++) { dg[e] = 0.f; db[e] = 0.f; }
+  if (live) {
 #pragma unroll 4
-  for (int r = r0; r < r1; r++) {
-    float dv[V], xv[V];
-    load_vec<T>(dy + (size_t)r * cols + c * V, dv);
-    load_vec<T>(x + (size_t)r * cols + c * V, xv);
-    const float mu = mean[r], rs = rstd[r];
+    for (int r = r0 + w; r < r1; r += 4) {
+      float dv[V], xv[V];
+      load_vec<T>(dy + (size_t)r * cols + c * V, dv);
+      load_vec<T>(x + (size_t)r * cols + c * V, xv);
+      const float mu = mean[r], rs = rstd[r];
 #pragma unroll
-    for (int e = 0; e < V; e++) {
-      dg[e] += dv[e] * ((xv[e] - mu) * rs);
-      db[e] += dv[e];
+      for (int e = 0; e < V; e++) {
+        dg[e] += dv[e] * ((xv[e] - mu) * rs);
+        db[e] += dv[e];
+      }
     }
   }
-  float* pg = part + (size_t)blockIdx.y * cols + c * V;
-  float* pb = part + ((size_t)gridDim.y + blockIdx.y) * cols + c * V;
+  if (w) {
 #pragma unroll
-  for (int e = 0; e < V; e++) { pg[e] = dg[e]; pb[e] = db[e]; }
+    for (int e = 0; e < V; e++) { red[0][w - 1][lane][e] = dg[e]; red[1][w - 1][lane][e] = db[e]; }
+  }
+  __syncthreads();
+  if (w == 0 && live) {
+    float* pg = part + (size_t)blockIdx.y * cols + c * V;
+    float* pb = part + ((size_t)gridDim.y + blockIdx.y) * cols + c * V;
+#pragma unroll
+    for (int e = 0; e < V; e++) {
+      pg[e] = (dg[e] + red[0][0][lane][e]) + (red[0][1][lane][e] + red[0][2][lane][e]);
+      pb[e] = (db[e] + red[1][0][lane][e]) + (red[1][1][lane][e] + red[1][2][lane][e]);
+    }
+  }
 }
 
-// stage 1 of a column sum: block (bx, by) adds rows [by*rpb, (by+1)*rpb) of 16 B column chunks
+// stage 1 of a column sum: workgroup (bx, by) adds rows [by*rpb, (by+1)*rpb) of 64 column chunks of
+// 16 B; its 4 wavefronts take every 4th row and combine through LDS in wavefront order.
 template <typename T>
 __global__ void __launch_bounds__(256) colsum_kernel(const T* __restrict__ a, int rows, int cols, int ld,
                                                      int rows_per_block, float* __restrict__ part) {
   constexpr int V = Vec<T>::N;
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c * V >= cols) return;
+  __shared__ float red[3][64][V + 1];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + lane;
+  const bool live = c * V < cols;
   const int r0 = blockIdx.y * rows_per_block, r1 = min(rows, r0 + rows_per_block);
   float acc[V];
 #pragma unroll
   for (int e = 0; e < V; e++) acc[e] = 0.f;
+  if (live) {
 #pragma unroll 8
-  for (int r = r0; r < r1; r++) {
-    float v[V];
-    load_vec<T>(a + (size_t)r * ld + c * V, v);
+    for (int r = r0 + w; r < r1; r += 4) {
+      float v[V];
+      load_vec<T>(a + (size_t)r * ld + c * V, v);
 #pragma unroll
-    for (int e = 0; e < V; e++) acc[e] += v[e];
+      for (int e = 0; e < V; e++) acc[e] += v[e];
+    }
   }
-  float* p = part + (size_t)blockIdx.y * cols + c * V;
+  if (w) {
 #pragma unroll
-  for (int e = 0; e < V; e++) p[e] = acc[e];
+    for (int e = 0; e < V; e++) red[w - 1][lane][e] = acc[e];
+  }
+  __syncthreads();
+  if (w == 0 && live) {
+    float* p = part + (size_t)blockIdx.y * cols + c * V;
+#pragma unroll
+    for (int e = 0; e < V; e++) p[e] = (acc[e] + red[0][lane][e]) + (red[1][lane][e] + red[2][lane][e]);
+  }
 }
 
 // stage 2: out[c] (=|+=) sum over blocks.  A workgroup owns 64 columns; its 4 wavefronts take
@@ -249,7 +276,7 @@ hipError_t ln_bwd_params(bool is_bf16, const void* dy, const void* x, const floa
   if (rows <= 0 || cols <= 0 || cols % vec) return hipErrorInvalidValue;
   const int nblk = ln_bwd_blocks(rows);
   const int rpb = cdiv(rows, nblk);
-  dim3 gpar(cdiv(cols / vec, 256), nblk), block(256);
+  dim3 gpar(cdiv(cols / vec, 64), nblk), block(256);
   if (is_bf16)
     hipLaunchKernelGGL(ln_bwd_param_kernel<bf16>, gpar, block, 0, s, (const bf16*)dy, (const bf16*)x, mean, rstd, rows,
                        cols, rpb, part);
@@ -275,7 +302,7 @@ hipError_t colsum(bool is_bf16, const void* a, int rows, int cols, int ld, float
   if (rows <= 0 || cols <= 0 || cols % vec || ld % vec) return hipErrorInvalidValue;
   const int nblk = colsum_blocks(rows);
   const int rpb = cdiv(rows, nblk);
-  dim3 grid(cdiv(cols / vec, 256), nblk), block(256);
+  dim3 grid(cdiv(cols / vec, 64), nblk), block(256);
   if (is_bf16)
     hipLaunchKernelGGL(colsum_kernel<bf16>, grid, block, 0, s, (const bf16*)a, rows, cols, ld, rpb, part);
   else
