@@ -263,8 +263,17 @@ __global__ void __launch_bounds__(256) attn_dsum_kernel(const bf16* __restrict__
 }
 
 // ------------------------------------------------------------------------------- backward: dK, dV
-constexpr int KV_NW = 4, KV_BJ = 32 * KV_NW, KV_BI = 64;
+// A workgroup owns 128 key rows as 4 blocks of 32; each block belongs to a PAIR of wavefronts on
+// the same SIMD that split the work by output: wavefront `pair` (role V) forms S = Q K^T, the
+// probabilities P and dV += P^T dO; wavefront `pair + 4` (role K) forms dP = dO V^T, then
+// dS = P (dP - D) and dK += dS^T Q.  P crosses from one to the other through LDS as bf16, in the
+// accumulator's own lane layout (16 B per lane per half sub-tile, conflict-free).  Each wavefront
+// thus keeps one operand (K or V) and one 32 x 128 accumulator in registers, which leaves room
+// for two wavefronts per SIMD: the exponentials of one overlap the matrix work of the other.
+constexpr int KV_PAIRS = 4, KV_NW = 2 * KV_PAIRS, KV_BJ = 32 * KV_PAIRS, KV_BI = 64;
 constexpr int KV_STAGE = 2 * KV_BI * ROWB + 2 * KV_BI * 4;   // Q tile | dO tile | lse2[64] | D[64]
+constexpr int KV_PX = KV_PAIRS * 4 * 1024;                   // P exchange: [pair][sub-tile, half][lane] x 16 B
+constexpr int KV_SMEM = 2 * KV_STAGE + KV_PX;
 
 __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __restrict__ qkv,
                                                                   const bf16* __restrict__ dctx,
@@ -274,25 +283,27 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
                                                                   unsigned qkv_bytes, unsigned dctx_bytes) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const bool role_v = wave < KV_PAIRS;
+  const int pair = wave & (KV_PAIRS - 1);
   const int g = lane >> 5, l32 = lane & 31;
   const int h = blockIdx.y, b = blockIdx.z;
   const int Hl = nl * DH, ld = 3 * Hl;
-  const int j0 = blockIdx.x * KV_BJ, jw = j0 + wave * 32;
+  const int j0 = blockIdx.x * KV_BJ, jw = j0 + pair * 32;
   const unsigned eq = (unsigned)((size_t)b * S * ld + h * DH);
   const unsigned edo = (unsigned)((size_t)b * S * Hl + h * DH);
   const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(qkv), 0, qkv_bytes,
                                                                       0x00020000);
   const __amdgpu_buffer_rsrc_t rdo = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(dctx), 0, dctx_bytes,
                                                                        0x00020000);
-  bf16x8 kf[DH / 16], vf[DH / 16];
-  load_row_frags(qkv + eq + Hl, ld, jw + l32, S, g, kf);
-  load_row_frags(qkv + eq + 2 * Hl, ld, jw + l32, S, g, vf);
-  f32x16 dk[DH / 32], dv[DH / 32];
+  bf16x8 kvf[DH / 16];                      // role V: this block's K rows; role K: its V rows
+  load_row_frags(qkv + eq + (role_v ? Hl : 2 * Hl), ld, jw + l32, S, g, kvf);
+  f32x16 acc[DH / 32];                      // role V: dV; role K: dK
 #pragma unroll
-  for (int dt = 0; dt < DH / 32; dt++) { dk[dt] = zero16(); dv[dt] = zero16(); }
+  for (int dt = 0; dt < DH / 32; dt++) acc[dt] = zero16();
   const float scale = rsqrtf((float)DH), c2 = scale * LOG2E;
   const float* lrow = lse + ((size_t)b * nl + h) * S;
   const float* drow = dsum + ((size_t)b * nl + h) * S;
+  char* px = smem + 2 * KV_STAGE + pair * 4096 + lane * 16;
 
   const int t0 = j0 / KV_BI, nt = (S + KV_BI - 1) / KV_BI;     // query tiles t0 .. nt-1 see these keys
   auto stage_load = [&](int t) {
@@ -315,63 +326,86 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
     const char* qt = smem + (t & 1) * KV_STAGE;
     const char* dot = qt + KV_BI * ROWB;
     const float* aux = reinterpret_cast<const float*>(qt + 2 * KV_BI * ROWB);
+    const char* rows_of = role_v ? qt : dot;      // first product:  S = Q K^T   |  dP = dO V^T
+    const char* cols_of = role_v ? dot : qt;      // second product: dV += P^T dO |  dK += dS^T Q
     const int j = jw + l32;
-    // two independent 32-row query sub-tiles per step: the matrix work of one overlaps the
-    // exponentials of the other
-    if (t * KV_BI + KV_BI - 1 >= jw) {                    // wave-uniform: some query of the tile sees a key
-      f32x16 sacc[2], pacc[2];
+    const bool active = (t * KV_BI + KV_BI - 1 >= jw);    // pair-uniform: some query of the tile sees a key
+    f32x16 sp[2];
+    bf16x8 xf[2][2];
+    if (active) {
+      // two independent 32-row query sub-tiles per step
 #pragma unroll
       for (int sub = 0; sub < 2; sub++) {
-        sacc[sub] = zero16();
-        pacc[sub] = zero16();
+        sp[sub] = zero16();
 #pragma unroll
-        for (int s = 0; s < DH / 16; s++) {
-          sacc[sub] = MFMA(frag_rows(qt, 32 * sub + l32, s, g), kf[s], sacc[sub]);      // S[i][j]
-          pacc[sub] = MFMA(frag_rows(dot, 32 * sub + l32, s, g), vf[s], pacc[sub]);     // dP[i][j]
-        }
+        for (int s = 0; s < DH / 16; s++)
+          sp[sub] = MFMA(frag_rows(rows_of, 32 * sub + l32, s, g), kvf[s], sp[sub]);      // [query i][key j]
       }
+      if (role_v) {
 #pragma unroll
-      for (int sub = 0; sub < 2; sub++) {
-        const int it0 = t * KV_BI + 32 * sub;
-        const bool diag = (it0 < jw + 31);
+        for (int sub = 0; sub < 2; sub++) {
+          const int it0 = t * KV_BI + 32 * sub;
+          const bool diag = (it0 < jw + 31);
 #pragma unroll
-        for (int q4 = 0; q4 < 4; q4++) {
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(aux + 32 * sub + 8 * q4 + 4 * g);
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(aux + KV_BI + 32 * sub + 8 * q4 + 4 * g);
+          for (int q4 = 0; q4 < 4; q4++) {
+            const f32x4 l4 = *reinterpret_cast<const f32x4*>(aux + 32 * sub + 8 * q4 + 4 * g);
 #pragma unroll
-          for (int e = 0; e < 4; e++) {
-            const int v = 4 * q4 + e;
-            float p = __builtin_amdgcn_exp2f(sacc[sub][v] * c2 - l4[e]);
-            if (diag && j > it0 + 8 * q4 + 4 * g + e) p = 0.f;
-            sacc[sub][v] = p;
-            pacc[sub][v] = p * (pacc[sub][v] - d4[e]);
+            for (int e = 0; e < 4; e++) {
+              const int v = 4 * q4 + e;
+              float p = __builtin_amdgcn_exp2f(sp[sub][v] * c2 - l4[e]);
+              if (diag && j > it0 + 8 * q4 + 4 * g + e) p = 0.f;
+              sp[sub][v] = p;
+            }
           }
-        }
 #pragma unroll
-        for (int u = 0; u < 2; u++) {
-          const bf16x8 pf = pack_half(sacc[sub], u), dsf = pack_half(pacc[sub], u);
-#pragma unroll
-          for (int dt = 0; dt < DH / 32; dt++) {
-            dv[dt] = MFMA(pf, frag_cols(dot, 32 * sub + 16 * u, dt, lane), dv[dt]);   // dV[j][d] += P^T dO
-            dk[dt] = MFMA(dsf, frag_cols(qt, 32 * sub + 16 * u, dt, lane), dk[dt]);   // dK[j][d] += dS^T Q
+          for (int u = 0; u < 2; u++) {
+            xf[sub][u] = pack_half(sp[sub], u);
+            *reinterpret_cast<bf16x8*>(px + (2 * sub + u) * 1024) = xf[sub][u];
           }
         }
       }
+    }
+    __syncthreads();                                     // P of every pair is in LDS
+    if (active) {
+      if (!role_v) {
+#pragma unroll
+        for (int sub = 0; sub < 2; sub++) {
+          bf16x8 pb[2];
+#pragma unroll
+          for (int u = 0; u < 2; u++) pb[u] = *reinterpret_cast<const bf16x8*>(px + (2 * sub + u) * 1024);
+#pragma unroll
+          for (int q4 = 0; q4 < 4; q4++) {
+            const f32x4 d4 = *reinterpret_cast<const f32x4*>(aux + KV_BI + 32 * sub + 8 * q4 + 4 * g);
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+              const int v = 4 * q4 + e;
+              sp[sub][v] = (float)pb[v >> 3][v & 7] * (sp[sub][v] - d4[e]);
+            }
+          }
+#pragma unroll
+          for (int u = 0; u < 2; u++) xf[sub][u] = pack_half(sp[sub], u);
+        }
+      }
+#pragma unroll
+      for (int sub = 0; sub < 2; sub++)
+#pragma unroll
+        for (int u = 0; u < 2; u++)
+#pragma unroll
+          for (int dt = 0; dt < DH / 32; dt++)
+            acc[dt] = MFMA(xf[sub][u], frag_cols(cols_of, 32 * sub + 16 * u, dt, lane), acc[dt]);   // [key j][d]
     }
     WAIT_VM0();
     __syncthreads();
   }
   // accumulator register v of lane l is row 8 (v/4) + 4 g + v%4, column l%32 of its 32x32 tile
+  const float oscale = role_v ? 1.f : scale;
+  bf16* obase = dqkv + (size_t)b * S * ld + h * DH + (role_v ? 2 * Hl : Hl);
 #pragma unroll
   for (int dt = 0; dt < DH / 32; dt++)
 #pragma unroll
     for (int v = 0; v < 16; v++) {
-      const int j = jw + 8 * (v >> 2) + 4 * g + (v & 3);
-      if (j < S) {
-        bf16* row = dqkv + ((size_t)b * S + j) * ld + h * DH + 32 * dt + l32;
-        row[Hl] = (bf16)(dk[dt][v] * scale);
-        row[2 * Hl] = (bf16)dv[dt][v];
-      }
+      const int jr = jw + 8 * (v >> 2) + 4 * g + (v & 3);
+      if (jr < S) obase[(size_t)jr * ld + 32 * dt + l32] = (bf16)(acc[dt][v] * oscale);
     }
 }
 
@@ -533,7 +567,7 @@ hipError_t attn_bwd_bf16(const AttnArgs& a, hipStream_t s, hipStream_t s_dq, hip
   if (!attn_shape_ok(a)) return hipErrorInvalidValue;
   static bool configured = false;
   if (!configured) {
-    hipError_t e = set_smem(attn_bwd_dkv_kernel, 2 * KV_STAGE);
+    hipError_t e = set_smem(attn_bwd_dkv_kernel, KV_SMEM);
     if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<1>, 4 * Q_BKV * ROWB);
     if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<2>, 8 * Q_BKV * ROWB);
     if (e != hipSuccess) return e;
@@ -551,7 +585,7 @@ hipError_t attn_bwd_bf16(const AttnArgs& a, hipStream_t s, hipStream_t s_dq, hip
     if ((e = hipEventRecord(fork, s)) != hipSuccess) return e;
     if ((e = hipStreamWaitEvent(s_dq, fork, 0)) != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3(cdiv(a.S, KV_BJ), a.nl, a.B), dim3(64 * KV_NW), 2 * KV_STAGE, s,
+  hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3(cdiv(a.S, KV_BJ), a.nl, a.B), dim3(64 * KV_NW), KV_SMEM, s,
                      (const bf16*)a.qkv, (const bf16*)a.dctx, a.lse, a.dsum, (bf16*)a.dqkv, a.S, a.nl, qkv_bytes,
                      dctx_bytes);
   if ((e = hipGetLastError()) != hipSuccess) return e;

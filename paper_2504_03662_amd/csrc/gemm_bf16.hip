@@ -111,7 +111,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
   constexpr int TM = BM / 64, TN = BN / 128;          // 32x32 accumulators per wave
   constexpr int WM = BM / 2, WN = BN / 4;             // wave tile
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
-  constexpr bool SPLIT_B = (LAY == LAY_NT);
+  constexpr bool SPLIT_B = (LAY == LAY_NT) || BM == 256;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 2, wn = wave & 3;
