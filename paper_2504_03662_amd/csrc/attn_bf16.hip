@@ -69,6 +69,38 @@ GX_DEVINL bf16x8 frag_cols(const char* tile, int rbase, int dt, int lane) {
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// The same operand family through untracked transposing reads (see lds_read_tr_issue): the four
+// head-dim blocks of the 16 tile rows starting at 16 * GI, from per-lane addresses prepared by
+// cols_lane_offsets() plus the tile's LDS address.  The caller waits (lds_wait_le) and pins.
+GX_DEVINL void cols_lane_offsets(int lane, unsigned (&off)[2][DH / 32]) {
+  const int g = lane >> 5, s = lane & 15, hb = (lane >> 4) & 1;
+#pragma unroll
+  for (int half = 0; half < 2; half++) {
+    const int r = 4 * g + (s >> 2) + 8 * half;       // swz(16 k + r) == swz(r)
+#pragma unroll
+    for (int dt = 0; dt < DH / 32; dt++) {
+      const int d0 = 32 * dt + 16 * hb + 4 * (s & 3);
+      off[half][dt] = (unsigned)(r * ROWB + (((d0 >> 3) ^ swz(r)) << 4) + (d0 & 7) * 2);
+    }
+  }
+}
+struct ColFrags {
+  bf16x4 lo[DH / 32], hi[DH / 32];
+};
+template <int GI>
+GX_DEVINL void cols_issue(unsigned tile, const unsigned (&off)[2][DH / 32], ColFrags& f) {
+#pragma unroll
+  for (int dt = 0; dt < DH / 32; dt++) {
+    f.lo[dt] = lds_read_tr_issue<GI * 16 * ROWB>(tile + off[0][dt]);
+    f.hi[dt] = lds_read_tr_issue<GI * 16 * ROWB>(tile + off[1][dt]);
+  }
+}
+GX_DEVINL bf16x8 cols_get(ColFrags& f, int dt) {
+  lds_pin(f.lo[dt]);
+  lds_pin(f.hi[dt]);
+  return __builtin_shufflevector(f.lo[dt], f.hi[dt], 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
 // registers v = 8 h .. 8 h + 7 of an accumulator, rounded to bf16, as an MFMA operand
 GX_DEVINL bf16x8 pack_half(const f32x16& a, int h) {
   bf16x8 o;
@@ -304,18 +336,23 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
   const float* lrow = lse + ((size_t)b * nl + h) * S;
   const float* drow = dsum + ((size_t)b * nl + h) * S;
   char* px = smem + 2 * KV_STAGE + pair * 4096 + lane * 16;
+  unsigned coff[2][DH / 32];
+  cols_lane_offsets(lane, coff);
 
   const int t0 = j0 / KV_BI, nt = (S + KV_BI - 1) / KV_BI;     // query tiles t0 .. nt-1 see these keys
+  // lse and D rows of a query tile go to LDS by the same direct path, 4 B per lane (wavefront 0:
+  // lse, wavefront 1: D).  Rows beyond the sequence read as 0 everywhere (Q, dO, lse, D), which
+  // makes their probabilities 1 but their contributions to dV and dK exactly 0.
+  const __amdgpu_buffer_rsrc_t raux = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<float*>(wave == 0 ? lrow : drow), 0, (unsigned)S * 4u, 0x00020000);
   auto stage_load = [&](int t) {
     char* st = smem + (t & 1) * KV_STAGE;
     tile_load<KV_BI, KV_NW>(rq, eq, ld, t * KV_BI, S, st, wave, lane);
     tile_load<KV_BI, KV_NW>(rdo, edo, Hl, t * KV_BI, S, st + KV_BI * ROWB, wave, lane);
-    if (threadIdx.x < 128) {
-      float* aux = reinterpret_cast<float*>(st + 2 * KV_BI * ROWB);
-      const int i = t * KV_BI + (threadIdx.x & 63);
-      // rows beyond the sequence get lse = +inf, so their recomputed probabilities are exactly 0
-      if (threadIdx.x < 64) aux[threadIdx.x] = (i < S) ? lrow[i] * LOG2E : INFINITY;
-      else aux[threadIdx.x] = (i < S) ? drow[i] : 0.f;
+    if (wave < 2) {
+      const int i = t * KV_BI + lane;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(raux, (lds_void_ptr)(st + 2 * KV_BI * ROWB + wave * (KV_BI * 4)), 4,
+                                               (i < S) ? (unsigned)i * 4u : OOB, 0, 0, 0);
     }
   };
   stage_load(t0);
@@ -352,7 +389,7 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
 #pragma unroll
             for (int e = 0; e < 4; e++) {
               const int v = 4 * q4 + e;
-              float p = __builtin_amdgcn_exp2f(sp[sub][v] * c2 - l4[e]);
+              float p = __builtin_amdgcn_exp2f(sp[sub][v] * c2 - l4[e] * LOG2E);
               if (diag && j > it0 + 8 * q4 + 4 * g + e) p = 0.f;
               sp[sub][v] = p;
             }
@@ -365,8 +402,15 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
         }
       }
     }
-    __syncthreads();                                     // P of every pair is in LDS
+    // P of every pair is in LDS: wait for this wavefront's LDS writes only (the direct-to-LDS
+    // loads of the next tile stay in flight across this barrier)
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     if (active) {
+      // transposed fragments of the second product, two groups of 16 tile rows ahead of their use
+      const unsigned ct = lds_addr(cols_of);
+      ColFrags cf[2];
+      cols_issue<0>(ct, coff, cf[0]);
+      cols_issue<1>(ct, coff, cf[1]);
       if (!role_v) {
 #pragma unroll
         for (int sub = 0; sub < 2; sub++) {
@@ -386,13 +430,21 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
           for (int u = 0; u < 2; u++) xf[sub][u] = pack_half(sp[sub], u);
         }
       }
+      // [key j][d] += X^T (16 query rows per group) times the matching rows of dO or Q
+      lds_wait_le<2 * (DH / 32)>();
 #pragma unroll
-      for (int sub = 0; sub < 2; sub++)
+      for (int dt = 0; dt < DH / 32; dt++) acc[dt] = MFMA(xf[0][0], cols_get(cf[0], dt), acc[dt]);
+      cols_issue<2>(ct, coff, cf[0]);
+      lds_wait_le<2 * (DH / 32)>();
 #pragma unroll
-        for (int u = 0; u < 2; u++)
+      for (int dt = 0; dt < DH / 32; dt++) acc[dt] = MFMA(xf[0][1], cols_get(cf[1], dt), acc[dt]);
+      cols_issue<3>(ct, coff, cf[1]);
+      lds_wait_le<2 * (DH / 32)>();
 #pragma unroll
-          for (int dt = 0; dt < DH / 32; dt++)
-            acc[dt] = MFMA(xf[sub][u], frag_cols(cols_of, 32 * sub + 16 * u, dt, lane), acc[dt]);   // [key j][d]
+      for (int dt = 0; dt < DH / 32; dt++) acc[dt] = MFMA(xf[1][0], cols_get(cf[0], dt), acc[dt]);
+      lds_wait_all();
+#pragma unroll
+      for (int dt = 0; dt < DH / 32; dt++) acc[dt] = MFMA(xf[1][1], cols_get(cf[1], dt), acc[dt]);
     }
     WAIT_VM0();
     __syncthreads();

@@ -79,6 +79,9 @@ GX_DEVINL bf16x4 lds_read_tr_issue(unsigned addr) {
   return r;
 }
 GX_DEVINL void lds_wait_all() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+// wait until at most N LDS operations of this wavefront are outstanding (they complete in order)
+template <int N>
+GX_DEVINL void lds_wait_le() { asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory"); }
 GX_DEVINL void lds_pin(bf16x4& v) { asm volatile("" : "+v"(v)); }
 
 inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
