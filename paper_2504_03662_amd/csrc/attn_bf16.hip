@@ -13,6 +13,7 @@
 // other owns query rows and produces dQ.  Probabilities are recomputed from the saved
 // log-sum-exp.
 #include "gx_kernels.h"
+#include <type_traits>
 
 namespace gx {
 namespace {
@@ -301,11 +302,22 @@ __global__ void __launch_bounds__(256) attn_dsum_kernel(const bf16* __restrict__
 // dS = P (dP - D) and dK += dS^T Q.  P crosses from one to the other through LDS as bf16, in the
 // accumulator's own lane layout (16 B per lane per half sub-tile, conflict-free).  Each wavefront
 // thus keeps one operand (K or V) and one 32 x 128 accumulator in registers, which leaves room
-// for two wavefronts per SIMD: the exponentials of one overlap the matrix work of the other.
+// for two wavefronts per SIMD.
+//
+// The roles are skewed so that the exponentials of one run under the matrix work of the other and
+// one barrier per query tile suffices.  In phase n
+//   role V: S(n), P(n) -> LDS, dV += P(n)^T dO(n)
+//   role K: dS(n-1) from P(n-1) and the dP(n-1) it kept in registers, dK += dS(n-1)^T Q(n-1), then dP(n)
+// Tiles n+1 and n+2 are in flight meanwhile (a tile has two phases to arrive from HBM).
 constexpr int KV_PAIRS = 4, KV_NW = 2 * KV_PAIRS, KV_BJ = 32 * KV_PAIRS, KV_BI = 64;
-constexpr int KV_STAGE = 2 * KV_BI * ROWB + 2 * KV_BI * 4;   // Q tile | dO tile | lse2[64] | D[64]
+// LDS: Q tiles (+ their D rows) in a ring of 4 (tiles n-1 .. n+2), dO tiles (+ lse rows) in a ring
+// of 3 (tiles n .. n+2), two P exchange buffers, and a 256 B sink (see stage_load).
+constexpr int KV_NQ = 4, KV_NDO = 3;
+constexpr int KV_TILE = KV_BI * ROWB + KV_BI * 4;            // 64 rows of Q or dO | 64 floats
 constexpr int KV_PX = KV_PAIRS * 4 * 1024;                   // P exchange: [pair][sub-tile, half][lane] x 16 B
-constexpr int KV_SMEM = 2 * KV_STAGE + KV_PX;
+constexpr int KV_OFF_DO = KV_NQ * KV_TILE, KV_OFF_PX = KV_OFF_DO + KV_NDO * KV_TILE;
+constexpr int KV_OFF_SINK = KV_OFF_PX + 2 * KV_PX, KV_SMEM = KV_OFF_SINK + 256;
+constexpr int KV_LOADS = 5;                                  // direct-to-LDS loads per wavefront per tile
 
 __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __restrict__ qkv,
                                                                   const bf16* __restrict__ dctx,
@@ -335,120 +347,151 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
   const float scale = rsqrtf((float)DH), c2 = scale * LOG2E;
   const float* lrow = lse + ((size_t)b * nl + h) * S;
   const float* drow = dsum + ((size_t)b * nl + h) * S;
-  char* px = smem + 2 * KV_STAGE + pair * 4096 + lane * 16;
+  char* px = smem + KV_OFF_PX + pair * 4096 + lane * 16;
   unsigned coff[2][DH / 32];
   cols_lane_offsets(lane, coff);
 
   const int t0 = j0 / KV_BI, nt = (S + KV_BI - 1) / KV_BI;     // query tiles t0 .. nt-1 see these keys
   // lse and D rows of a query tile go to LDS by the same direct path, 4 B per lane (wavefront 0:
-  // lse, wavefront 1: D).  Rows beyond the sequence read as 0 everywhere (Q, dO, lse, D), which
-  // makes their probabilities 1 but their contributions to dV and dK exactly 0.
+  // lse, wavefront 1: D; the others send an out-of-range load to a sink so that every wavefront
+  // has the same number of loads in flight per tile).  Rows beyond the sequence read as 0
+  // everywhere (Q, dO, lse, D): their probabilities are 1 but their contributions to dV and dK
+  // are exactly 0, and whole tiles beyond the sequence may be requested harmlessly.
   const __amdgpu_buffer_rsrc_t raux = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<float*>(wave == 0 ? lrow : drow), 0, (unsigned)S * 4u, 0x00020000);
-  auto stage_load = [&](int t) {
-    char* st = smem + (t & 1) * KV_STAGE;
-    tile_load<KV_BI, KV_NW>(rq, eq, ld, t * KV_BI, S, st, wave, lane);
-    tile_load<KV_BI, KV_NW>(rdo, edo, Hl, t * KV_BI, S, st + KV_BI * ROWB, wave, lane);
-    if (wave < 2) {
-      const int i = t * KV_BI + lane;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(raux, (lds_void_ptr)(st + 2 * KV_BI * ROWB + wave * (KV_BI * 4)), 4,
-                                               (i < S) ? (unsigned)i * 4u : OOB, 0, 0, 0);
+  auto stage_load = [&](int t, int qslot, int dslot) {
+    char* qs = smem + qslot * KV_TILE;
+    char* ds = smem + KV_OFF_DO + dslot * KV_TILE;
+    tile_load<KV_BI, KV_NW>(rq, eq, ld, t * KV_BI, S, qs, wave, lane);
+    tile_load<KV_BI, KV_NW>(rdo, edo, Hl, t * KV_BI, S, ds, wave, lane);
+    const int i = t * KV_BI + lane;
+    char* ad = (wave == 0) ? ds + KV_BI * ROWB : (wave == 1) ? qs + KV_BI * ROWB : smem + KV_OFF_SINK;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(raux, (lds_void_ptr)ad, 4, (wave < 2 && i < S) ? (unsigned)i * 4u : OOB,
+                                             0, 0, 0);
+  };
+  // first product of a role over both 32-row query sub-tiles: [query i][key j]
+  f32x16 sp[2];
+  auto first_product = [&](const char* rows_of) {
+    bf16x8 fr[2][DH / 16];
+#pragma unroll
+    for (int s = 0; s < DH / 16; s++) fr[0][s] = frag_rows(rows_of, l32, s, g);
+#pragma unroll
+    for (int sub = 0; sub < 2; sub++) {
+      sp[sub] = zero16();
+#pragma unroll
+      for (int s = 0; s < DH / 16; s++) {
+        if (sub == 0) fr[1][s] = frag_rows(rows_of, 32 + l32, s, g);
+        sp[sub] = MFMA(fr[sub][s], kvf[s], sp[sub]);
+      }
     }
   };
-  stage_load(t0);
-  WAIT_VM0();
+  // second product: [key j][d] += X^T (16 query rows per group) times the matching rows of dO or Q,
+  // transposed fragments fetched two groups ahead of their use
+  auto second_product = [&](const char* cols_of, const bf16x8 (&xf)[2][2], ColFrags (&cf)[2]) {
+    const unsigned ct = lds_addr(cols_of);
+    lds_wait_le<2 * (DH / 32)>();
+#pragma unroll
+    for (int dt = 0; dt < DH / 32; dt++) acc[dt] = MFMA(xf[0][0], cols_get(cf[0], dt), acc[dt]);
+    cols_issue<2>(ct, coff, cf[0]);
+    lds_wait_le<2 * (DH / 32)>();
+#pragma unroll
+    for (int dt = 0; dt < DH / 32; dt++) acc[dt] = MFMA(xf[0][1], cols_get(cf[1], dt), acc[dt]);
+    cols_issue<3>(ct, coff, cf[1]);
+    lds_wait_le<2 * (DH / 32)>();
+#pragma unroll
+    for (int dt = 0; dt < DH / 32; dt++) acc[dt] = MFMA(xf[1][0], cols_get(cf[0], dt), acc[dt]);
+    lds_wait_all();
+#pragma unroll
+    for (int dt = 0; dt < DH / 32; dt++) acc[dt] = MFMA(xf[1][1], cols_get(cf[1], dt), acc[dt]);
+  };
+
+  stage_load(t0, 0, 0);
+  stage_load(t0 + 1, 1, 1);
+  __builtin_amdgcn_s_waitcnt(0x0F70 | KV_LOADS);                  // tile t0 has landed, t0 + 1 may be in flight
   __syncthreads();
-  for (int t = t0; t < nt; t++) {
-    if (t + 1 < nt) stage_load(t + 1);
-    const char* qt = smem + (t & 1) * KV_STAGE;
-    const char* dot = qt + KV_BI * ROWB;
-    const float* aux = reinterpret_cast<const float*>(qt + 2 * KV_BI * ROWB);
-    const char* rows_of = role_v ? qt : dot;      // first product:  S = Q K^T   |  dP = dO V^T
-    const char* cols_of = role_v ? dot : qt;      // second product: dV += P^T dO |  dK += dS^T Q
-    const int j = jw + l32;
-    const bool active = (t * KV_BI + KV_BI - 1 >= jw);    // pair-uniform: some query of the tile sees a key
-    f32x16 sp[2];
-    bf16x8 xf[2][2];
-    if (active) {
-      // two independent 32-row query sub-tiles per step
-#pragma unroll
-      for (int sub = 0; sub < 2; sub++) {
-        sp[sub] = zero16();
-#pragma unroll
-        for (int s = 0; s < DH / 16; s++)
-          sp[sub] = MFMA(frag_rows(rows_of, 32 * sub + l32, s, g), kvf[s], sp[sub]);      // [query i][key j]
-      }
-      if (role_v) {
-#pragma unroll
-        for (int sub = 0; sub < 2; sub++) {
-          const int it0 = t * KV_BI + 32 * sub;
-          const bool diag = (it0 < jw + 31);
-#pragma unroll
-          for (int q4 = 0; q4 < 4; q4++) {
-            const f32x4 l4 = *reinterpret_cast<const f32x4*>(aux + 32 * sub + 8 * q4 + 4 * g);
-#pragma unroll
-            for (int e = 0; e < 4; e++) {
-              const int v = 4 * q4 + e;
-              float p = __builtin_amdgcn_exp2f(sp[sub][v] * c2 - l4[e] * LOG2E);
-              if (diag && j > it0 + 8 * q4 + 4 * g + e) p = 0.f;
-              sp[sub][v] = p;
-            }
-          }
-#pragma unroll
-          for (int u = 0; u < 2; u++) {
-            xf[sub][u] = pack_half(sp[sub], u);
-            *reinterpret_cast<bf16x8*>(px + (2 * sub + u) * 1024) = xf[sub][u];
-          }
-        }
-      }
-    }
-    // P of every pair is in LDS: wait for this wavefront's LDS writes only (the direct-to-LDS
-    // loads of the next tile stay in flight across this barrier)
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    if (active) {
-      // transposed fragments of the second product, two groups of 16 tile rows ahead of their use
-      const unsigned ct = lds_addr(cols_of);
+  const int j = jw + l32;
+  // One loop per role (the branch is wavefront-uniform and both loops pass the same number of
+  // barriers), so that neither role carries the other's addresses and fragments in registers.
+  auto run = [&](auto role_tag) {
+    constexpr bool ROLE_V = decltype(role_tag)::value;
+    int qslot = 0, dslot = 0;                                     // ring positions of tile n
+#pragma unroll 1
+    for (int n = t0; n <= nt; n++) {
+      stage_load(n + 2, (qslot + 2) & (KV_NQ - 1), dslot == 0 ? 2 : dslot - 1);
+      const char* qt = smem + qslot * KV_TILE;                    // Q rows of tile n, then their D
+      const char* dot = smem + KV_OFF_DO + dslot * KV_TILE;       // dO rows of tile n, then their lse
+      bf16x8 xf[2][2];
       ColFrags cf[2];
-      cols_issue<0>(ct, coff, cf[0]);
-      cols_issue<1>(ct, coff, cf[1]);
-      if (!role_v) {
+      if (ROLE_V) {
+        if (n < nt && n * KV_BI + KV_BI - 1 >= jw) {              // pair-uniform: some query of tile n sees a key
+          const float* aux = reinterpret_cast<const float*>(dot + KV_BI * ROWB);
+          first_product(qt);                                      // S = Q K^T
+          const unsigned ct = lds_addr(dot);
+          cols_issue<0>(ct, coff, cf[0]);
+          cols_issue<1>(ct, coff, cf[1]);
 #pragma unroll
-        for (int sub = 0; sub < 2; sub++) {
-          bf16x8 pb[2];
+          for (int sub = 0; sub < 2; sub++) {
 #pragma unroll
-          for (int u = 0; u < 2; u++) pb[u] = *reinterpret_cast<const bf16x8*>(px + (2 * sub + u) * 1024);
+            for (int q4 = 0; q4 < 4; q4++) {
+              const f32x4 l4 = *reinterpret_cast<const f32x4*>(aux + 32 * sub + 8 * q4 + 4 * g);
 #pragma unroll
-          for (int q4 = 0; q4 < 4; q4++) {
-            const f32x4 d4 = *reinterpret_cast<const f32x4*>(aux + KV_BI + 32 * sub + 8 * q4 + 4 * g);
+              for (int e = 0; e < 4; e++)
+                sp[sub][4 * q4 + e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sp[sub][4 * q4 + e], c2, -LOG2E * l4[e]));
+            }
+            const int it0 = n * KV_BI + 32 * sub;
+            if (it0 < jw + 31) {                                  // the sub-tile touches the diagonal
 #pragma unroll
-            for (int e = 0; e < 4; e++) {
-              const int v = 4 * q4 + e;
-              sp[sub][v] = (float)pb[v >> 3][v & 7] * (sp[sub][v] - d4[e]);
+              for (int v = 0; v < 16; v++)
+                if (j > it0 + 8 * (v >> 2) + 4 * g + (v & 3)) sp[sub][v] = 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+              xf[sub][u] = pack_half(sp[sub], u);
+              *reinterpret_cast<bf16x8*>(px + (n & 1) * KV_PX + (2 * sub + u) * 1024) = xf[sub][u];
             }
           }
-#pragma unroll
-          for (int u = 0; u < 2; u++) xf[sub][u] = pack_half(sp[sub], u);
+          second_product(dot, xf, cf);                            // dV += P^T dO
         }
+      } else {
+        const int m = n - 1;                                      // tile whose dP this wavefront holds
+        if (m >= t0 && m * KV_BI + KV_BI - 1 >= jw) {
+          const char* qp = smem + ((qslot + KV_NQ - 1) & (KV_NQ - 1)) * KV_TILE;
+          const float* dp = reinterpret_cast<const float*>(qp + KV_BI * ROWB);
+          const unsigned ct = lds_addr(qp);
+          cols_issue<0>(ct, coff, cf[0]);
+          cols_issue<1>(ct, coff, cf[1]);
+#pragma unroll
+          for (int sub = 0; sub < 2; sub++) {
+            bf16x8 pb[2];
+#pragma unroll
+            for (int u = 0; u < 2; u++)
+              pb[u] = *reinterpret_cast<const bf16x8*>(px + (m & 1) * KV_PX + (2 * sub + u) * 1024);
+#pragma unroll
+            for (int q4 = 0; q4 < 4; q4++) {
+              const f32x4 d4 = *reinterpret_cast<const f32x4*>(dp + 32 * sub + 8 * q4 + 4 * g);
+#pragma unroll
+              for (int e = 0; e < 4; e++) {
+                const int v = 4 * q4 + e;
+                sp[sub][v] = (float)pb[v >> 3][v & 7] * (sp[sub][v] - d4[e]);
+              }
+            }
+#pragma unroll
+            for (int u = 0; u < 2; u++) xf[sub][u] = pack_half(sp[sub], u);
+          }
+          second_product(qp, xf, cf);                             // dK += dS^T Q
+        }
+        if (n < nt && n * KV_BI + KV_BI - 1 >= jw) first_product(dot);   // dP = dO V^T, used in the next phase
       }
-      // [key j][d] += X^T (16 query rows per group) times the matching rows of dO or Q
-      lds_wait_le<2 * (DH / 32)>();
-#pragma unroll
-      for (int dt = 0; dt < DH / 32; dt++) acc[dt] = MFMA(xf[0][0], cols_get(cf[0], dt), acc[dt]);
-      cols_issue<2>(ct, coff, cf[0]);
-      lds_wait_le<2 * (DH / 32)>();
-#pragma unroll
-      for (int dt = 0; dt < DH / 32; dt++) acc[dt] = MFMA(xf[0][1], cols_get(cf[1], dt), acc[dt]);
-      cols_issue<3>(ct, coff, cf[1]);
-      lds_wait_le<2 * (DH / 32)>();
-#pragma unroll
-      for (int dt = 0; dt < DH / 32; dt++) acc[dt] = MFMA(xf[1][0], cols_get(cf[0], dt), acc[dt]);
-      lds_wait_all();
-#pragma unroll
-      for (int dt = 0; dt < DH / 32; dt++) acc[dt] = MFMA(xf[1][1], cols_get(cf[1], dt), acc[dt]);
+      // tile n+1 has landed (n+2 may still be in flight) and this wavefront's LDS traffic is
+      // complete; then the workgroup meets
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(KV_LOADS) : "memory");
+      qslot = (qslot + 1) & (KV_NQ - 1);
+      dslot = (dslot == KV_NDO - 1) ? 0 : dslot + 1;
     }
-    WAIT_VM0();
-    __syncthreads();
-  }
+  };
+  if (role_v) run(std::true_type{});
+  else run(std::false_type{});
+  WAIT_VM0();   // requests for tiles beyond the last one (zero fill) must not outlive the workgroup's LDS
   // accumulator register v of lane l is row 8 (v/4) + 4 g + v%4, column l%32 of its 32x32 tile
   const float oscale = role_v ? 1.f : scale;
   bf16* obase = dqkv + (size_t)b * S * ld + h * DH + (role_v ? 2 * Hl : Hl);
