@@ -39,10 +39,11 @@
  *     accumulation); parameter gradients are always fp32.
  *   - Calls only enqueue work (a hipStream_t, or NULL for the default stream); they never allocate
  *     device memory, free or synchronise the host, and results are bitwise reproducible run to
- *     run.  gx_layer_bwd forks part of its work (bias / LayerNorm parameter gradients, one small
- *     weight gradient) onto a second stream that the library creates on first use (default
- *     priority, non-blocking) and joins it back with events before returning: to the caller
- *     everything is ordered on `hip_stream` as if it had run there.  That stream and the optional
+ *     run.  gx_layer_bwd forks part of its work (the weight gradients, the bias / LayerNorm
+ *     parameter reductions and one attention kernel) onto two streams that the library creates on
+ *     first use (default priority, non-blocking) and joins them back with events before returning:
+ *     to the caller everything is ordered on `hip_stream` as if it had run there
+ *     (gx_set_overlap(0) really runs it there).  Those streams with their events and the optional
  *     timing record of gx_prof_* are the only process-global state; because of them, calls from
  *     several host threads must not overlap.
  *   - Errors are returned as gx_status; nothing is thrown across the boundary.  Configuration and
