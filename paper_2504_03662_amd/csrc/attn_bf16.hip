@@ -55,22 +55,10 @@ GX_DEVINL bf16x8 frag_rows(const char* tile, int r, int s, int g) {
   const int c = (2 * s + g) ^ swz(r);
   return *reinterpret_cast<const bf16x8*>(tile + r * ROWB + (c << 4));
 }
-// MFMA operand whose 32 rows are head-dim columns 32 dt .. 32 dt + 31 and whose reduction index
-// runs over 16 tile rows starting at rbase, in the slot order of an accumulator column
-// (slot (g, e) <-> row rbase + 8 (e / 4) + 4 g + e % 4)
-GX_DEVINL bf16x8 frag_cols(const char* tile, int rbase, int dt, int lane) {
-  const int g = lane >> 5, s = lane & 15, hb = (lane >> 4) & 1;
-  const int r = rbase + 4 * g + (s >> 2);
-  const int d0 = 32 * dt + 16 * hb + 4 * (s & 3);
-  const int c = d0 >> 3, within = (d0 & 7) * 2;
-  const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-      (lds_bf16x4_ptr)(tile + r * ROWB + ((c ^ swz(r)) << 4) + within));
-  const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-      (lds_bf16x4_ptr)(tile + (r + 8) * ROWB + ((c ^ swz(r + 8)) << 4) + within));
-  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-}
-
-// The same operand family through untracked transposing reads (see lds_read_tr_issue): the four
+// MFMA operands whose 32 rows are head-dim columns 32 dt .. 32 dt + 31 and whose reduction index
+// runs over 16 tile rows starting at a multiple of 16, in the slot order of an accumulator column
+// (slot (g, e) <-> row 8 (e / 4) + 4 g + e % 4 of the group), come from transposing reads issued
+// as untracked asm (see lds_read_tr_issue): the four
 // head-dim blocks of the 16 tile rows starting at 16 * GI, from per-lane addresses prepared by
 // cols_lane_offsets() plus the tile's LDS address.  The caller waits (lds_wait_le) and pins.
 GX_DEVINL void cols_lane_offsets(int lane, unsigned (&off)[2][DH / 32]) {
@@ -127,6 +115,30 @@ GX_DEVINL void load_row_frags(const bf16* base, int ld, int row, int nrows, int 
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
 #define WAIT_VM0() __builtin_amdgcn_s_waitcnt(0x0F70)
 
+// acc[dt] += product of the transposed fragments of a 64-row tile (four groups of 16 rows at LDS
+// address `ct`) with xf[group]; COLS_A puts the transposed fragment first (rows of the result =
+// head-dim columns).  Groups 0 and 1 must have been issued into cf[0], cf[1] by the caller (as
+// early as it likes, to cover LDS latency with its own work); groups 2 and 3 are issued here, so
+// that two groups are always in flight.
+template <bool COLS_A>
+GX_DEVINL void tr_product4(f32x16 (&acc)[DH / 32], unsigned ct, const unsigned (&coff)[2][DH / 32],
+                           ColFrags (&cf)[2], const bf16x8 (&xf)[4]) {
+#define GX_TR_GROUP(U, BUF)                                                                              \
+  _Pragma("unroll") for (int dt = 0; dt < DH / 32; dt++)                                                 \
+      acc[dt] = COLS_A ? MFMA(cols_get(cf[BUF], dt), xf[U], acc[dt]) : MFMA(xf[U], cols_get(cf[BUF], dt), acc[dt])
+  lds_wait_le<2 * (DH / 32)>();
+  GX_TR_GROUP(0, 0);
+  cols_issue<2>(ct, coff, cf[0]);
+  lds_wait_le<2 * (DH / 32)>();
+  GX_TR_GROUP(1, 1);
+  cols_issue<3>(ct, coff, cf[1]);
+  lds_wait_le<2 * (DH / 32)>();
+  GX_TR_GROUP(2, 0);
+  lds_wait_all();
+  GX_TR_GROUP(3, 1);
+#undef GX_TR_GROUP
+}
+
 // ------------------------------------------------------------------------------- forward
 constexpr int F_BQ = 128, F_BKV = 64;
 
@@ -159,6 +171,8 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_fwd_kernel(const 
   for (int dt = 0; dt < DH / 32; dt++) o[dt] = zero16();
   float m = -INFINITY, lsum = 0.f;
   const float c2 = rsqrtf((float)DH) * LOG2E;
+  unsigned coff[2][DH / 32];
+  cols_lane_offsets(lane, coff);
 
   const int jend = min(S, i0 + F_BQ);                 // keys 0 .. jend-1 can be visible
   const int nt = (jend + ROWS - 1) / ROWS;
@@ -183,47 +197,52 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_fwd_kernel(const 
 #pragma unroll
         for (int s = 0; s < DH / 16; s++) sacc[jt] = MFMA(frag_rows(kt, 32 * jt + l32, s, g), qf[s], sacc[jt]);
       }
-      // online softmax for query column i = iw + l32 (base-2 exponentials)
+      // transposed V fragments of the first 32 keys travel while the softmax runs
+      const unsigned ct = lds_addr(vt);
+      ColFrags cf[2];
+      cols_issue<0>(ct, coff, cf[0]);
+      cols_issue<1>(ct, coff, cf[1]);
+      // online softmax for query column i = iw + l32 (base-2 exponentials, scale folded into the
+      // exponent's multiply-add)
       const int i = iw + l32;
-      const bool diag = (j0 + F_BKV - 1 > iw);
-      float mloc = -INFINITY;
+      if (j0 + F_BKV - 1 > iw) {                       // the tile touches the diagonal
+#pragma unroll
+        for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+          for (int v = 0; v < 16; v++)
+            if (j0 + 32 * jt + 8 * (v >> 2) + 4 * g + (v & 3) > i) sacc[jt][v] = -INFINITY;
+      }
+      float mloc = sacc[0][0];
 #pragma unroll
       for (int jt = 0; jt < 2; jt++)
 #pragma unroll
-        for (int v = 0; v < 16; v++) {
-          float sv = sacc[jt][v] * c2;
-          if (diag) {
-            const int j = j0 + 32 * jt + 8 * (v >> 2) + 4 * g + (v & 3);
-            if (j > i) sv = -INFINITY;
-          }
-          sacc[jt][v] = sv;
-          mloc = fmaxf(mloc, sv);
-        }
-      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+        for (int v = 0; v < 16; v++) mloc = fmaxf(mloc, sacc[jt][v]);
+      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64)) * c2;
       const float mnew = fmaxf(m, mloc);
-      const float alpha = __builtin_amdgcn_exp2f(m - mnew);
-      m = mnew;
+      if (__builtin_amdgcn_ballot_w64(mnew > m)) {     // wave-uniform: some row's running max moved
+        const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+        m = mnew;
+        lsum *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < DH / 32; dt++)
+#pragma unroll
+          for (int v = 0; v < 16; v++) o[dt][v] *= alpha;
+      }
       float psum = 0.f;
 #pragma unroll
       for (int jt = 0; jt < 2; jt++)
 #pragma unroll
         for (int v = 0; v < 16; v++) {
-          const float p = __builtin_amdgcn_exp2f(sacc[jt][v] - mnew);
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[jt][v], c2, -m));
           sacc[jt][v] = p;
           psum += p;
         }
-      lsum = lsum * alpha + psum;
+      lsum += psum;
+      // O^T += V^T P^T, 16 keys per group
+      bf16x8 pf[4];
 #pragma unroll
-      for (int dt = 0; dt < DH / 32; dt++)
-#pragma unroll
-        for (int v = 0; v < 16; v++) o[dt][v] *= alpha;
-      // O^T += V^T P^T, 16 keys per step
-#pragma unroll
-      for (int u = 0; u < 4; u++) {
-        const bf16x8 pf = pack_half(sacc[u >> 1], u & 1);
-#pragma unroll
-        for (int dt = 0; dt < DH / 32; dt++) o[dt] = MFMA(frag_cols(vt, 16 * u, dt, lane), pf, o[dt]);
-      }
+      for (int u = 0; u < 4; u++) pf[u] = pack_half(sacc[u >> 1], u & 1);
+      tr_product4<true>(o, ct, coff, cf, pf);
     }
     WAIT_VM0();
     __syncthreads();
@@ -385,26 +404,6 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
       }
     }
   };
-  // second product: [key j][d] += X^T (16 query rows per group) times the matching rows of dO or Q,
-  // transposed fragments fetched two groups ahead of their use
-  auto second_product = [&](const char* cols_of, const bf16x8 (&xf)[2][2], ColFrags (&cf)[2]) {
-    const unsigned ct = lds_addr(cols_of);
-    lds_wait_le<2 * (DH / 32)>();
-#pragma unroll
-    for (int dt = 0; dt < DH / 32; dt++) acc[dt] = MFMA(xf[0][0], cols_get(cf[0], dt), acc[dt]);
-    cols_issue<2>(ct, coff, cf[0]);
-    lds_wait_le<2 * (DH / 32)>();
-#pragma unroll
-    for (int dt = 0; dt < DH / 32; dt++) acc[dt] = MFMA(xf[0][1], cols_get(cf[1], dt), acc[dt]);
-    cols_issue<3>(ct, coff, cf[1]);
-    lds_wait_le<2 * (DH / 32)>();
-#pragma unroll
-    for (int dt = 0; dt < DH / 32; dt++) acc[dt] = MFMA(xf[1][0], cols_get(cf[0], dt), acc[dt]);
-    lds_wait_all();
-#pragma unroll
-    for (int dt = 0; dt < DH / 32; dt++) acc[dt] = MFMA(xf[1][1], cols_get(cf[1], dt), acc[dt]);
-  };
-
   stage_load(t0, 0, 0);
   stage_load(t0 + 1, 1, 1);
   __builtin_amdgcn_s_waitcnt(0x0F70 | KV_LOADS);                  // tile t0 has landed, t0 + 1 may be in flight
@@ -420,7 +419,7 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
       stage_load(n + 2, (qslot + 2) & (KV_NQ - 1), dslot == 0 ? 2 : dslot - 1);
       const char* qt = smem + qslot * KV_TILE;                    // Q rows of tile n, then their D
       const char* dot = smem + KV_OFF_DO + dslot * KV_TILE;       // dO rows of tile n, then their lse
-      bf16x8 xf[2][2];
+      bf16x8 xf[4];                                               // P or dS, 16 query rows per entry
       ColFrags cf[2];
       if (ROLE_V) {
         if (n < nt && n * KV_BI + KV_BI - 1 >= jw) {              // pair-uniform: some query of tile n sees a key
@@ -446,11 +445,11 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
             }
 #pragma unroll
             for (int u = 0; u < 2; u++) {
-              xf[sub][u] = pack_half(sp[sub], u);
-              *reinterpret_cast<bf16x8*>(px + (n & 1) * KV_PX + (2 * sub + u) * 1024) = xf[sub][u];
+              xf[2 * sub + u] = pack_half(sp[sub], u);
+              *reinterpret_cast<bf16x8*>(px + (n & 1) * KV_PX + (2 * sub + u) * 1024) = xf[2 * sub + u];
             }
           }
-          second_product(dot, xf, cf);                            // dV += P^T dO
+          tr_product4<false>(acc, ct, coff, cf, xf);              // dV[j][d] += P^T dO
         }
       } else {
         const int m = n - 1;                                      // tile whose dP this wavefront holds
@@ -476,9 +475,9 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
               }
             }
 #pragma unroll
-            for (int u = 0; u < 2; u++) xf[sub][u] = pack_half(sp[sub], u);
+            for (int u = 0; u < 2; u++) xf[2 * sub + u] = pack_half(sp[sub], u);
           }
-          second_product(qp, xf, cf);                             // dK += dS^T Q
+          tr_product4<false>(acc, ct, coff, cf, xf);              // dK[j][d] += dS^T Q
         }
         if (n < nt && n * KV_BI + KV_BI - 1 >= jw) first_product(dot);   // dP = dO V^T, used in the next phase
       }
@@ -537,6 +536,8 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_bwd_dq_kernel(con
   const float scale = rsqrtf((float)DH), c2 = scale * LOG2E;
   const float lse2 = lse[((size_t)b * nl + h) * S + ic] * LOG2E;
   const float dd = dsum[((size_t)b * nl + h) * S + ic];
+  unsigned coff[2][DH / 32];
+  cols_lane_offsets(lane, coff);
   f32x16 dq[DH / 32];
 #pragma unroll
   for (int dt = 0; dt < DH / 32; dt++) dq[dt] = zero16();
@@ -568,21 +569,29 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_bwd_dq_kernel(con
           pacc[jt] = MFMA(frag_rows(vt, 32 * jt + l32, s, g), dof[s], pacc[jt]);   // dP^T[j][i]
         }
       }
-      const bool diag = (j0 + Q_BKV - 1 > iw);
 #pragma unroll
       for (int jt = 0; jt < 2; jt++)
 #pragma unroll
         for (int v = 0; v < 16; v++) {
-          float p = __builtin_amdgcn_exp2f(sacc[jt][v] * c2 - lse2);
-          if (diag && j0 + 32 * jt + 8 * (v >> 2) + 4 * g + (v & 3) > i) p = 0.f;
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[jt][v], c2, -lse2));
           pacc[jt][v] = p * (pacc[jt][v] - dd);                                    // dS^T
         }
+      // the scores are dead: their registers take the first transposed K fragments
+      const unsigned ct = lds_addr(kt);
+      ColFrags cf[2];
+      cols_issue<0>(ct, coff, cf[0]);
+      cols_issue<1>(ct, coff, cf[1]);
+      if (j0 + Q_BKV - 1 > iw) {                       // the tile touches the diagonal
 #pragma unroll
-      for (int u = 0; u < 4; u++) {
-        const bf16x8 dsf = pack_half(pacc[u >> 1], u & 1);
+        for (int jt = 0; jt < 2; jt++)
 #pragma unroll
-        for (int dt = 0; dt < DH / 32; dt++) dq[dt] = MFMA(frag_cols(kt, 16 * u, dt, lane), dsf, dq[dt]);
+          for (int v = 0; v < 16; v++)
+            if (j0 + 32 * jt + 8 * (v >> 2) + 4 * g + (v & 3) > i) pacc[jt][v] = 0.f;
       }
+      bf16x8 dsf[4];
+#pragma unroll
+      for (int u = 0; u < 4; u++) dsf[u] = pack_half(pacc[u >> 1], u & 1);
+      tr_product4<true>(dq, ct, coff, cf, dsf);       // dQ^T[d][i] += K^T dS^T
     }
     WAIT_VM0();
     __syncthreads();
