@@ -78,6 +78,10 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain elementwise copy of 256 MiB (read) + 256 MiB (write), as the "
                          "known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--neighbours", action="store_true",
+                    help="also time the layer step's memory-bound neighbours at this workload's shapes (AdamW "
+                         "update of the rank's parameters, slicing the rank's shard out of the whole block and "
+                         "merging it back) and report them under \"neighbours\"")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU's share on one GPU: run it with --gpus 1 "
@@ -185,9 +189,67 @@ def main():
            "model_tflop_per_step": flops / 1e12,
            "roofline": roofline, "kernels": kernels}
 
+    if args.neighbours:
+        out["neighbours"] = neighbours(shape, stack, max(3, min(args.steps, 20)))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, case)
     print(json.dumps(out))
+
+
+def neighbours(shape, stack, reps):
+    """HBM-bound passes next to the layer step, timed with HIP events on the current stream and held
+    against the 8 TB/s HBM peak by their algorithmic bytes: AdamW reads w, m, v, g and writes w, m, v
+    (fp32) plus the bf16 copy = 30 B per element; a shard transition reads and writes each element of
+    the rank's shard once."""
+    import torch
+    from paper_2504_03662_amd import binding as gx
+    from paper_2504_03662_amd import inputs as I
+    dev = "cuda:0"
+    st = torch.cuda.current_stream().cuda_stream
+    n = sum(int(t.numel()) for t in stack.layers[0].params.values())
+    w, m, v, g = (torch.randn(n, device=dev) * s for s in (0.02, 1e-3, 1e-3, 1e-2))
+    v = v * v + 1e-8
+    out = torch.empty(n, dtype=torch.bfloat16, device=dev)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    step = [0]
+
+    def adam():
+        step[0] += 1
+        gx.adamw_step(n, w, m, v, g, out, gx.GX_BF16, step=step[0], lr=1e-4, weight_decay=0.01, stream=st)
+
+    t_adam = timed(adam)
+    res = {"adamw": {"elements": n, "ms": t_adam, "GB/s": 30.0 * n / t_adam / 1e6, "frac_of_hbm_peak": 30.0 * n / t_adam / 1e6 / 8000.0}}
+    del w, m, v, g, out
+    H, F = shape.hidden, shape.ffn
+    e = 2 if shape.dtype == "bf16" else 4
+    tdt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    dims = dict(ln1_g=(H,), ln1_b=(H,), w_qkv=(H, 3 * H), b_qkv=(3 * H,), w_o=(H, H), b_o=(H,),
+                ln2_g=(H,), ln2_b=(H,), w_fc1=(H, F), b_fc1=(F,), w_fc2=(F, H), b_fc2=(H,))
+    whole_bytes = sum(e * int(torch.Size(d).numel()) for d in dims.values())
+    if whole_bytes <= 8 << 30:
+        whole = {k: torch.zeros(d, dtype=tdt, device=dev) for k, d in dims.items()}
+        shard = stack.layers[0].params
+        cfg = gx.make_cfg(H, shape.heads, F, shape.tp_attn, shape.tp_ffn, shape.tp_rank, 1, 1,
+                          gx.GX_BF16 if shape.dtype == "bf16" else gx.GX_F32, 3)
+        sbytes = sum(int(t.numel()) * e for t in shard.values())
+        t_merge = timed(lambda: gx.params_merge(cfg, shard, whole, stream=st))
+        tmp = {k: torch.empty_like(t) for k, t in shard.items()}
+        t_slice = timed(lambda: gx.params_slice(cfg, whole, tmp, stream=st))
+        for name, t in (("params_merge", t_merge), ("params_slice", t_slice)):
+            res[name] = {"shard_bytes": sbytes, "ms": t, "GB/s": 2.0 * sbytes / t / 1e6,
+                         "frac_of_hbm_peak": 2.0 * sbytes / t / 1e6 / 8000.0}
+    return res
 
 
 def cpu_baseline(shape, case):

@@ -164,6 +164,54 @@ enum { GX_KC_LN_FWD = 1, GX_KC_LN_BWD = 2, GX_KC_ATTN_FWD = 3, GX_KC_ATTN_BWD = 
 gx_status gx_prof_enable(int on);
 int gx_prof_collect(int* kernel_class, float* ms, int capacity);
 
+/* ------------------------------------------------------------------------------------------
+ * Neighbours of the layer step: the optimizer update and the re-partitioning of a block's
+ * parameters between tensor-parallel degrees.  Both are memory-bound passes over device arrays.
+ * ------------------------------------------------------------------------------------------ */
+
+/* AdamW on a flat range of n elements (the paper's section 3 "Microsoft DeepSpeed" and section 5.2
+ * place partitioned fp32 optimizer states next to the layer compute; a rank passes the range it
+ * owns).  Per element, with g' = grad_scale * grad and t = step >= 1:
+ *     m = beta1 m + (1 - beta1) g';   v = beta2 v + (1 - beta2) g'^2
+ *     w = w - lr * ( (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps) + weight_decay * w )
+ * master, m, v : fp32 [n], updated in place;  grad : fp32 [n], read only;
+ * param_out    : optional copy of the new w in param_dtype (GX_BF16: round to nearest even;
+ *                GX_F32), [n]; NULL to skip.  Arithmetic is fp32.
+ * n = 0 is a no-op.  Errors: GX_ERR_NULL (cfg or a required array), GX_ERR_SHAPE (step < 1, a beta
+ * outside [0, 1), n >= 2^40), GX_ERR_DTYPE, GX_ERR_ALIGN (16 bytes), GX_ERR_ARCH, GX_ERR_LAUNCH. */
+typedef struct {
+  float lr, beta1, beta2, eps, weight_decay, grad_scale;
+  int32_t step;
+} gx_adamw_cfg;
+gx_status gx_adamw_step(const gx_adamw_cfg* cfg, size_t n, float* master, float* m, float* v, const float* grad,
+                        void* param_out, int param_dtype, void* hip_stream);
+
+/* Shard transitions (the paper's section 4, "Handling Transitions": going to model parallelism
+ * cuts a rank's shard out of whole weights, going back puts shards side by side again).
+ * `whole` holds the unsharded block (w_qkv [H, 3H] with column blocks [Q | K | V], w_o [H, H],
+ * w_fc1 [H, F], b_fc1 [F], w_fc2 [F, H]); `shard` holds one rank's tensors at cfg's degrees,
+ * laid out as gx_layer_fwd takes them.  The rank is tp_rank % tp_attn for the attention half and
+ * tp_rank % tp_ffn for the feed-forward half.
+ *   gx_params_slice : shard <- the rank's part of whole   (whole is read, shard written)
+ *   gx_params_merge : whole <- shard, in the rank's place (shard is read; other ranks' parts of
+ *                     whole are left untouched)
+ * LayerNorm parameters and the row-parallel biases b_o, b_fc2 are whole on every rank and are
+ * copied as they are.  cfg->flags selects the halves (GX_PHASE_*); cfg->dtype is the element type
+ * of every tensor, so the same calls move fp32 master weights, moments or gradients.  Only
+ * hidden, heads, ffn, tp_*, dtype and the phase bits of cfg are used (seq and micro_batch are
+ * ignored, and the layer kernels' size limits do not apply), but H/tp_attn and F/tp_ffn must be
+ * multiples of 16 bytes' worth of elements.  Source and destination must not overlap.
+ * Errors: GX_ERR_NULL, GX_ERR_SHAPE, GX_ERR_DIVIS, GX_ERR_DTYPE, GX_ERR_ALIGN, GX_ERR_FLAGS,
+ * GX_ERR_ARCH, GX_ERR_LAUNCH; checks happen before anything is enqueued. */
+typedef struct {
+  void *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_o, *b_o;
+  void *ln2_g, *ln2_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
+} gx_params_out;
+gx_status gx_params_slice(const gx_layer_cfg* cfg, const gx_params* whole, const gx_params_out* shard,
+                          void* hip_stream);
+gx_status gx_params_merge(const gx_layer_cfg* cfg, const gx_params* shard, const gx_params_out* whole,
+                          void* hip_stream);
+
 /* Static strings; never NULL. */
 const char* gx_status_str(gx_status s);
 const char* gx_version(void);

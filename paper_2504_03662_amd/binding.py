@@ -21,7 +21,8 @@ GX_ACCUM_WGRAD, GX_RECOMPUTE = 16, 32
 PARAM_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
 EXPORTS = ("gx_layer_validate", "gx_layer_saved_bytes", "gx_layer_workspace_bytes", "gx_layer_fwd",
-           "gx_layer_bwd", "gx_status_str", "gx_version", "gx_prof_enable", "gx_prof_collect", "gx_set_overlap")
+           "gx_layer_bwd", "gx_status_str", "gx_version", "gx_prof_enable", "gx_prof_collect", "gx_set_overlap",
+           "gx_adamw_step", "gx_params_slice", "gx_params_merge")
 GX_KC_LN_FWD, GX_KC_LN_BWD, GX_KC_ATTN_FWD, GX_KC_ATTN_BWD, GX_KC_COLSUM, GX_KC_GEMM = 1, 2, 3, 4, 5, 100
 
 
@@ -36,6 +37,15 @@ class Params(ctypes.Structure):
 
 class Grads(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in PARAM_NAMES]
+
+
+class ParamsOut(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in PARAM_NAMES]
+
+
+class AdamWCfg(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_float) for n in ("lr", "beta1", "beta2", "eps", "weight_decay", "grad_scale")] + \
+               [("step", ctypes.c_int32)]
 
 
 class GxError(RuntimeError):
@@ -76,6 +86,12 @@ def lib():
         L.gx_prof_enable.restype = ctypes.c_int
         L.gx_prof_collect.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float), ctypes.c_int]
         L.gx_prof_collect.restype = ctypes.c_int
+        L.gx_adamw_step.argtypes = [ctypes.POINTER(AdamWCfg), ctypes.c_size_t, P, P, P, P, P, ctypes.c_int, P]
+        L.gx_adamw_step.restype = ctypes.c_int
+        L.gx_params_slice.argtypes = [ctypes.POINTER(LayerCfg), ctypes.POINTER(Params), ctypes.POINTER(ParamsOut), P]
+        L.gx_params_slice.restype = ctypes.c_int
+        L.gx_params_merge.argtypes = [ctypes.POINTER(LayerCfg), ctypes.POINTER(Params), ctypes.POINTER(ParamsOut), P]
+        L.gx_params_merge.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -160,3 +176,31 @@ def set_overlap(on):
     st = lib().gx_set_overlap(int(bool(on)))
     if st != GX_OK:
         raise GxError(st, "gx_set_overlap")
+
+
+def adamw_step(n, master, m, v, grad, param_out=None, param_dtype=GX_BF16, *, step, lr, beta1=0.9, beta2=0.999,
+               eps=1e-8, weight_decay=0.0, grad_scale=1.0, stream=0, check=True):
+    c = AdamWCfg(lr, beta1, beta2, eps, weight_decay, grad_scale, step)
+    st = lib().gx_adamw_step(ctypes.byref(c), int(n), _ptr(master), _ptr(m), _ptr(v), _ptr(grad), _ptr(param_out),
+                             int(param_dtype), ctypes.c_void_p(stream))
+    if check and st != GX_OK:
+        raise GxError(st, "gx_adamw_step")
+    return int(st)
+
+
+def params_slice(cfg, whole, shard, stream=0, check=True):
+    w = _struct(Params, whole)
+    s = _struct(ParamsOut, shard)
+    st = lib().gx_params_slice(ctypes.byref(cfg), ctypes.byref(w), ctypes.byref(s), ctypes.c_void_p(stream))
+    if check and st != GX_OK:
+        raise GxError(st, "gx_params_slice")
+    return int(st)
+
+
+def params_merge(cfg, shard, whole, stream=0, check=True):
+    s = _struct(Params, shard)
+    w = _struct(ParamsOut, whole)
+    st = lib().gx_params_merge(ctypes.byref(cfg), ctypes.byref(s), ctypes.byref(w), ctypes.c_void_p(stream))
+    if check and st != GX_OK:
+        raise GxError(st, "gx_params_merge")
+    return int(st)

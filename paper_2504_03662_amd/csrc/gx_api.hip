@@ -6,6 +6,19 @@
 
 #include <string.h>
 
+namespace gx {
+bool device_is_gfx950() {
+  static int cached = -1;     // per process; the library targets a single architecture
+  if (cached < 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return false;
+    cached = (strncmp(prop.gcnArchName, "gfx950", 6) == 0) ? 1 : 0;
+  }
+  return cached == 1;
+}
+}  // namespace gx
+
 namespace {
 
 using namespace gx;
@@ -143,16 +156,7 @@ gx_status validate(const gx_layer_cfg* c) {
 
 bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
 
-gx_status check_arch() {
-  static int cached = -1;     // per process; the library targets a single architecture
-  if (cached < 0) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return GX_ERR_ARCH;
-    cached = (strncmp(prop.gcnArchName, "gfx950", 6) == 0) ? 1 : 0;
-  }
-  return cached == 1 ? GX_OK : GX_ERR_ARCH;
-}
+gx_status check_arch() { return device_is_gfx950() ? GX_OK : GX_ERR_ARCH; }
 
 #define GX_TRY(expr)                              \
   do {                                            \

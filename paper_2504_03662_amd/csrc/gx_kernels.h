@@ -4,6 +4,9 @@
 
 namespace gx {
 
+// true when the current device is the architecture this library is built for (cached per process)
+bool device_is_gfx950();
+
 // C[M,N] = op(A) * op(B), all matrices row-major with leading dimensions in elements.
 //   NN: A is [M,K], B is [K,N]      (forward: activations times "in x out" weights)
 //   NT: A is [M,K], B is [N,K]      (input gradient: dY times W^T, reduction over W's columns)

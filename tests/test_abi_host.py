@@ -80,3 +80,32 @@ def test_entry_points_check_pointers_before_touching_the_gpu(lib):
     assert gx.layer_bwd(c, ptrs, 4096, 4096, 4096, {}, 4096, 4096, check=False) == 1        # NULL grads
     with pytest.raises(gx.GxError):
         gx.layer_fwd(_cfg(flags=0), ptrs, 4096, 4096, None, None, 4096, None)
+
+
+def test_adamw_checks_arguments_before_touching_the_gpu(lib):
+    kw = dict(step=1, lr=1e-3)
+    assert gx.adamw_step(0, None, None, None, None, check=False, **kw) == gx.GX_OK          # n = 0: no-op
+    assert gx.adamw_step(8, None, 4096, 4096, 4096, check=False, **kw) == 1                  # NULL master
+    assert gx.adamw_step(8, 4096, 4096, 4096, 4096 + 8, check=False, **kw) == 5              # misaligned grad
+    assert gx.adamw_step(8, 4096, 4096, 4096, 4096, check=False, step=0, lr=1e-3) == 2       # steps start at 1
+    assert gx.adamw_step(8, 4096, 4096, 4096, 4096, check=False, step=1, lr=1e-3, beta2=1.0) == 2
+    assert gx.adamw_step(8, 4096, 4096, 4096, 4096, 4096, 7, check=False, **kw) == 4         # unknown output dtype
+
+
+def test_shard_transitions_check_arguments_before_touching_the_gpu(lib):
+    ptrs = {n: 4096 for n in gx.PARAM_NAMES}
+    c = _cfg()
+    assert gx.params_slice(c, {}, ptrs, check=False) == 1                                    # NULL tensors
+    assert gx.params_merge(c, ptrs, {**ptrs, "w_fc2": None}, check=False) == 1
+    # tensors of a half that is not selected may be NULL
+    assert gx.params_slice(_cfg(flags=gx.GX_PHASE_ATTN), {**ptrs, "w_fc1": None}, ptrs, check=False) != 1
+    assert gx.params_slice(_cfg(flags=0), ptrs, ptrs, check=False) == 6
+    assert gx.params_slice(_cfg(tp_attn=3), ptrs, ptrs, check=False) == 3
+    assert gx.params_slice(_cfg(dtype=9), ptrs, ptrs, check=False) == 4
+    assert gx.params_slice(_cfg(hidden=0), ptrs, ptrs, check=False) == 2
+    assert gx.params_slice(c, {**ptrs, "w_o": 4096 + 2}, ptrs, check=False) == 5
+    # bf16 with H / tp_attn = 4 elements is less than one 16-byte piece
+    assert gx.params_slice(_cfg(hidden=32, heads=8, ffn=64, tp_attn=8, tp_ffn=1), ptrs, ptrs, check=False) == 3
+    # head dim 64 and other sizes the layer kernels reject are fine for the copies (no GPU here: the
+    # call gets as far as the device check)
+    assert gx.params_slice(_cfg(hidden=2048, heads=32), ptrs, ptrs, check=False) in (7, 0)
