@@ -1,0 +1,57 @@
+"""Pins for the brute-force plan oracle: special cases whose answer is known without any search."""
+import numpy as np
+
+from oracle import plan as P
+
+
+def _rand(L, S, seed):
+    rng = np.random.default_rng(seed)
+    time = rng.uniform(1.0, 5.0, (L, S)).tolist()
+    mem = rng.uniform(1.0, 9.0, (L, S)).tolist()
+    sw = rng.uniform(0.1, 1.0, (S, S))
+    np.fill_diagonal(sw, 0.0)
+    return time, mem, sw.tolist()
+
+
+def test_unconstrained_without_switch_cost_is_per_layer_argmin():
+    time, mem, _ = _rand(5, 3, 1)
+    choice, t, m = P.brute_force_plan(time, mem, None, budget=1e9)
+    assert list(choice) == [int(np.argmin(row)) for row in time]
+    assert abs(t - sum(min(row) for row in time)) < 1e-12
+
+
+def test_tight_budget_forces_least_memory():
+    time, mem, sw = _rand(4, 3, 2)
+    least = sum(min(row) for row in mem)
+    choice, t, m = P.brute_force_plan(time, mem, sw, budget=least * (1 + 1e-12))
+    assert list(choice) == [int(np.argmin(row)) for row in mem]
+    assert P.brute_force_plan(time, mem, sw, budget=least * 0.999) is None
+
+
+def test_prohibitive_switch_cost_gives_a_uniform_plan():
+    time, mem, _ = _rand(5, 3, 3)
+    S = 3
+    sw = [[0.0 if a == b else 1e6 for b in range(S)] for a in range(S)]
+    choice, t, m = P.brute_force_plan(time, mem, sw, budget=1e9)
+    assert len(set(choice)) == 1
+    col = int(np.argmin(np.sum(np.array(time), axis=0)))
+    assert choice[0] == col and abs(t - np.sum(np.array(time)[:, col])) < 1e-12
+
+
+def test_hand_worked_example():
+    # two strategies: 0 = fast but heavy (2 ms, 6 units), 1 = slow but light (3 ms, 2 units);
+    # three layers, budget 12 units, switching costs 0.4 ms.
+    # all fast = 18 units (no); two fast = 14 (no); one fast + two slow = 10 units (fits), 8 ms + switches:
+    # fast at an end -> one switch (8.4 ms), fast in the middle -> two (8.8 ms); all slow = 9 ms.
+    time = [[2.0, 3.0]] * 3
+    mem = [[6.0, 2.0]] * 3
+    sw = [[0.0, 0.4], [0.4, 0.0]]
+    choice, t, m = P.brute_force_plan(time, mem, sw, budget=12.0)
+    assert choice == (0, 1, 1) and abs(t - 8.4) < 1e-12 and m == 10.0      # ties broken lexicographically
+    # a quantum of 4 rounds the light layers up to 4 units: 6 + 4 + 4 = 14 no longer fits, all slow does
+    choice, t, m = P.brute_force_plan(time, mem, sw, budget=12.0, quantum=4.0)
+    assert choice == (1, 1, 1) and abs(t - 9.0) < 1e-12 and m == 12.0
+
+
+def test_round_up():
+    assert P.round_up(5.0, 0) == 5.0 and P.round_up(5.0, 4.0) == 8.0 and P.round_up(8.0, 4.0) == 8.0
