@@ -68,7 +68,8 @@ typedef enum {
   GX_ERR_ALIGN = 5,     /* a pointer is not 16-byte aligned */
   GX_ERR_FLAGS = 6,     /* no phase selected, or unknown flag bits */
   GX_ERR_ARCH = 7,      /* the current device is not gfx950 */
-  GX_ERR_LAUNCH = 8     /* the HIP runtime refused a launch; see hipGetLastError */
+  GX_ERR_LAUNCH = 8,    /* the HIP runtime refused a launch; see hipGetLastError */
+  GX_ERR_INFEASIBLE = 9 /* gx_plan_search: no assignment fits the memory budget */
 } gx_status;
 
 typedef enum { GX_F32 = 0, GX_BF16 = 1 } gx_dtype;
@@ -211,6 +212,38 @@ gx_status gx_params_slice(const gx_layer_cfg* cfg, const gx_params* whole, const
                           void* hip_stream);
 gx_status gx_params_merge(const gx_layer_cfg* cfg, const gx_params* shard, const gx_params_out* whole,
                           void* hip_stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Layer-wise strategy plan (host only, no GPU involved).  The paper's strategy selector, in its
+ * discovery phase (section 3, "Dynamic Strategy Selector"; section 2, "Layer-Specific Parallelism
+ * Optimization"), prunes the candidate strategies with a decision tree and then runs a dynamic
+ * program over the layers "given a performance model"; neither the model nor the recurrence is
+ * printed, so the problem solved here is the plainest one of that shape:
+ *     choose one of `strategies` per layer so that the layers' memories (each first rounded up
+ *     to a multiple of mem_quantum_bytes when that is > 0) sum to at most mem_budget_bytes,
+ *     minimising  sum_l time_ms[l][c_l] + sum_{l>0} switch_ms[c_{l-1}][c_l].
+ * The cost table is what a sweep of gx_layer_fwd / gx_layer_bwd over shard shapes measures.
+ * Pruning: strategies that cannot fit beside the other layers' least memories; without switching
+ * costs also strategies that another one beats or equals in both time and memory.  Search: exact
+ * dynamic program whose state is the last layer's strategy with a Pareto frontier of (memory,
+ * time); ties in total time go to less memory.
+ * All pointers are HOST pointers owned by the caller; `choice` receives `layers` strategy indices.
+ * Errors: GX_ERR_NULL, GX_ERR_SHAPE (sizes <= 0 or > 4096 layers / 1024 strategies, negative or
+ * non-finite costs, or a frontier beyond 4 M points: use a coarser quantum), GX_ERR_INFEASIBLE. */
+typedef struct {
+  int32_t layers, strategies;
+  const double* time_ms;     /* [layers][strategies] */
+  const double* mem_bytes;   /* [layers][strategies] */
+  const double* switch_ms;   /* [strategies][strategies], diagonal ignored; NULL: switching is free */
+  double mem_budget_bytes;
+  double mem_quantum_bytes;  /* 0: memories are used as given */
+} gx_plan_problem;
+typedef struct {
+  double total_ms, total_mem_bytes;   /* of the returned plan (memory after rounding) */
+  int64_t pruned;                      /* (layer, strategy) pairs removed before the search */
+  int64_t frontier_peak;               /* largest Pareto frontier met */
+} gx_plan_result;
+gx_status gx_plan_search(const gx_plan_problem* problem, int32_t* choice, gx_plan_result* result);
 
 /* Static strings; never NULL. */
 const char* gx_status_str(gx_status s);

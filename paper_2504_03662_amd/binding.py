@@ -22,7 +22,7 @@ PARAM_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
 EXPORTS = ("gx_layer_validate", "gx_layer_saved_bytes", "gx_layer_workspace_bytes", "gx_layer_fwd",
            "gx_layer_bwd", "gx_status_str", "gx_version", "gx_prof_enable", "gx_prof_collect", "gx_set_overlap",
-           "gx_adamw_step", "gx_params_slice", "gx_params_merge")
+           "gx_adamw_step", "gx_params_slice", "gx_params_merge", "gx_plan_search")
 GX_KC_LN_FWD, GX_KC_LN_BWD, GX_KC_ATTN_FWD, GX_KC_ATTN_BWD, GX_KC_COLSUM, GX_KC_GEMM = 1, 2, 3, 4, 5, 100
 
 
@@ -48,6 +48,18 @@ class AdamWCfg(ctypes.Structure):
                [("step", ctypes.c_int32)]
 
 
+class PlanProblem(ctypes.Structure):
+    _fields_ = [("layers", ctypes.c_int32), ("strategies", ctypes.c_int32),
+                ("time_ms", ctypes.POINTER(ctypes.c_double)), ("mem_bytes", ctypes.POINTER(ctypes.c_double)),
+                ("switch_ms", ctypes.POINTER(ctypes.c_double)), ("mem_budget_bytes", ctypes.c_double),
+                ("mem_quantum_bytes", ctypes.c_double)]
+
+
+class PlanResult(ctypes.Structure):
+    _fields_ = [("total_ms", ctypes.c_double), ("total_mem_bytes", ctypes.c_double),
+                ("pruned", ctypes.c_int64), ("frontier_peak", ctypes.c_int64)]
+
+
 class GxError(RuntimeError):
     def __init__(self, status, where):
         self.status = int(status)
@@ -63,6 +75,14 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(f"{LIB_PATH} not found: build it with `python -m paper_2504_03662_amd.build`")
+        # One HIP runtime per process: PyTorch ships its own copy, and the dynamic linker only shares it
+        # with libgx when PyTorch's copy is loaded first (its soname then satisfies libgx's dependency);
+        # the other order leaves two runtimes on one GPU and libgx's calls fail.  PyTorch supplies the
+        # device memory wherever this binding is used, so load it first when it is installed.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(LIB_PATH)
         P = ctypes.c_void_p
         L.gx_layer_validate.argtypes = [ctypes.POINTER(LayerCfg)]
@@ -92,6 +112,9 @@ def lib():
         L.gx_params_slice.restype = ctypes.c_int
         L.gx_params_merge.argtypes = [ctypes.POINTER(LayerCfg), ctypes.POINTER(Params), ctypes.POINTER(ParamsOut), P]
         L.gx_params_merge.restype = ctypes.c_int
+        L.gx_plan_search.argtypes = [ctypes.POINTER(PlanProblem), ctypes.POINTER(ctypes.c_int32),
+                                     ctypes.POINTER(PlanResult)]
+        L.gx_plan_search.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -204,3 +227,19 @@ def params_merge(cfg, shard, whole, stream=0, check=True):
     if check and st != GX_OK:
         raise GxError(st, "gx_params_merge")
     return int(st)
+
+
+def plan_search(time_ms, mem_bytes, switch_ms=None, *, budget, quantum=0.0, check=True):
+    """time_ms, mem_bytes: [layers][strategies] nested sequences; switch_ms: [strategies][strategies] or None.
+    Returns (status, choice list, PlanResult)."""
+    L, S = len(time_ms), len(time_ms[0])
+    flat = lambda a: (ctypes.c_double * (len(a) * len(a[0])))(*[float(x) for row in a for x in row])
+    t, m = flat(time_ms), flat(mem_bytes)
+    sw = flat(switch_ms) if switch_ms is not None else None
+    prob = PlanProblem(L, S, t, m, sw, float(budget), float(quantum))
+    choice = (ctypes.c_int32 * L)()
+    res = PlanResult()
+    st = lib().gx_plan_search(ctypes.byref(prob), choice, ctypes.byref(res))
+    if check and st != GX_OK:
+        raise GxError(st, "gx_plan_search")
+    return int(st), list(choice), res

@@ -521,6 +521,7 @@ const char* gx_status_str(gx_status s) {
     case GX_ERR_FLAGS: return "no phase selected or unknown flag bits";
     case GX_ERR_ARCH: return "the current device is not gfx950";
     case GX_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+    case GX_ERR_INFEASIBLE: return "no assignment fits the memory budget";
   }
   return "unknown status";
 }

@@ -1,0 +1,139 @@
+// Layer-wise strategy plan search (host code only): the discovery-phase search of the strategy
+// selector, given a per-layer cost table.  Decision-tree style pruning of the candidates first
+// (feasibility, dominance), then an exact dynamic program over layers whose state is the last
+// layer's strategy and a Pareto frontier of (memory used, time spent).
+#include "../../include/gx.h"
+
+#include <algorithm>
+#include <cmath>
+#include <vector>
+
+namespace {
+
+struct Pt {
+  double mem, time;
+  int prev_s, prev_i;     // strategy of the previous layer and index into its frontier
+};
+
+constexpr size_t MAX_POINTS = 1u << 22;     // per (layer, strategy) candidate list; beyond: coarser quantum needed
+
+double round_up(double x, double q) { return q > 0.0 ? std::ceil(x / q - 1e-12) * q : x; }
+
+}  // namespace
+
+extern "C" gx_status gx_plan_search(const gx_plan_problem* p, int32_t* choice, gx_plan_result* out) {
+  if (!p || !choice || !out || !p->time_ms || !p->mem_bytes) return GX_ERR_NULL;
+  const int L = p->layers, S = p->strategies;
+  if (L <= 0 || S <= 0 || L > 4096 || S > 1024) return GX_ERR_SHAPE;
+  if (!(p->mem_budget_bytes >= 0.0) || !(p->mem_quantum_bytes >= 0.0)) return GX_ERR_SHAPE;
+  const double B = p->mem_budget_bytes;
+  std::vector<double> mem((size_t)L * S);
+  for (size_t i = 0; i < mem.size(); i++) {
+    if (!(p->time_ms[i] >= 0.0) || !(p->mem_bytes[i] >= 0.0) || !std::isfinite(p->time_ms[i]) ||
+        !std::isfinite(p->mem_bytes[i]))
+      return GX_ERR_SHAPE;
+    mem[i] = round_up(p->mem_bytes[i], p->mem_quantum_bytes);
+  }
+  auto T = [&](int l, int s) { return p->time_ms[(size_t)l * S + s]; };
+  auto M = [&](int l, int s) { return mem[(size_t)l * S + s]; };
+  auto SW = [&](int a, int b) { return (p->switch_ms && a != b) ? p->switch_ms[(size_t)a * S + b] : 0.0; };
+  if (p->switch_ms)
+    for (int a = 0; a < S; a++)
+      for (int b = 0; b < S; b++)
+        if (a != b && (!(SW(a, b) >= 0.0) || !std::isfinite(SW(a, b)))) return GX_ERR_SHAPE;
+
+  // pruning.  Rule 1 (feasibility): a strategy whose memory, together with the least memory every
+  // other layer can have, exceeds the budget is on no feasible plan.  Rule 2 (dominance): a strategy
+  // is dropped at a layer when another one there is no slower, no larger and no costlier to switch
+  // to or from, with a strict improvement somewhere or a smaller index.
+  std::vector<double> least(L);
+  double least_total = 0.0;
+  for (int l = 0; l < L; l++) {
+    least[l] = M(l, 0);
+    for (int s = 1; s < S; s++) least[l] = std::min(least[l], M(l, s));
+    least_total += least[l];
+  }
+  std::vector<char> alive((size_t)L * S, 1);
+  int64_t pruned = 0;
+  for (int l = 0; l < L; l++)
+    for (int s = 0; s < S; s++)
+      if (least_total - least[l] + M(l, s) > B * (1.0 + 1e-15)) { alive[(size_t)l * S + s] = 0; pruned++; }
+  for (int l = 0; l < L; l++)
+    for (int s = 0; s < S; s++) {
+      if (!alive[(size_t)l * S + s]) continue;
+      for (int d = 0; d < S; d++) {
+        if (d == s || !alive[(size_t)l * S + d]) continue;
+        const bool no_worse = T(l, d) <= T(l, s) && M(l, d) <= M(l, s);
+        const bool strict = T(l, d) < T(l, s) || M(l, d) < M(l, s) || d < s;
+        // with switching costs a dominated strategy could still pay off by avoiding a switch, so
+        // the rule is only applied when there are none
+        if (no_worse && strict && !p->switch_ms) {
+          alive[(size_t)l * S + s] = 0;
+          pruned++;
+          break;
+        }
+      }
+    }
+
+  // dynamic program
+  std::vector<std::vector<std::vector<Pt>>> fr(L, std::vector<std::vector<Pt>>(S));
+  size_t peak = 0;
+  for (int s = 0; s < S; s++)
+    if (alive[s] && M(0, s) <= B) fr[0][s].push_back(Pt{M(0, s), T(0, s), -1, -1});
+  std::vector<Pt> cand;
+  for (int l = 1; l < L; l++) {
+    for (int s2 = 0; s2 < S; s2++) {
+      if (!alive[(size_t)l * S + s2]) continue;
+      cand.clear();
+      const double m2 = M(l, s2), t2 = T(l, s2);
+      for (int s1 = 0; s1 < S; s1++) {
+        const std::vector<Pt>& f = fr[l - 1][s1];
+        const double sw = SW(s1, s2);
+        for (int i = 0; i < (int)f.size(); i++) {
+          const double m = f[i].mem + m2;
+          if (m > B) break;                      // frontiers are sorted by memory
+          cand.push_back(Pt{m, f[i].time + t2 + sw, s1, i});
+        }
+        if (cand.size() > MAX_POINTS) return GX_ERR_SHAPE;
+      }
+      std::sort(cand.begin(), cand.end(), [](const Pt& a, const Pt& b) {
+        if (a.mem != b.mem) return a.mem < b.mem;
+        if (a.time != b.time) return a.time < b.time;
+        if (a.prev_s != b.prev_s) return a.prev_s < b.prev_s;
+        return a.prev_i < b.prev_i;
+      });
+      std::vector<Pt>& dst = fr[l][s2];
+      double best = INFINITY;
+      for (const Pt& c : cand)
+        if (c.time < best) { dst.push_back(c); best = c.time; }
+      peak = std::max(peak, dst.size());
+    }
+  }
+  int bs = -1, bi = -1;
+  for (int s = 0; s < S; s++) {
+    const std::vector<Pt>& f = fr[L - 1][s];
+    for (int i = 0; i < (int)f.size(); i++) {
+      if (bs < 0 || f[i].time < fr[L - 1][bs][bi].time ||
+          (f[i].time == fr[L - 1][bs][bi].time && f[i].mem < fr[L - 1][bs][bi].mem)) {
+        bs = s;
+        bi = i;
+      }
+    }
+  }
+  out->pruned = pruned;
+  out->frontier_peak = (int64_t)peak;
+  if (bs < 0) {
+    out->total_ms = 0.0;
+    out->total_mem_bytes = 0.0;
+    return GX_ERR_INFEASIBLE;
+  }
+  out->total_ms = fr[L - 1][bs][bi].time;
+  out->total_mem_bytes = fr[L - 1][bs][bi].mem;
+  for (int l = L - 1; l >= 0; l--) {
+    choice[l] = bs;
+    const Pt& q = fr[l][bs][bi];
+    bs = q.prev_s;
+    bi = q.prev_i;
+  }
+  return GX_OK;
+}

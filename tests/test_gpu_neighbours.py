@@ -165,3 +165,15 @@ def test_full_size_transition_round_trip():
     torch.cuda.synchronize()
     for k in dims:
         assert torch.equal(back[k].view(torch.int16), whole[k].view(torch.int16)), k
+
+
+def test_cost_table_row_is_measured_on_the_gpu():
+    """The model profiler's compute column comes from timing single-phase calls of the library;
+    a row at a graded shard shape must land in a sane band around the bench's rate."""
+    from paper_2504_03662_amd import profiler as PF
+    shape, _, _ = I.WORKLOADS["C3"]
+    m = PF.Model(shape.hidden, shape.heads, shape.ffn, shape.seq, 1)
+    rows = PF.cost_table(m, gpus=4, global_batch=2, measure=True)
+    r = next(r for r in rows if (r["tp_attn"], r["tp_ffn"]) == (4, 4))
+    assert 300.0 < r["tflops_per_gpu"] < 2500.0, r
+    assert r["compute_ms"] > 0 and r["mem_bytes"] > r["state_bytes"]
