@@ -368,7 +368,9 @@ def test_micro_batch_split_equals_batch_and_stack_composes():
     assert np.array_equal(o1["y"], y)
 
 
-def test_model_flops_matches_survey_table():
+def test_model_flops_hand_count():
+    # hand count for the TP-shard workload: 3 x (2 T H 3Hl + 2 T Hl H + 4 T H Fl + 4 B nl dh S (S + 1) / 2)
+    # with T 4096, H 4096, Hl 1024, Fl 4096, B 2, nl 8, dh 128, S 2048  ->  1288.5 GFLOP
     shape, blocks, mbs = I.WORKLOADS["C3"]
     assert abs(O.model_flops(shape) / 1e9 - 1288.5) < 0.5
     shape, blocks, mbs = I.WORKLOADS["C2"]
