@@ -1,9 +1,10 @@
 // bf16 MFMA GEMM family for gfx950: the dense contractions of one rank's transformer-block share
 // (column-parallel QKV / FC1, row-parallel out-proj / FC2, their input and weight gradients).
 //
-// One workgroup of 8 wavefronts computes a 256x256 (or 128x128) tile of C with a K step of 64.  Operand tiles
-// go from HBM straight into LDS (buffer_load ... lds, 16 B per lane, no register staging) into a
-// double buffer; fragments for v_mfma_f32_32x32x16_bf16 are read with ds_read_b128 when the
+// One workgroup of 8 wavefronts computes a 256x256 tile of C with a K step of 64 through a double
+// buffer, or a 128x128 tile with a K step of 32 through a ring of four stages (products with few
+// tiles keep only one small workgroup per compute unit, which needs the deeper prefetch).  Operand
+// tiles go from HBM straight into LDS (buffer_load ... lds, 16 B per lane, no register staging); fragments for v_mfma_f32_32x32x16_bf16 are read with ds_read_b128 when the
 // reduction index is contiguous in memory ("K-major" tiles) and with the transposing
 // ds_read_b64_tr_b16 when it is strided ("MN-major" tiles), so no operand is ever transposed in
 // HBM.  LDS positions are XOR-swizzled on the global-address side because a direct-to-LDS load
@@ -13,13 +14,15 @@
 namespace gx {
 namespace {
 
-constexpr int BK = 64;
 constexpr int NTHREADS = 512;
+constexpr int NWAVES = NTHREADS / 64;
 constexpr unsigned OOB = 0x80000000u;           // beyond num_records: the load writes zeros
 
-// K-major tile: [R rows][64 k], 128 B per row, 16 B chunk c of row r stored at c ^ swz_k(r).
-GX_DEVINL int swz_k(int r) { return (r >> 1) & 7; }
-// MN-major tile: [64 k-rows][R cols], 2R B per k-row, 16 B chunk c of k-row kr stored at
+// K-major tile: [R rows][BK k], 2 BK bytes per row, 16 B chunk c of row r stored at c ^ swz_k(r):
+// the 16 rows that one ds_read_b128 pass covers at a fixed chunk then fall in distinct banks.
+template <int BK>
+GX_DEVINL int swz_k(int r) { return BK == 64 ? ((r >> 1) & 7) : ((r >> 2) & 3); }
+// MN-major tile: [BK k-rows][R cols], 2R B per k-row, 16 B chunk c of k-row kr stored at
 // c ^ swz_mn(kr) (moves whole 64 B groups so that 4 consecutive k-rows fall in distinct banks).
 GX_DEVINL int swz_mn(int kr) { return (kr & 3) << 2; }
 
@@ -28,10 +31,10 @@ GX_DEVINL __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
 }
 
 // This wave's share of the direct-to-LDS loads of one operand tile (R = 256 or 128 rows/columns
-// by 64 reduction steps): R/64 instructions of 64 lanes x 16 B each.
-template <bool KMAJOR, int R>
+// by BK reduction steps): R * BK / 4096 instructions of 64 lanes x 16 B each.
+template <bool KMAJOR, int R, int BK>
 struct TileLoader {
-  static constexpr int PER = R / 64;
+  static constexpr int PER = R * BK / (512 * NWAVES);
   unsigned base[PER];   // k-invariant part of the lane's element offset, or OOB
   int kc[PER];          // K-major: k offset of the chunk; MN-major: k-row of the chunk
   __amdgpu_buffer_rsrc_t rsrc;
@@ -46,8 +49,10 @@ struct TileLoader {
     for (int i = 0; i < PER; i++) {
       const int q = wave * PER + i;
       if (KMAJOR) {
-        const int r = 8 * q + (lane >> 3);
-        const int c = (lane & 7) ^ swz_k(r);
+        constexpr int CPR = BK / 8;                // 16 B chunks per row
+        constexpr int RPI = 64 / CPR;              // rows per instruction
+        const int r = RPI * q + lane / CPR;
+        const int c = (lane % CPR) ^ swz_k<BK>(r);
         kc[i] = c * 8;
         base[i] = (origin + r < extent) ? (unsigned)((origin + r) * ld + c * 8) : OOB;
       } else {
@@ -74,9 +79,10 @@ struct TileLoader {
 };
 
 // fragment of a 32-row block for k sub-step ks (16 k), K-major tile
+template <int BK>
 GX_DEVINL bf16x8 frag_k(const char* tile, int row, int ks, int g) {
-  const int c = (2 * ks + g) ^ swz_k(row);
-  return *reinterpret_cast<const bf16x8*>(tile + row * 128 + (c << 4));
+  const int c = (2 * ks + g) ^ swz_k<BK>(row);
+  return *reinterpret_cast<const bf16x8*>(tile + row * (2 * BK) + (c << 4));
 }
 // A fragment being fetched: either complete (K-major tile, one ds_read_b128 the compiler tracks)
 // or two untracked transposing reads of an MN-major tile that lds_wait_all() must cover.
@@ -102,16 +108,19 @@ GX_DEVINL bf16x8 frag_mn_finish(Frag& f) {
 }
 
 // BM x BN output tile (256 x 256, or 128 x 128 for products with too few large tiles to fill the
-// chip); 8 wavefronts as 2 x 4, each owning (BM/2) x (BN/4).
-template <int LAY, int EPI, int BM, int BN>
+// chip); 8 wavefronts as 2 x 4, each owning (BM/2) x (BN/4).  K step BK through STAGES LDS stages.
+template <int LAY, int EPI, int BM, int BN, int BK>
 __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
+  constexpr int STAGES = (BK == 64) ? 2 : 4;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   constexpr bool A_K = (LAY != LAY_TN);
   constexpr bool B_K = (LAY == LAY_NT);
   constexpr int TM = BM / 64, TN = BN / 128;          // 32x32 accumulators per wave
   constexpr int WM = BM / 2, WN = BN / 4;             // wave tile
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
-  constexpr bool SPLIT_B = (LAY == LAY_NT) || BM == 256;
+  constexpr bool SPLIT_B = (STAGES == 2) && ((LAY == LAY_NT) || BM == 256);
+  constexpr int KS = BK / 16;
+  static_assert(KS % 2 == 0, "fragment double buffer assumes an even number of sub-steps");
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 2, wn = wave & 3;
@@ -133,8 +142,8 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
 
   const bf16* A = static_cast<const bf16*>(g.A);
   const bf16* B = static_cast<const bf16*>(g.B);
-  TileLoader<A_K, BM> la;
-  TileLoader<B_K, BN> lb;
+  TileLoader<A_K, BM, BK> la;
+  TileLoader<B_K, BN, BK> lb;
   la.init(A, (unsigned)((size_t)(A_K ? g.M : g.K) * g.lda * 2), g.lda, g.K, m0, g.M, wave, lane);
   lb.init(B, (unsigned)((size_t)(B_K ? g.N : g.K) * g.ldb * 2), g.ldb, g.K, n0, g.N, wave, lane);
 
@@ -146,74 +155,119 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
 
-  char* sa = smem;                       // A[2]
-  char* sb = smem + 2 * A_BYTES;         // B[2]
+  char* sa = smem;                       // A[STAGES]
+  char* sb = smem + STAGES * A_BYTES;    // B[STAGES]
   const int nk = (g.K + BK - 1) / BK;
-  la.issue(sa, 0, wave);
-  lb.issue(sb, 0, wave);
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's LDS-DMA has landed
-  __syncthreads();
-  if (nk > 1) {
-    la.issue(sa + A_BYTES, BK, wave);
-    lb.issue(sb + B_BYTES, BK, wave);
-  }
-
   // Fragments of sub-step ks+1 are requested before the products of sub-step ks are issued, also
   // across tiles: the wait for the next tile's DMA and the workgroup barrier sit before the LAST
   // sub-step's products, whose operands are already in registers, so the first fragments of the
   // next tile are in flight while those products run and no wavefront starts a tile by waiting
-  // for LDS.  The tile after next is loaded into the buffer the barrier has just retired.
+  // for LDS.  The stage the barrier has just retired receives the next tile to be fetched.
   Frag fa[2][TM], fb[2][TN];
   auto request = [&](const char* ta, const char* tb, int ks, int buf) {
 #pragma unroll
     for (int mi = 0; mi < TM; mi++) {
-      if (A_K) fa[buf][mi].full = frag_k(ta, wm * WM + mi * 32 + l32, ks, grp);
+      if (A_K) fa[buf][mi].full = frag_k<BK>(ta, wm * WM + mi * 32 + l32, ks, grp);
       else     frag_mn_issue<BM>(ta, wm * WM + mi * 32, ks, lane, fa[buf][mi]);
     }
 #pragma unroll
     for (int ni = 0; ni < TN; ni++) {
-      if (B_K) fb[buf][ni].full = frag_k(tb, wn * WN + ni * 32 + l32, ks, grp);
+      if (B_K) fb[buf][ni].full = frag_k<BK>(tb, wn * WN + ni * 32 + l32, ks, grp);
       else     frag_mn_issue<BN>(tb, wn * WN + ni * 32, ks, lane, fb[buf][ni]);
     }
   };
-  request(sa, sb, 0, 0);
-  constexpr int KS = BK / 16;
-  static_assert(KS % 2 == 0, "fragment double buffer assumes an even number of sub-steps");
+  // one sub-step: finish this sub-step's fragments, let `between` request the next ones (and do
+  // the tile hand-over on the last sub-step), then issue the products
+  auto substep = [&](int ks, auto between) {
+    const int buf = ks & 1;
+    bf16x8 af[TM], bfr[TN];
+    if (!A_K || !B_K || ks == KS - 1) lds_wait_all();
+#pragma unroll
+    for (int mi = 0; mi < TM; mi++) af[mi] = A_K ? fa[buf][mi].full : frag_mn_finish(fa[buf][mi]);
+#pragma unroll
+    for (int ni = 0; ni < TN; ni++) bfr[ni] = B_K ? fb[buf][ni].full : frag_mn_finish(fb[buf][ni]);
+    between(buf);
+#pragma unroll
+    for (int mi = 0; mi < TM; mi++)
+#pragma unroll
+      for (int ni = 0; ni < TN; ni++)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ni], af[mi], acc[mi][ni], 0, 0, 0);
+  };
 
-  for (int kt = 0; kt < nk; kt++) {
-    const int cur = kt & 1;
-    const char* ta = sa + cur * A_BYTES;
-    const char* tb = sb + cur * B_BYTES;
-#pragma unroll
-    for (int ks = 0; ks < KS; ks++) {
-      const int buf = ks & 1;
-      bf16x8 af[TM], bfr[TN];
-      if (!A_K || !B_K || ks == KS - 1) lds_wait_all();
-#pragma unroll
-      for (int mi = 0; mi < TM; mi++) af[mi] = A_K ? fa[buf][mi].full : frag_mn_finish(fa[buf][mi]);
-#pragma unroll
-      for (int ni = 0; ni < TN; ni++) bfr[ni] = B_K ? fb[buf][ni].full : frag_mn_finish(fb[buf][ni]);
-      if (ks + 1 < KS) {
-        request(ta, tb, ks + 1, buf ^ 1);
-      } else {
-        // every LDS read of this tile by this wavefront has completed (lds_wait_all above)
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
-        if (kt + 2 < nk) {
-          la.issue(sa + cur * A_BYTES, (kt + 2) * BK, wave);
-          if (!SPLIT_B) lb.issue(sb + cur * B_BYTES, (kt + 2) * BK, wave);
-        }
-        if (kt + 1 < nk) request(sa + (cur ^ 1) * A_BYTES, sb + (cur ^ 1) * B_BYTES, 0, buf ^ 1);
-      }
-      // the B half of a prefetch may go out one sub-step after the A half, so that the wavefronts
-      // of a SIMD do not all sit in the load issue queue at once
-      if (SPLIT_B && ks == 0 && kt >= 1 && kt + 1 < nk) lb.issue(sb + (cur ^ 1) * B_BYTES, (kt + 1) * BK, wave);
-#pragma unroll
-      for (int mi = 0; mi < TM; mi++)
-#pragma unroll
-        for (int ni = 0; ni < TN; ni++)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ni], af[mi], acc[mi][ni], 0, 0, 0);
+  if (STAGES == 2) {
+    // double buffer: one tile in flight, waited for completely at each hand-over
+    la.issue(sa, 0, wave);
+    lb.issue(sb, 0, wave);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's LDS-DMA has landed
+    __syncthreads();
+    if (nk > 1) {
+      la.issue(sa + A_BYTES, BK, wave);
+      lb.issue(sb + B_BYTES, BK, wave);
     }
+    request(sa, sb, 0, 0);
+    for (int kt = 0; kt < nk; kt++) {
+      const int cur = kt & 1;
+      const char* ta = sa + cur * A_BYTES;
+      const char* tb = sb + cur * B_BYTES;
+#pragma unroll
+      for (int ks = 0; ks < KS; ks++) {
+        substep(ks, [&](int buf) {
+          if (ks + 1 < KS) {
+            request(ta, tb, ks + 1, buf ^ 1);
+          } else {
+            // every LDS read of this tile by this wavefront has completed (lds_wait_all)
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+            if (kt + 2 < nk) {
+              la.issue(sa + cur * A_BYTES, (kt + 2) * BK, wave);
+              if (!SPLIT_B) lb.issue(sb + cur * B_BYTES, (kt + 2) * BK, wave);
+            }
+            if (kt + 1 < nk) request(sa + (cur ^ 1) * A_BYTES, sb + (cur ^ 1) * B_BYTES, 0, buf ^ 1);
+          }
+          // the B half of a prefetch may go out one sub-step after the A half, so that the
+          // wavefronts of a SIMD do not all sit in the load issue queue at once
+          if (SPLIT_B && ks == 0 && kt >= 1 && kt + 1 < nk)
+            lb.issue(sb + (cur ^ 1) * B_BYTES, (kt + 1) * BK, wave);
+        });
+      }
+    }
+  } else {
+    // ring of STAGES tiles, STAGES - 1 in flight.  Loads in flight are counted per wavefront, LPT
+    // per tile; tiles beyond K are requested like any other (every lane out of range: zeros, no
+    // memory traffic), so that the count at each wait is the same in every step.
+    constexpr int LPT = TileLoader<A_K, BM, BK>::PER + TileLoader<B_K, BN, BK>::PER;
+    static_assert((STAGES - 1) * LPT < 16, "vmcnt immediate");
+#pragma unroll
+    for (int t = 0; t < STAGES; t++) {
+      la.issue(sa + t * A_BYTES, t * BK, wave);
+      lb.issue(sb + t * B_BYTES, t * BK, wave);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70 | ((STAGES - 1) * LPT));   // vmcnt: tile 0 has landed
+    __syncthreads();
+    request(sa, sb, 0, 0);
+    for (int kt = 0; kt < nk; kt++) {
+      const int cur = kt & (STAGES - 1), nxt = (kt + 1) & (STAGES - 1);
+      const char* ta = sa + cur * A_BYTES;
+      const char* tb = sb + cur * B_BYTES;
+#pragma unroll
+      for (int ks = 0; ks < KS; ks++) {
+        substep(ks, [&](int buf) {
+          if (ks + 1 < KS) {
+            request(ta, tb, ks + 1, buf ^ 1);
+          } else {
+            // tile kt+1 has landed once at most STAGES-2 younger tiles are still in flight
+            __builtin_amdgcn_s_waitcnt(0x0F70 | ((STAGES - 2) * LPT));
+            __syncthreads();
+            la.issue(sa + cur * A_BYTES, (kt + STAGES) * BK, wave);
+            lb.issue(sb + cur * B_BYTES, (kt + STAGES) * BK, wave);
+            if (kt + 1 < nk) request(sa + nxt * A_BYTES, sb + nxt * B_BYTES, 0, buf ^ 1);
+          }
+        });
+      }
+    }
+    // the zero-fill requests of the tail must have landed before the staging below reuses LDS
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
   }
   // every wavefront passed the last barrier with all its LDS reads complete, so the tile buffers
   // are free to serve as staging space below
@@ -292,18 +346,18 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
   }
 }
 
-template <int LAY, int EPI, int BM, int BN>
+template <int LAY, int EPI, int BM, int BN, int BK>
 hipError_t launch_tile(const GemmArgs& g, hipStream_t s) {
-  constexpr int SMEM = 2 * (BM + BN) * BK * 2;
+  constexpr int SMEM = ((BK == 64) ? 2 : 4) * (BM + BN) * BK * 2;
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<LAY, EPI, BM, BN>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<LAY, EPI, BM, BN, BK>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
     if (e != hipSuccess) return e;
     configured = true;
   }
   const int tm = cdiv(g.M, BM), tn = cdiv(g.N, BN);
-  hipLaunchKernelGGL((gemm_kernel<LAY, EPI, BM, BN>), dim3(tm * tn), dim3(NTHREADS), SMEM, s, g);
+  hipLaunchKernelGGL((gemm_kernel<LAY, EPI, BM, BN, BK>), dim3(tm * tn), dim3(NTHREADS), SMEM, s, g);
   return hipGetLastError();
 }
 
@@ -313,8 +367,8 @@ hipError_t launch(const GemmArgs& g, hipStream_t s) {
   // 256 compute units: measured on this chip, the small tile only pays when the large one would
   // leave half of them idle (128 large tiles: small tile 22 % faster; 160: large tile 4-23 % faster)
   const long big = (long)cdiv(g.M, 256) * cdiv(g.N, 256);
-  if (big <= 144) return launch_tile<LAY, EPI, 128, 128>(g, s);
-  return launch_tile<LAY, EPI, 256, 256>(g, s);
+  if (big <= 144) return launch_tile<LAY, EPI, 128, 128, 32>(g, s);
+  return launch_tile<LAY, EPI, 256, 256, 64>(g, s);
 }
 
 template <int LAY>
