@@ -138,6 +138,9 @@ struct SegBuilder {
   void whole(const void* src, void* dst, long bytes) { add(src, dst, 1, bytes, bytes, bytes); }
 };
 
+static_assert(sizeof(gx_params) == 12 * sizeof(void*) && sizeof(gx_params_out) == 12 * sizeof(void*),
+              "the transition code indexes both parameter structs as arrays of 12 pointers");
+
 // slice: src = whole, dst = shard; merge: the other way round.  W() picks the whole-side pointer
 // and S() the shard-side pointer of a tensor, whichever struct they live in.
 gx_status transition(const gx_layer_cfg* c, const void* const* whole, const void* const* shard, bool to_shard,
