@@ -107,7 +107,7 @@ typedef struct {
 
 /* Host-only check of a configuration (no GPU needed): sizes positive, hidden % heads == 0,
  * heads % tp_attn == 0, ffn % tp_ffn == 0, 0 <= tp_rank < max(tp_attn, tp_ffn), at least one phase,
- * no unknown flag, and the kernels' limits: bf16 needs head dim 128, hidden and Fl multiples of 8,
+ * no unknown flag, and the kernels' limits: bf16 needs head dim 64 or 128, hidden and Fl multiples of 8,
  * hidden <= 8192; fp32 needs head dim <= 128 and hidden, Fl multiples of 4, hidden <= 4096,
  * seq <= 8192; every activation tensor must stay below 2 GiB. */
 gx_status gx_layer_validate(const gx_layer_cfg* cfg);

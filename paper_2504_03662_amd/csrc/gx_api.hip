@@ -141,7 +141,7 @@ gx_status validate(const gx_layer_cfg* c) {
   const int vec = d.bf ? 8 : 4;
   if (d.H % vec || d.Fl % vec || d.Hl % vec) return GX_ERR_DIVIS;
   if (d.bf) {
-    if (d.dh != 128 || d.H > 8192) return GX_ERR_SHAPE;
+    if ((d.dh != 128 && d.dh != 64) || d.H > 8192) return GX_ERR_SHAPE;
   } else {
     if (d.dh > 128 || d.H > 4096 || d.S > 8192) return GX_ERR_SHAPE;
   }

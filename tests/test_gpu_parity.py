@@ -81,6 +81,26 @@ def test_bf16_many_query_blocks():
     compare(gpu, ref, TOL["bf16"])
 
 
+@pytest.mark.parametrize("phase", ["both", "attn"])
+@pytest.mark.parametrize("a,f,rank,seq,batch", [(1, 1, 0, 200, 2), (2, 3, 1, 333, 1), (1, 1, 0, 1, 3)])
+def test_bf16_head_dim_64_ragged_shapes(phase, a, f, rank, seq, batch):
+    # hidden 384 = 6 heads x 64: the 128-byte-row tile layout of the attention kernels
+    shape = I.LayerShape(384, 6, 1536, a, f, rank, seq, batch, "bf16")
+    params, x, dy = _case(shape, 70 + a)
+    rb = (rank == 0)
+    gpu, ref, _ = run_both(shape, params, x, dy, phase, rb, not rb, want_partials=(phase == "both"))
+    compare(gpu, ref, TOL["bf16"], phase, want_partials=(phase == "both"))
+
+
+def test_bf16_head_dim_64_many_and_long_blocks():
+    # one-tile-per-step kernels (many (sample, head) pairs) and a longer ragged sequence with few pairs
+    for hidden, heads, seq, batch, case in ((512, 8, 1300, 6, 75), (256, 4, 1999, 1, 76)):
+        shape = I.LayerShape(hidden, heads, 1024, 1, 1, 0, seq, batch, "bf16")
+        params, x, dy = _case(shape, case)
+        gpu, ref, _ = run_both(shape, params, x, dy, "attn", want_partials=False)
+        compare(gpu, ref, TOL["bf16"], "attn")
+
+
 def test_bf16_degenerate_sizes():
     # one token per sample (attention is the identity on V), and a single sample of 2 tokens
     for seq, batch, case in ((1, 5, 61), (2, 1, 62)):
