@@ -198,6 +198,17 @@ def test_bitwise_reproducible():
     assert np.array_equal(a["y"], b["y"]) and np.array_equal(a["dx"], b["dx"])
     for n in I.PARAM_NAMES:
         assert np.array_equal(a["grads"][n], b["grads"][n]), n
+    # queuing the whole backward pass on the caller's stream instead of forking onto the side
+    # streams only changes when kernels run, never what they compute
+    from paper_2504_03662_amd import binding as gx
+    gx.set_overlap(False)
+    try:
+        c, _, _ = run_both(shape, params, x, dy)
+    finally:
+        gx.set_overlap(True)
+    assert np.array_equal(a["dx"], c["dx"])
+    for n in I.PARAM_NAMES:
+        assert np.array_equal(a["grads"][n], c["grads"][n]), n
 
 
 def test_launch_timing_record():
