@@ -17,7 +17,8 @@ pre-LayerNorm GPT block written out directly:
                    p_attn = ctx @ Wo (+ bo when this rank owns the row-parallel bias)
     feed-forward : y2 = LN(h1; g2, b2);  z = y2 @ W1 + b1;  act = gelu(z)
                    p_mlp = act @ W2 (+ b2 when this rank owns the row-parallel bias)
-    gelu(z)      = z * Phi(z),  Phi the standard normal CDF (erf form)
+    gelu(z)      = z * Phi(z),  Phi the standard normal CDF (erf form); a configuration may select
+                   the tanh form 0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))) instead
     both halves  : h1 = x + p_attn;  y = h1 + p_mlp          (the rank's partial sum stands in
                                                                for the reduced sum; exact at TP=1)
     one half     : returns p_attn (from x) or p_mlp (from h1) alone, no residual, so that a
@@ -86,6 +87,27 @@ def gelu_grad(z):
     cdf = 0.5 * (1.0 + _erf(z / np.sqrt(2.0)))
     pdf = np.exp(-0.5 * z * z) / np.sqrt(2.0 * np.pi)
     return cdf + z * pdf
+
+
+def gelu_tanh(z):
+    """The tanh form of GELU (a variant selected per configuration, `gelu_tanh`):
+    0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3)))."""
+    z = _f64(z)
+    return 0.5 * z * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (z + 0.044715 * z ** 3)))
+
+
+def gelu_tanh_grad(z):
+    """Derivative of gelu_tanh: with u = sqrt(2/pi) (z + 0.044715 z^3) and t = tanh(u),
+    0.5 (1 + t) + 0.5 z (1 - t^2) sqrt(2/pi) (1 + 3 * 0.044715 z^2)."""
+    z = _f64(z)
+    c = np.sqrt(2.0 / np.pi)
+    t = np.tanh(c * (z + 0.044715 * z ** 3))
+    return 0.5 * (1.0 + t) + 0.5 * z * (1.0 - t * t) * c * (1.0 + 3.0 * 0.044715 * z * z)
+
+
+def _activation(cfg):
+    """(function, derivative) of the feed-forward activation the configuration selects."""
+    return (gelu_tanh, gelu_tanh_grad) if getattr(cfg, "gelu_tanh", False) else (gelu, gelu_grad)
 
 
 def causal_attention_fwd(q, k, v):
@@ -195,7 +217,7 @@ def mlp_half_fwd(cfg, p, h1, row_bias=True):
     h1 = _f64(h1)
     y2, xhat2, rstd2 = layer_norm_fwd(h1, p["ln2_g"], p["ln2_b"], sh.eps)
     z = y2 @ _f64(p["w_fc1"]) + _f64(p["b_fc1"])
-    act = gelu(z)
+    act = _activation(cfg)[0](z)
     p_mlp = act @ _f64(p["w_fc2"])
     if row_bias:
         p_mlp = p_mlp + _f64(p["b_fc2"])
@@ -211,7 +233,7 @@ def mlp_half_bwd(cfg, p, dp_mlp, cache, row_bias=True):
     g["w_fc2"] = cache["act"].T @ dp_mlp
     g["b_fc2"] = dp_mlp.sum(axis=0) if row_bias else np.zeros(sh.H)
     dact = dp_mlp @ _f64(p["w_fc2"]).T
-    dz = dact * gelu_grad(cache["z"])
+    dz = dact * _activation(cfg)[1](cache["z"])
     g["w_fc1"] = cache["y2"].T @ dz
     g["b_fc1"] = dz.sum(axis=0)
     dy2 = dz @ _f64(p["w_fc1"]).T

@@ -206,12 +206,13 @@ hipError_t ln_params_p(bool bf, const void* dy, const void* x, const float* mean
   return ln_bwd_params(bf, dy, x, mean, rstd, part, rows, cols, dg, db, acc, s);
 }
 
-// The backward pass has bandwidth-bound column reductions (bias and LayerNorm parameter
-// gradients) and one small weight-gradient product whose inputs are ready long before anything
-// consumes their results.  They run on a second, library-owned stream so that they overlap the
-// MFMA-bound products and the attention kernels on the caller's stream: fork with an event after
-// the producer, join once at the end of the call.  Created on first use, default priority,
-// shared by all calls of the process (calls from several host threads must not overlap).
+// The backward pass has work whose inputs are ready long before anything consumes its results:
+// the bandwidth-bound column reductions (bias and LayerNorm parameter gradients) and every
+// weight-gradient product.  It runs on a second, library-owned stream beside the dependent chain
+// (input gradients, LayerNorm input gradients, attention) on the caller's stream, and a third
+// stream takes the dQ kernel beside the dK/dV kernel: fork with an event after the producer, join
+// once at the end of the call.  Created on first use, default priority, shared by all calls of the
+// process (calls from several host threads must not overlap).
 struct SideStream {
   bool tried = false, ok = false;
   hipStream_t s = nullptr, s2 = nullptr;
@@ -242,11 +243,13 @@ struct Fork {
   int n = 0;
   bool used = false;
   explicit Fork(hipStream_t m) : main(m), side(side_ready() ? g_side.s : m) {}
+  hipError_t err = hipSuccess;     // first failure of an event call; reported by join()
   // stream for a task that depends on what `main` holds now
   hipStream_t branch() {
-    if (side != main && n < 8) {
-      (void)hipEventRecord(g_side.fork[n], main);
-      (void)hipStreamWaitEvent(side, g_side.fork[n], 0);
+    if (side != main && n < 8 && err == hipSuccess) {
+      err = hipEventRecord(g_side.fork[n], main);
+      if (err == hipSuccess) err = hipStreamWaitEvent(side, g_side.fork[n], 0);
+      if (err != hipSuccess) return main;       // not ordered after the producer: stay on its stream
       n++;
       used = true;
       return side;
@@ -254,6 +257,7 @@ struct Fork {
     return main;
   }
   hipError_t join() {
+    if (err != hipSuccess) return err;
     if (!used) return hipSuccess;
     hipError_t e = hipEventRecord(g_side.join, side);
     if (e != hipSuccess) return e;

@@ -38,6 +38,7 @@ class LayerShape:
     micro_batch: int = 1
     dtype: str = "f32"          # "f32" or "bf16"
     ln_eps: float = 1e-5
+    gelu_tanh: bool = False     # tanh form of GELU instead of the erf form
 
     @property
     def head_dim(self):

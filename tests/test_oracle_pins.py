@@ -375,3 +375,35 @@ def test_model_flops_hand_count():
     assert abs(O.model_flops(shape) / 1e9 - 1288.5) < 0.5
     shape, blocks, mbs = I.WORKLOADS["C2"]
     assert abs(O.model_flops(shape, blocks, mbs) / 1e12 - 10.72) < 0.01
+
+
+def test_gelu_tanh_variant_matches_torch_and_finite_differences():
+    z = np.linspace(-6, 6, 97)
+    ref = torch.nn.functional.gelu(torch.tensor(z, dtype=torch.float64), approximate="tanh").numpy()
+    assert np.allclose(O.gelu_tanh(z), ref, rtol=1e-13, atol=1e-15)
+    h = 1e-6
+    fd = (O.gelu_tanh(z + h) - O.gelu_tanh(z - h)) / (2 * h)
+    assert np.allclose(O.gelu_tanh_grad(z), fd, atol=1e-9)
+    assert abs(O.gelu_tanh_grad(np.array([0.0]))[0] - 0.5) < 1e-15
+    # the two forms agree to about 5e-4 and no better: the variant is really a different function
+    d = np.abs(O.gelu_tanh(z) - O.gelu(z)).max()
+    assert 1e-4 < d < 1e-3
+    # the configuration switch reaches the block: forward and backward of the feed-forward half
+    cfg = cfg_of()
+    cfg_t = cfg_of(gelu_tanh=True)
+    rng = np.random.default_rng(12)
+    p = rand_params(cfg, rng)
+    x = rng.standard_normal((12, 16))
+    a = O.layer_fwd(cfg, p, x, "mlp")
+    b = O.layer_fwd(cfg_t, p, x, "mlp")
+    assert not np.allclose(a["p_mlp"], b["p_mlp"], atol=1e-6)
+    w = rng.standard_normal((12, 16))
+    dx, g = O.layer_bwd(cfg_t, p, w, b["cache"], "mlp")
+    eps = 1e-6
+    for _ in range(5):
+        i, j = rng.integers(12), rng.integers(16)
+        xp, xm = x.copy(), x.copy()
+        xp[i, j] += eps
+        xm[i, j] -= eps
+        fdx = (np.sum(O.layer_fwd(cfg_t, p, xp, "mlp")["p_mlp"] * w) - np.sum(O.layer_fwd(cfg_t, p, xm, "mlp")["p_mlp"] * w)) / (2 * eps)
+        assert abs(fdx - dx[i, j]) < 1e-6 * max(1.0, abs(fdx))
