@@ -80,7 +80,9 @@ enum {
   GX_ROW_BIAS_ATTN = 4,   /* this rank adds b_o to p_attn (exactly one rank of a group should) */
   GX_ROW_BIAS_MLP = 8,    /* this rank adds b_fc2 to p_mlp */
   GX_ACCUM_WGRAD = 16,    /* backward: add into the parameter gradients instead of overwriting */
-  GX_RECOMPUTE = 32       /* backward: recompute the forward activations from x; `saved` unused */
+  GX_RECOMPUTE = 32,      /* backward: recompute the forward activations from x; `saved` unused */
+  GX_GELU_TANH = 64       /* feed-forward activation 0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))) instead of
+                             the erf form; pass the same flag to the forward and the backward call */
 };
 
 /* One rank's share of one block.  tp_rank is informational (which shard the caller passed). */
@@ -89,7 +91,7 @@ typedef struct {
   int32_t tp_attn, tp_ffn, tp_rank;
   int32_t seq, micro_batch;
   int32_t dtype;            /* gx_dtype */
-  int32_t flags;            /* GX_PHASE_* | GX_ROW_BIAS_* | GX_ACCUM_WGRAD | GX_RECOMPUTE */
+  int32_t flags;            /* GX_PHASE_* | GX_ROW_BIAS_* | GX_ACCUM_WGRAD | GX_RECOMPUTE | GX_GELU_TANH */
   float ln_eps;             /* LayerNorm epsilon (inside the square root; biased variance) */
 } gx_layer_cfg;
 

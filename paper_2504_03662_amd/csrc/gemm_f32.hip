@@ -85,9 +85,9 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(GemmArgs g) {
       } else if (EPI == EPI_GELU) {
         x += bv;
         C[idx] = x;
-        aux[idx] = gelu_f(x);
+        aux[idx] = g.gelu_tanh ? gelu_tanh_f(x) : gelu_f(x);
       } else if (EPI == EPI_DGELU) {
-        C[idx] = x * gelu_grad_f(zin[idx]);
+        C[idx] = x * (g.gelu_tanh ? gelu_tanh_grad_f(zin[idx]) : gelu_grad_f(zin[idx]));
       } else {
         C[idx] += x;
       }

@@ -24,7 +24,7 @@ namespace {
 using namespace gx;
 
 constexpr int ALL_FLAGS = GX_PHASE_ATTN | GX_PHASE_MLP | GX_ROW_BIAS_ATTN | GX_ROW_BIAS_MLP | GX_ACCUM_WGRAD |
-                          GX_RECOMPUTE;
+                          GX_RECOMPUTE | GX_GELU_TANH;
 
 struct Dims {
   long T, H, Hl, Fl, S, B, nl, dh;
@@ -317,6 +317,7 @@ gx_status run_fwd(const gx_layer_cfg& c, const gx_params& p, const void* x, void
     GemmArgs f1 = gargs(sv.y2, p.w_fc1, sv.z, d.T, d.Fl, d.H, d.H, d.Fl, d.Fl);
     f1.bias = p.b_fc1;
     f1.aux = sv.act;
+    f1.gelu_tanh = (c.flags & GX_GELU_TANH) ? 1 : 0;
     GX_TRY(gemm(d, LAY_NN, EPI_GELU, f1, st));
     if (!for_backward_only) {
       GemmArgs f2 = gargs(sv.act, p.w_fc2, attn ? y : p_mlp, d.T, d.H, d.Fl, d.Fl, d.H, d.H);
@@ -365,6 +366,7 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     // input gradient fused with GELU' on the caller's stream
     GemmArgs dz = gargs(dy, p.w_fc2, w.dz, d.T, d.Fl, d.H, d.H, d.H, d.Fl);
     dz.z = sv.z;
+    dz.gelu_tanh = (c.flags & GX_GELU_TANH) ? 1 : 0;
     GX_TRY(gemm(d, LAY_NT, EPI_DGELU, dz, st));
     // column-parallel FC1: bias and weight gradients on the side once dz exists
     sd = fk.branch();

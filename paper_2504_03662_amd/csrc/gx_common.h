@@ -53,6 +53,30 @@ GX_DEVINL float gelu_grad_fast(float z) {
   return fmaf(z * 0.39894228040143267794f, e, 0.5f * (1.0f + copysignf(r, z)));
 }
 
+// The tanh form of GELU, z * sigmoid(2u) with u = sqrt(2/pi) (z + 0.044715 z^3), and its derivative
+// s + 2 z s (1 - s) u'(z), s = sigmoid(2u); full-precision exponential and division for fp32
+// outputs, hardware exponential and reciprocal for bf16 outputs.
+GX_DEVINL float gelu_tanh_f(float z) {
+  const float u = 0.7978845608028654f * fmaf(0.044715f * z * z, z, z);
+  return z / (1.0f + expf(-2.0f * u));
+}
+GX_DEVINL float gelu_tanh_grad_f(float z) {
+  const float z2 = z * z;
+  const float u = 0.7978845608028654f * fmaf(0.044715f * z2, z, z);
+  const float s = 1.0f / (1.0f + expf(-2.0f * u));
+  return fmaf(2.0f * z * s * (1.0f - s), 0.7978845608028654f * fmaf(0.134145f, z2, 1.0f), s);
+}
+GX_DEVINL float gelu_tanh_fast(float z) {
+  const float u = 0.7978845608028654f * fmaf(0.044715f * z * z, z, z);
+  return z * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u));
+}
+GX_DEVINL float gelu_tanh_grad_fast(float z) {
+  const float z2 = z * z;
+  const float u = 0.7978845608028654f * fmaf(0.044715f * z2, z, z);
+  const float s = __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u));
+  return fmaf(2.0f * z * s * (1.0f - s), 0.7978845608028654f * fmaf(0.134145f, z2, 1.0f), s);
+}
+
 GX_DEVINL float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

@@ -17,7 +17,7 @@ enum Epilogue {
   EPI_STORE = 0,   // C = acc                                   (storage type)
   EPI_BIAS,        // C = acc + bias[n]            (bias may be null)
   EPI_RESID,       // p = acc + bias[n]; aux = p if aux; C = resid + p
-  EPI_GELU,        // z = acc + bias[n]; C = z; aux = gelu(z)
+  EPI_GELU,        // z = acc + bias[n]; C = z; aux = gelu(z)        (erf form, or tanh form if gelu_tanh)
   EPI_DGELU,       // C = acc * gelu'(z[m,n])
   EPI_F32,         // C (fp32) = acc
   EPI_F32_ACC      // C (fp32) += acc
@@ -33,6 +33,7 @@ struct GemmArgs {
   const void* resid;   // [M, ldc], storage type
   void* aux;           // [M, ldc], storage type
   const void* z;       // [M, ldc], storage type
+  int gelu_tanh;       // EPI_GELU / EPI_DGELU: tanh form of GELU instead of the erf form
 };
 
 hipError_t gemm_bf16(Layout lay, Epilogue epi, const GemmArgs& g, hipStream_t s);

@@ -18,6 +18,7 @@ def cfg_of(shape: LayerShape, phase="both", row_bias_attn=True, row_bias_mlp=Tru
     flags |= gx.GX_ROW_BIAS_MLP if row_bias_mlp else 0
     flags |= gx.GX_ACCUM_WGRAD if accumulate else 0
     flags |= gx.GX_RECOMPUTE if recompute else 0
+    flags |= gx.GX_GELU_TANH if shape.gelu_tanh else 0
     return gx.make_cfg(shape.hidden, shape.heads, shape.ffn, shape.tp_attn, shape.tp_ffn, shape.tp_rank, shape.seq,
                        shape.micro_batch, gx.GX_BF16 if shape.dtype == "bf16" else gx.GX_F32, flags, shape.ln_eps)
 

@@ -43,7 +43,7 @@ def test_validate_accepts_the_graded_workloads(lib):
 
 
 @pytest.mark.parametrize("kw,status", [
-    (dict(hidden=0), 2), (dict(seq=-1), 2), (dict(dtype=7), 4), (dict(flags=0), 6), (dict(flags=3 | 1024), 6),
+    (dict(hidden=0), 2), (dict(seq=-1), 2), (dict(dtype=7), 4), (dict(flags=0), 6), (dict(flags=3 | 1024), 6), (dict(flags=3 | 128), 6),
     (dict(heads=33), 3), (dict(tp_attn=3), 3), (dict(ffn=16385), 3), (dict(tp_rank=4), 2),
     (dict(hidden=1024, heads=32), 2),                 # bf16 head dim 32 is not supported (64 and 128 are)
     (dict(hidden=16384, heads=128), 2),               # beyond the LayerNorm kernels' width

@@ -101,6 +101,21 @@ def test_bf16_head_dim_64_many_and_long_blocks():
         compare(gpu, ref, TOL["bf16"], "attn")
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("recompute", [False, True])
+def test_gelu_tanh_variant(dtype, recompute):
+    # the flag must reach the forward epilogue, the backward epilogue and the recomputation
+    hidden, heads = (256, 4) if dtype == "f32" else (512, 4)
+    shape = I.LayerShape(hidden, heads, 1096, 1, 1, 0, 150, 2, dtype, gelu_tanh=True)
+    params, x, dy = _case(shape, 95)
+    gpu, ref, _ = run_both(shape, params, x, dy, "both", recompute=recompute)
+    compare(gpu, ref, TOL[dtype])
+    # and it must make a difference: the erf-form oracle is measurably elsewhere at fp32 resolution
+    if dtype == "f32":
+        ref_erf = O.layer_fwd(shape.with_(gelu_tanh=False), params, x)["y"]
+        assert np.abs(ref_erf - ref["y"]).max() > 1e-5 * np.abs(ref["y"]).max()
+
+
 def test_bf16_degenerate_sizes():
     # one token per sample (attention is the identity on V), and a single sample of 2 tokens
     for seq, batch, case in ((1, 5, 61), (2, 1, 62)):
