@@ -27,11 +27,11 @@ def model_flops(sh, blocks, mbs):
     return 3.0 * fwd * blocks * mbs
 
 
-def gemm_flops_by_class(sh, accumulate):
+def gemm_flops_by_class(sh, accumulate, wgrad_bf16=False):
     """Kernel class -> list of 2*M*N*K for the GEMM launches of one layer pass (fwd + bwd)."""
     T, H, Hl, Fl = sh.tokens, sh.hidden, sh.hidden_local, sh.ffn_local
     f = lambda m, n, k: 2.0 * m * n * k
-    wg = 126 if accumulate else 125
+    wg = (122 if accumulate else 120) if wgrad_bf16 else (126 if accumulate else 125)
     return {101: [f(T, 3 * Hl, H)], 102: [f(T, H, Hl), f(T, H, Fl)], 103: [f(T, Fl, H)],
             wg: [f(Fl, H, T), f(H, Fl, T), f(Hl, H, T), f(H, 3 * Hl, T)],
             114: [f(T, Fl, H)], 110: [f(T, H, Fl), f(T, Hl, H), f(T, H, 3 * Hl)]}
@@ -62,7 +62,8 @@ def measured_traffic(workload, kernel):
 
 CLASS_NAMES = {1: "ln_fwd", 2: "ln_bwd", 3: "attn_fwd", 4: "attn_bwd", 5: "colsum",
                101: "gemm_nn_bias", 102: "gemm_nn_resid", 103: "gemm_nn_gelu", 110: "gemm_nt_store",
-               114: "gemm_nt_dgelu", 125: "gemm_tn_f32", 126: "gemm_tn_f32_acc"}
+               114: "gemm_nt_dgelu", 125: "gemm_tn_f32", 126: "gemm_tn_f32_acc",
+               120: "gemm_tn_bf16", 122: "gemm_tn_bf16_acc"}
 
 
 def main():
@@ -78,6 +79,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain elementwise copy of 256 MiB (read) + 256 MiB (write), as the "
                          "known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--wgrad-bf16", action="store_true",
+                    help="variant: weight-matrix gradients written as bf16 (GX_WGRAD_BF16) instead of fp32; "
+                         "recorded in config.weight_grad")
     ap.add_argument("--neighbours", action="store_true",
                     help="also time the layer step's memory-bound neighbours at this workload's shapes (AdamW "
                          "update of the rank's parameters, slicing the rank's shard out of the whole block and "
@@ -99,7 +103,7 @@ def main():
     shape, blocks, mbs = I.WORKLOADS[args.workload]
     case = {"C1": 1, "C2": 2, "C3": 3, "C4": 4, "C5": 5}[args.workload]
     plist = [I.rank_params(shape, case=case, block=k) for k in range(blocks)]
-    stack = DeviceStack(shape, plist)
+    stack = DeviceStack(shape, plist, wgrad_bf16=args.wgrad_bf16)
     del plist
     acts = [I.activations(shape, case=case, micro_batch_index=m) for m in range(mbs)]
     xs = [to_device(a[0], shape.dtype) for a in acts]
@@ -159,12 +163,13 @@ def main():
     kernels = {CLASS_NAMES.get(c, str(c)): {"launches_per_step": len(v) * launches_per_step // len(rec),
                                             "avg_ms": sum(v) / len(v), "share": sum(v) / total_ms}
                for c, v in sorted(by.items(), key=lambda kv: -sum(kv[1]))}
-    gemm_fl = gemm_flops_by_class(shape, pipelined)
+    gemm_fl = gemm_flops_by_class(shape, pipelined, args.wgrad_bf16)
     dom = max((c for c in by if c >= 100), key=lambda c: sum(by[c]))
-    fl = gemm_fl.get(dom) or gemm_fl.get(125 if dom == 126 else 126)     # first micro-batch overwrites
+    pair = {125: 126, 126: 125, 120: 122, 122: 120}                      # store / accumulate forms of one product
+    fl = gemm_fl.get(dom) or gemm_fl.get(pair.get(dom))                  # first micro-batch overwrites
     avg_ms = sum(by[dom]) / len(by[dom])
-    if dom in (125, 126) and pipelined:
-        both = by.get(125, []) + by.get(126, [])
+    if dom in pair and pipelined:
+        both = by.get(dom, []) + by.get(pair[dom], [])
         avg_ms = sum(both) / len(both)
     flops_per_launch = sum(fl) / len(fl)
     achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12
@@ -183,7 +188,7 @@ def main():
                       "tp_attn": shape.tp_attn, "tp_ffn": shape.tp_ffn, "tp_rank": shape.tp_rank, "seq": shape.seq,
                       "micro_batch": shape.micro_batch, "blocks": blocks, "micro_batches": mbs,
                       "schedule": "1F1B, full recompute" if pipelined else "fwd then bwd",
-                      "backward_overlap": not args.serial},
+                      "backward_overlap": not args.serial, "weight_grad": "bf16" if args.wgrad_bf16 else "f32"},
            "frac_of_mfma_peak": tflops / peak,
            "tokens_per_s_per_layer": shape.tokens * blocks * mbs / (ms * 1e-3),
            "model_tflop_per_step": flops / 1e12,

@@ -81,8 +81,12 @@ enum {
   GX_ROW_BIAS_MLP = 8,    /* this rank adds b_fc2 to p_mlp */
   GX_ACCUM_WGRAD = 16,    /* backward: add into the parameter gradients instead of overwriting */
   GX_RECOMPUTE = 32,      /* backward: recompute the forward activations from x; `saved` unused */
-  GX_GELU_TANH = 64       /* feed-forward activation 0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))) instead of
+  GX_GELU_TANH = 64,      /* feed-forward activation 0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))) instead of
                              the erf form; pass the same flag to the forward and the backward call */
+  GX_WGRAD_BF16 = 128     /* backward, bf16 configurations only: the four weight-matrix gradients (w_qkv, w_o,
+                             w_fc1, w_fc2 of gx_grads) point to bf16 buffers; each element is the fp32
+                             accumulator rounded once (with GX_ACCUM_WGRAD: old bf16 value + accumulator, added
+                             in fp32 and rounded once).  Bias and LayerNorm gradients stay fp32. */
 };
 
 /* One rank's share of one block.  tp_rank is informational (which shard the caller passed). */
@@ -91,7 +95,7 @@ typedef struct {
   int32_t tp_attn, tp_ffn, tp_rank;
   int32_t seq, micro_batch;
   int32_t dtype;            /* gx_dtype */
-  int32_t flags;            /* GX_PHASE_* | GX_ROW_BIAS_* | GX_ACCUM_WGRAD | GX_RECOMPUTE | GX_GELU_TANH */
+  int32_t flags;            /* GX_PHASE_* | GX_ROW_BIAS_* | GX_ACCUM_WGRAD | GX_RECOMPUTE | GX_GELU_TANH | GX_WGRAD_BF16 */
   float ln_eps;             /* LayerNorm epsilon (inside the square root; biased variance) */
 } gx_layer_cfg;
 
@@ -101,7 +105,8 @@ typedef struct {
   const void *ln2_g, *ln2_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
 } gx_params;
 
-/* Parameter gradients, always fp32, same shapes as the parameters. */
+/* Parameter gradients, same shapes as the parameters: fp32, except that with GX_WGRAD_BF16 the four
+ * weight-matrix pointers are reinterpreted as bf16 buffers. */
 typedef struct {
   float *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_o, *b_o;
   float *ln2_g, *ln2_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
@@ -109,7 +114,7 @@ typedef struct {
 
 /* Host-only check of a configuration (no GPU needed): sizes positive, hidden % heads == 0,
  * heads % tp_attn == 0, ffn % tp_ffn == 0, 0 <= tp_rank < max(tp_attn, tp_ffn), at least one phase,
- * no unknown flag, and the kernels' limits: bf16 needs head dim 64 or 128, hidden and Fl multiples of 8,
+ * no unknown flag, GX_WGRAD_BF16 only with dtype bf16 (else GX_ERR_DTYPE), and the kernels' limits: bf16 needs head dim 64 or 128, hidden and Fl multiples of 8,
  * hidden <= 8192; fp32 needs head dim <= 128 and hidden, Fl multiples of 4, hidden <= 4096,
  * seq <= 8192; every activation tensor must stay below 2 GiB. */
 gx_status gx_layer_validate(const gx_layer_cfg* cfg);

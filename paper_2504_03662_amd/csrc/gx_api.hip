@@ -24,7 +24,7 @@ namespace {
 using namespace gx;
 
 constexpr int ALL_FLAGS = GX_PHASE_ATTN | GX_PHASE_MLP | GX_ROW_BIAS_ATTN | GX_ROW_BIAS_MLP | GX_ACCUM_WGRAD |
-                          GX_RECOMPUTE | GX_GELU_TANH;
+                          GX_RECOMPUTE | GX_GELU_TANH | GX_WGRAD_BF16;
 
 struct Dims {
   long T, H, Hl, Fl, S, B, nl, dh;
@@ -134,6 +134,7 @@ gx_status validate(const gx_layer_cfg* c) {
       c->micro_batch <= 0 || !(c->ln_eps >= 0.f))
     return GX_ERR_SHAPE;
   if ((c->flags & ~ALL_FLAGS) || !(c->flags & (GX_PHASE_ATTN | GX_PHASE_MLP))) return GX_ERR_FLAGS;
+  if ((c->flags & GX_WGRAD_BF16) && c->dtype != GX_BF16) return GX_ERR_DTYPE;
   if (c->hidden % c->heads || c->heads % c->tp_attn || c->ffn % c->tp_ffn) return GX_ERR_DIVIS;
   const int tpmax = c->tp_attn > c->tp_ffn ? c->tp_attn : c->tp_ffn;
   if (c->tp_rank < 0 || c->tp_rank >= tpmax) return GX_ERR_SHAPE;
@@ -350,8 +351,16 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
                   const gx_grads& gr, const Saved& sv, const Work& w, hipStream_t st) {
   const Dims d = dims_of(c);
   const bool attn = c.flags & GX_PHASE_ATTN, mlp = c.flags & GX_PHASE_MLP;
-  const Epilogue wg = (c.flags & GX_ACCUM_WGRAD) ? EPI_F32_ACC : EPI_F32;
   const bool acc = c.flags & GX_ACCUM_WGRAD;
+  // weight gradient A^T B into fp32 (store or add) or, on request, into bf16: a plain rounding
+  // store, or the residual epilogue reading the old value from the output itself (every lane
+  // reads exactly the four elements it then writes, so in place is safe)
+  auto wgrad = [&](GemmArgs g, hipStream_t s) -> hipError_t {
+    if (!(c.flags & GX_WGRAD_BF16)) return gemm(d, LAY_TN, acc ? EPI_F32_ACC : EPI_F32, g, s);
+    if (!acc) return gemm(d, LAY_TN, EPI_STORE, g, s);
+    g.resid = g.C;
+    return gemm(d, LAY_TN, EPI_RESID, g, s);
+  };
   Fork fk(st);
   gx_status s;
   const void* dcur = dy;           // gradient arriving at the attention half's output
@@ -362,7 +371,7 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     hipStream_t sd = fk.branch();
     if ((s = bias_grad(d, c, c.flags & GX_ROW_BIAS_MLP, dy, d.H, w.part, gr.b_fc2, sd)) != GX_OK) return s;
     GemmArgs w2 = gargs(sv.act, dy, gr.w_fc2, d.Fl, d.H, d.T, d.Fl, d.H, d.H);
-    GX_TRY(gemm(d, LAY_TN, wg, w2, sd));
+    GX_TRY(wgrad(w2, sd));
     // input gradient fused with GELU' on the caller's stream
     GemmArgs dz = gargs(dy, p.w_fc2, w.dz, d.T, d.Fl, d.H, d.H, d.H, d.Fl);
     dz.z = sv.z;
@@ -372,7 +381,7 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     sd = fk.branch();
     GX_TRY(colsum_p(d.bf, w.dz, (int)d.T, (int)d.Fl, w.part, gr.b_fc1, acc, sd));
     GemmArgs w1 = gargs(sv.y2, w.dz, gr.w_fc1, d.H, d.Fl, d.T, d.H, d.Fl, d.Fl);
-    GX_TRY(gemm(d, LAY_TN, wg, w1, sd));
+    GX_TRY(wgrad(w1, sd));
     GemmArgs dy2 = gargs(w.dz, p.w_fc1, w.dy2, d.T, d.H, d.Fl, d.Fl, d.Fl, d.H);
     GX_TRY(gemm(d, LAY_NT, EPI_STORE, dy2, st));
     // LayerNorm 2: parameter gradients on the side; input gradient (plus dy through the residual
@@ -393,7 +402,7 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     hipStream_t sd = fk.branch();
     if ((s = bias_grad(d, c, c.flags & GX_ROW_BIAS_ATTN, dcur, d.H, w.part, gr.b_o, sd)) != GX_OK) return s;
     GemmArgs wo = gargs(sv.ctx, dcur, gr.w_o, d.Hl, d.H, d.T, d.Hl, d.H, d.H);
-    GX_TRY(gemm(d, LAY_TN, wg, wo, sd));
+    GX_TRY(wgrad(wo, sd));
     GemmArgs dc = gargs(dcur, p.w_o, w.dctx, d.T, d.Hl, d.H, d.H, d.H, d.Hl);
     GX_TRY(gemm(d, LAY_NT, EPI_STORE, dc, st));
     AttnArgs a;
@@ -407,7 +416,7 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     hipStream_t sq = fk.branch();
     GX_TRY(colsum_p(d.bf, w.dqkv, (int)d.T, (int)(3 * d.Hl), w.part, gr.b_qkv, acc, sq));
     GemmArgs wq = gargs(sv.y1, w.dqkv, gr.w_qkv, d.H, 3 * d.Hl, d.T, d.H, 3 * d.Hl, 3 * d.Hl);
-    GX_TRY(gemm(d, LAY_TN, wg, wq, sq));
+    GX_TRY(wgrad(wq, sq));
     GemmArgs dy1 = gargs(w.dqkv, p.w_qkv, w.dy1, d.T, d.H, 3 * d.Hl, 3 * d.Hl, 3 * d.Hl, d.H);
     GX_TRY(gemm(d, LAY_NT, EPI_STORE, dy1, st));
     GX_TRY(ln_params_p(d.bf, w.dy1, x, sv.mean1, sv.rstd1, w.part, (int)d.T, (int)d.H, gr.ln1_g, gr.ln1_b, acc,

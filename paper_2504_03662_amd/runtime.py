@@ -11,14 +11,18 @@ from .inputs import PARAM_NAMES, LayerShape, bf16_bits, bf16_from_bits
 _FLAG_OF_PHASE = {"both": gx.GX_PHASE_ATTN | gx.GX_PHASE_MLP, "attn": gx.GX_PHASE_ATTN, "mlp": gx.GX_PHASE_MLP}
 
 
+WEIGHT_NAMES = ("w_qkv", "w_o", "w_fc1", "w_fc2")
+
+
 def cfg_of(shape: LayerShape, phase="both", row_bias_attn=True, row_bias_mlp=True, accumulate=False,
-           recompute=False):
+           recompute=False, wgrad_bf16=False):
     flags = _FLAG_OF_PHASE[phase]
     flags |= gx.GX_ROW_BIAS_ATTN if row_bias_attn else 0
     flags |= gx.GX_ROW_BIAS_MLP if row_bias_mlp else 0
     flags |= gx.GX_ACCUM_WGRAD if accumulate else 0
     flags |= gx.GX_RECOMPUTE if recompute else 0
     flags |= gx.GX_GELU_TANH if shape.gelu_tanh else 0
+    flags |= gx.GX_WGRAD_BF16 if wgrad_bf16 else 0
     return gx.make_cfg(shape.hidden, shape.heads, shape.ffn, shape.tp_attn, shape.tp_ffn, shape.tp_rank, shape.seq,
                        shape.micro_batch, gx.GX_BF16 if shape.dtype == "bf16" else gx.GX_F32, flags, shape.ln_eps)
 
@@ -43,13 +47,16 @@ class DeviceLayer:
     """One rank's share of one block on the GPU: owns parameter, gradient, saved-activation and
     workspace buffers and forwards calls to gx_layer_fwd / gx_layer_bwd."""
 
-    def __init__(self, shape: LayerShape, params, device="cuda:0"):
+    def __init__(self, shape: LayerShape, params, device="cuda:0", wgrad_bf16=False):
         gx.lib()                                   # fail loudly if the library is not built
         self.shape = shape
+        self.wgrad_bf16 = wgrad_bf16               # weight-matrix gradients kept in bf16 (GX_WGRAD_BF16)
         self.device = device
         self.tdtype = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
         self.params = {n: to_device(params[n], shape.dtype, device) for n in PARAM_NAMES}
-        self.grads = {n: torch.zeros(self.params[n].shape, dtype=torch.float32, device=device) for n in PARAM_NAMES}
+        self.grads = {n: torch.zeros(self.params[n].shape, device=device,
+                                     dtype=torch.bfloat16 if wgrad_bf16 and n in WEIGHT_NAMES else torch.float32)
+                      for n in PARAM_NAMES}
         self._bufs = {}
 
     def _buf(self, key, nbytes):
@@ -80,7 +87,7 @@ class DeviceLayer:
 
     def backward(self, x, dy, phase="both", row_bias_attn=True, row_bias_mlp=True, accumulate=False, recompute=False,
                  saved_key="saved", out=None):
-        cfg = cfg_of(self.shape, phase, row_bias_attn, row_bias_mlp, accumulate, recompute)
+        cfg = cfg_of(self.shape, phase, row_bias_attn, row_bias_mlp, accumulate, recompute, self.wgrad_bf16)
         ws = self._buf("work", gx.layer_workspace_bytes(cfg, True))
         saved = None if recompute else self._bufs[saved_key]
         dx = out if out is not None else self.empty_act()
@@ -92,9 +99,9 @@ class DeviceStack:
     """Consecutive blocks of one pipeline stage on the GPU.  Each block keeps its own saved
     activations per in-flight micro-batch, or, with recomputation, only its input."""
 
-    def __init__(self, shape: LayerShape, params_list, device="cuda:0"):
+    def __init__(self, shape: LayerShape, params_list, device="cuda:0", wgrad_bf16=False):
         self.shape = shape
-        self.layers = [DeviceLayer(shape, p, device) for p in params_list]
+        self.layers = [DeviceLayer(shape, p, device, wgrad_bf16) for p in params_list]
         self.inputs = {}          # micro-batch id -> per-block input tensors
 
     def forward(self, x, mb=0, keep_saved=True):

@@ -43,7 +43,8 @@ def test_validate_accepts_the_graded_workloads(lib):
 
 
 @pytest.mark.parametrize("kw,status", [
-    (dict(hidden=0), 2), (dict(seq=-1), 2), (dict(dtype=7), 4), (dict(flags=0), 6), (dict(flags=3 | 1024), 6), (dict(flags=3 | 128), 6),
+    (dict(hidden=0), 2), (dict(seq=-1), 2), (dict(dtype=7), 4), (dict(flags=0), 6), (dict(flags=3 | 1024), 6), (dict(flags=3 | 256), 6),
+    (dict(dtype=gx.GX_F32, hidden=256, heads=4, ffn=1024, tp_attn=1, tp_ffn=1, flags=3 | gx.GX_WGRAD_BF16), 4),
     (dict(heads=33), 3), (dict(tp_attn=3), 3), (dict(ffn=16385), 3), (dict(tp_rank=4), 2),
     (dict(hidden=1024, heads=32), 2),                 # bf16 head dim 32 is not supported (64 and 128 are)
     (dict(hidden=16384, heads=128), 2),               # beyond the LayerNorm kernels' width
@@ -52,6 +53,10 @@ def test_validate_accepts_the_graded_workloads(lib):
 ])
 def test_validate_rejects(lib, kw, status):
     assert gx.layer_validate(_cfg(**kw)) == status
+
+
+def test_bf16_weight_gradient_flag_is_accepted_for_bf16(lib):
+    assert gx.layer_validate(_cfg(flags=3 | gx.GX_WGRAD_BF16 | gx.GX_ACCUM_WGRAD)) == gx.GX_OK
 
 
 def test_size_queries(lib):

@@ -147,6 +147,40 @@ def test_recompute_and_accumulate_flags(dtype):
         check("acc d" + n, to_host(layer.grads[n]), 2.0 * ref["grads"][n], TOL[dtype])
 
 
+@pytest.mark.parametrize("phase", ["both", "attn", "mlp"])
+def test_bf16_weight_gradient_output(phase):
+    """GX_WGRAD_BF16: the four weight-matrix gradients arrive as bf16, each the fp32 accumulator
+    rounded once; everything else is unchanged."""
+    shape = I.LayerShape(512, 4, 1096, 2, 1, 1, 150, 2, "bf16")
+    params, x, dy = _case(shape, 96)
+    gpu, ref, _ = run_both(shape, params, x, dy, phase)
+    layer = DeviceLayer(shape, params, wgrad_bf16=True)
+    xd, dyd = to_device(x, "bf16"), to_device(dy, "bf16")
+    layer.forward(xd, phase)
+    dx = layer.backward(xd, dyd, phase)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(dx), gpu["dx"])
+    mine = {"both": I.PARAM_NAMES, "attn": I.PARAM_NAMES[:6], "mlp": I.PARAM_NAMES[6:]}[phase]
+    first = {}
+    for n in mine:
+        got = to_host(layer.grads[n])
+        first[n] = got
+        if n.startswith("w_"):
+            assert layer.grads[n].dtype == torch.bfloat16
+            assert np.array_equal(got, I.bf16_round(gpu["grads"][n])), n      # one rounding of the same sums
+            check("d" + n, got, ref["grads"][n], TOL["bf16"])
+        else:
+            assert np.array_equal(got, gpu["grads"][n]), n
+    # accumulation adds in fp32 and rounds once
+    layer.backward(xd, dyd, phase, accumulate=True)
+    torch.cuda.synchronize()
+    for n in mine:
+        got = to_host(layer.grads[n])
+        if n.startswith("w_"):
+            assert np.array_equal(got, I.bf16_round(first[n] + gpu["grads"][n])), n
+        check("acc d" + n, got, 2.0 * ref["grads"][n], TOL["bf16"])
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_rank_partials_add_up_to_the_unsharded_block(dtype):
     """Simulated ranks run one after another on the GPU; their partial sums, added on the host,
