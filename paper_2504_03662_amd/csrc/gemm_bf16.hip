@@ -128,17 +128,23 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
 
   // tile index: spread consecutive tiles over the 8 XCDs' round-robin dispatch so that each XCD
   // (own L2) works on a compact block of tiles, then walk tiles in groups of 8 tile-rows.
-  const int tm = (g.M + BM - 1) / BM, tn = (g.N + BN - 1) / BN;
   int pid = blockIdx.x;
   const int nwg = gridDim.x;
   if ((nwg & 7) == 0) pid = (pid & 7) * (nwg >> 3) + (pid >> 3);
+  // tail launch: the walk runs over super-tiles of 2BM x 2BN (the tiles of the large-tile launch
+  // that took the whole rounds), starting at g.tile_first; four consecutive workgroups share one
+  const int sub = g.tail ? (pid & 3) : 0;
+  const int SB = g.tail ? 2 : 1;
+  if (g.tail) pid = g.tile_first + (pid >> 2);
+  const int tm = (g.M + SB * BM - 1) / (SB * BM), tn = (g.N + SB * BN - 1) / (SB * BN);
   constexpr int GROUP = 8;
   const int in_group = GROUP * tn;
   const int first_m = (pid / in_group) * GROUP;
   const int gsize = min(tm - first_m, GROUP);
   const int pm = first_m + (pid % in_group) % gsize;
   const int pn = (pid % in_group) / gsize;
-  const int m0 = pm * BM, n0 = pn * BN;
+  const int m0 = (SB * pm + (sub >> 1)) * BM, n0 = (SB * pn + (sub & 1)) * BN;
+  if (m0 >= g.M || n0 >= g.N) return;      // quarter of a ragged super-tile that lies outside C
 
   const bf16* A = static_cast<const bf16*>(g.A);
   const bf16* B = static_cast<const bf16*>(g.B);
@@ -348,7 +354,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
 }
 
 template <int LAY, int EPI, int BM, int BN, int BK>
-hipError_t launch_tile(const GemmArgs& g, hipStream_t s) {
+hipError_t launch_tile(const GemmArgs& g, hipStream_t s, int grid) {
   constexpr int SMEM = ((BK == 64) ? 2 : 4) * (BM + BN) * BK * 2;
   static bool configured = false;
   if (!configured) {
@@ -357,19 +363,29 @@ hipError_t launch_tile(const GemmArgs& g, hipStream_t s) {
     if (e != hipSuccess) return e;
     configured = true;
   }
-  const int tm = cdiv(g.M, BM), tn = cdiv(g.N, BN);
-  hipLaunchKernelGGL((gemm_kernel<LAY, EPI, BM, BN, BK>), dim3(tm * tn), dim3(NTHREADS), SMEM, s, g);
+  hipLaunchKernelGGL((gemm_kernel<LAY, EPI, BM, BN, BK>), dim3(grid), dim3(NTHREADS), SMEM, s, g);
   return hipGetLastError();
 }
 
-// 256 x 256 tiles unless they would leave a quarter or more of the 256 compute units idle
+// 256 compute units, one large workgroup each.  Measured on this chip:
+//  - up to 144 large tiles the 128 x 128 tile is faster (128 large tiles: by 22 %; 160: large tile
+//    4-23 % faster);
+//  - beyond one round of 256 large tiles, a remainder of up to TAIL_MAX large tiles would hold the
+//    chip for a whole extra round at a fraction of its width: the whole rounds go to the large
+//    tile and the remainder region is cut into 128 x 128 tiles in a second launch.
+constexpr long ROUND = 256, TAIL_MAX = 128;
 template <int LAY, int EPI>
 hipError_t launch(const GemmArgs& g, hipStream_t s) {
-  // 256 compute units: measured on this chip, the small tile only pays when the large one would
-  // leave half of them idle (128 large tiles: small tile 22 % faster; 160: large tile 4-23 % faster)
   const long big = (long)cdiv(g.M, 256) * cdiv(g.N, 256);
-  if (big <= 144) return launch_tile<LAY, EPI, 128, 128, 32>(g, s);
-  return launch_tile<LAY, EPI, 256, 256, 64>(g, s);
+  if (big <= 144) return launch_tile<LAY, EPI, 128, 128, 32>(g, s, cdiv(g.M, 128) * cdiv(g.N, 128));
+  const long rem = big % ROUND;
+  if (big < ROUND || rem == 0 || rem > TAIL_MAX) return launch_tile<LAY, EPI, 256, 256, 64>(g, s, (int)big);
+  hipError_t e = launch_tile<LAY, EPI, 256, 256, 64>(g, s, (int)(big - rem));
+  if (e != hipSuccess) return e;
+  GemmArgs t = g;
+  t.tail = 1;
+  t.tile_first = (int)(big - rem);
+  return launch_tile<LAY, EPI, 128, 128, 32>(t, s, (int)(4 * rem));
 }
 
 template <int LAY>
@@ -388,7 +404,9 @@ hipError_t dispatch_epi(Epilogue epi, const GemmArgs& g, hipStream_t s) {
 
 }  // namespace
 
-hipError_t gemm_bf16(Layout lay, Epilogue epi, const GemmArgs& g, hipStream_t s) {
+hipError_t gemm_bf16(Layout lay, Epilogue epi, const GemmArgs& args, hipStream_t s) {
+  GemmArgs g = args;
+  g.tail = g.tile_first = 0;                 // the launcher's own fields
   if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
   // 16-byte chunks along each operand's contiguous index; 31-bit byte offsets in buffer loads
   const long a_rows = (lay == LAY_TN) ? g.K : g.M, b_rows = (lay == LAY_NT) ? g.N : g.K;

@@ -34,6 +34,9 @@ struct GemmArgs {
   void* aux;           // [M, ldc], storage type
   const void* z;       // [M, ldc], storage type
   int gelu_tanh;       // EPI_GELU / EPI_DGELU: tanh form of GELU instead of the erf form
+  // set by the bf16 launcher only (callers leave them 0): a launch that covers the super-tiles
+  // (2 x 2 kernel tiles) numbered tile_first onwards in the tile walk, four workgroups each
+  int tail, tile_first;
 };
 
 hipError_t gemm_bf16(Layout lay, Epilogue epi, const GemmArgs& g, hipStream_t s);

@@ -147,6 +147,17 @@ def test_recompute_and_accumulate_flags(dtype):
         check("acc d" + n, to_host(layer.grads[n]), 2.0 * ref["grads"][n], TOL[dtype])
 
 
+def test_bf16_remainder_round_of_large_tiles():
+    """Products a little over one or several rounds of 256 large tiles (here 17 x 17 = 289 for the
+    FC1 / FC2 / out-proj outputs and weight gradients, 17 x 50 = 850 for the QKV weight gradient)
+    are split into a large-tile launch and a small-tile launch over the remainder; 4200 rows and
+    4224 columns leave quarters of the last super-tiles outside the matrix."""
+    shape = I.LayerShape(4224, 33, 4104, 1, 1, 0, 1050, 4, "bf16")
+    params, x, dy = _case(shape, 97)
+    gpu, ref, _ = run_both(shape, params, x, dy, want_partials=True)
+    compare(gpu, ref, TOL["bf16"], want_partials=True)
+
+
 @pytest.mark.parametrize("phase", ["both", "attn", "mlp"])
 def test_bf16_weight_gradient_output(phase):
     """GX_WGRAD_BF16: the four weight-matrix gradients arrive as bf16, each the fp32 accumulator
