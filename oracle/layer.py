@@ -24,6 +24,14 @@ pre-LayerNorm GPT block written out directly:
     one half     : returns p_attn (from x) or p_mlp (from h1) alone, no residual, so that a
                    harness can add simulated ranks' partials itself
 
+    dropout      : a variant a configuration may select (drop_attn, drop_hidden in 1/256ths,
+                   drop_seed; all 0 = none).  P is replaced by P * keep * 256/(256 - drop_attn)
+                   before O = P V; with both halves, h1 = x + drop(p_attn) and y = h1 +
+                   drop(p_mlp) with their own masks.  A lone half returns its partial sum
+                   undropped (the harness that adds the ranks' partials owns that dropout).
+                   Masks come from oracle/dropout.py and are part of the function: the backward
+                   pass differentiates with the masks held fixed.
+
 Everything is evaluated with full S x S score matrices and no tiling, blocking or online
 softmax, in float64.  The backward pass is the exact gradient of the function above.
 
@@ -41,6 +49,8 @@ from __future__ import annotations
 
 import numpy as np
 from scipy.special import erf as _erf
+
+from . import dropout as _dropout
 
 PARAM_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
@@ -110,8 +120,10 @@ def _activation(cfg):
     return (gelu_tanh, gelu_tanh_grad) if getattr(cfg, "gelu_tanh", False) else (gelu, gelu_grad)
 
 
-def causal_attention_fwd(q, k, v):
-    """q, k, v: [S, dh] of one sample and head.  Returns (O [S, dh], P [S, S])."""
+def causal_attention_fwd(q, k, v, keep=None, keep_scale=1.0):
+    """q, k, v: [S, dh] of one sample and head.  Returns (O [S, dh], P [S, S]).  With a keep mask
+    [S, S] the probabilities that multiply V are P * keep * keep_scale; the returned P is the
+    softmax itself."""
     S, dh = q.shape
     s = (q @ k.T) / np.sqrt(dh)
     masked = np.triu(np.ones((S, S), dtype=bool), k=1)        # j > i
@@ -119,14 +131,18 @@ def causal_attention_fwd(q, k, v):
     s = s - s.max(axis=-1, keepdims=True)
     e = np.exp(s)                                             # exp(-inf) = 0 exactly
     p = e / e.sum(axis=-1, keepdims=True)
-    return p @ v, p
+    pd = p if keep is None else p * keep * keep_scale
+    return pd @ v, p
 
 
-def causal_attention_bwd(do, q, k, v, p):
-    """Gradient of causal_attention_fwd: returns (dq, dk, dv)."""
+def causal_attention_bwd(do, q, k, v, p, keep=None, keep_scale=1.0):
+    """Gradient of causal_attention_fwd (same keep mask): returns (dq, dk, dv)."""
     dh = q.shape[1]
-    dv = p.T @ do
-    dp = do @ v.T
+    pd = p if keep is None else p * keep * keep_scale
+    dv = pd.T @ do
+    dp = do @ v.T                                             # gradient w.r.t. the dropped probabilities
+    if keep is not None:
+        dp = dp * keep * keep_scale
     ds = p * (dp - (dp * p).sum(axis=-1, keepdims=True))      # softmax Jacobian; 0 where p = 0
     dq = (ds @ k) / np.sqrt(dh)
     dk = (ds.T @ q) / np.sqrt(dh)
@@ -150,6 +166,10 @@ class Shape:
         self.eps = float(getattr(cfg, "ln_eps", 1e-5))
         if self.H % self.nh or self.nh % self.a or self.F % self.f:
             raise ValueError("indivisible shape")
+        self.rank = int(getattr(cfg, "tp_rank", 0))
+        self.drop_attn = int(getattr(cfg, "drop_attn", 0))
+        self.drop_hidden = int(getattr(cfg, "drop_hidden", 0))
+        self.drop_seed = int(getattr(cfg, "drop_seed", 0))
         self.dh = self.H // self.nh
         self.nl = self.nh // self.a
         self.Hl = self.nl * self.dh
@@ -166,20 +186,27 @@ def attn_half_fwd(cfg, p, x, row_bias=True):
     y1, xhat1, rstd1 = layer_norm_fwd(x, p["ln1_g"], p["ln1_b"], sh.eps)
     qkv = y1 @ _f64(p["w_qkv"]) + _f64(p["b_qkv"])
     ctx = np.empty((sh.T, sh.Hl))
-    probs = {}
+    probs, keeps = {}, {}
+    keep_scale = _dropout.scale_of(sh.drop_attn)
     for b in range(sh.B):
         rows = slice(b * sh.S, (b + 1) * sh.S)
         for h in range(sh.nl):
             cq = slice(h * sh.dh, (h + 1) * sh.dh)
             ck = slice(sh.Hl + h * sh.dh, sh.Hl + (h + 1) * sh.dh)
             cv = slice(2 * sh.Hl + h * sh.dh, 2 * sh.Hl + (h + 1) * sh.dh)
-            o, pr = causal_attention_fwd(qkv[rows, cq], qkv[rows, ck], qkv[rows, cv])
+            keep = None
+            if sh.drop_attn:
+                # the mask belongs to the head of the whole model, whichever rank holds it
+                keep = _dropout.keep_attention(sh.drop_seed, sh.drop_attn, sh.S, b,
+                                               (sh.rank % sh.a) * sh.nl + h, sh.nh)
+            o, pr = causal_attention_fwd(qkv[rows, cq], qkv[rows, ck], qkv[rows, cv], keep, keep_scale)
             ctx[rows, cq] = o
             probs[(b, h)] = pr
+            keeps[(b, h)] = keep
     p_attn = ctx @ _f64(p["w_o"])
     if row_bias:
         p_attn = p_attn + _f64(p["b_o"])
-    cache = dict(xhat1=xhat1, rstd1=rstd1, y1=y1, qkv=qkv, ctx=ctx, probs=probs)
+    cache = dict(xhat1=xhat1, rstd1=rstd1, y1=y1, qkv=qkv, ctx=ctx, probs=probs, keeps=keeps, keep_scale=keep_scale)
     return p_attn, cache
 
 
@@ -200,7 +227,8 @@ def attn_half_bwd(cfg, p, dp_attn, cache, row_bias=True):
             ck = slice(sh.Hl + h * sh.dh, sh.Hl + (h + 1) * sh.dh)
             cv = slice(2 * sh.Hl + h * sh.dh, 2 * sh.Hl + (h + 1) * sh.dh)
             dq, dk, dv = causal_attention_bwd(dctx[rows, cq], qkv[rows, cq], qkv[rows, ck],
-                                              qkv[rows, cv], cache["probs"][(b, h)])
+                                              qkv[rows, cv], cache["probs"][(b, h)],
+                                              cache["keeps"][(b, h)], cache["keep_scale"])
             dqkv[rows, cq] = dq
             dqkv[rows, ck] = dk
             dqkv[rows, cv] = dv
@@ -259,11 +287,17 @@ def layer_fwd(cfg, p, x, phase="both", row_bias_attn=True, row_bias_mlp=True):
         return dict(p_mlp=p_mlp, cache=dict(mlp=cm))
     if phase != "both":
         raise ValueError(phase)
+    sh = Shape(cfg)
     p_attn, ca = attn_half_fwd(cfg, p, x, row_bias_attn)
-    h1 = x + p_attn
+    m_attn = m_mlp = 1.0
+    if sh.drop_hidden:
+        hs = _dropout.scale_of(sh.drop_hidden)
+        m_attn = hs * _dropout.keep_hidden(sh.drop_seed, sh.drop_hidden, sh.T, sh.H, _dropout.STREAM_ATTN_OUT)
+        m_mlp = hs * _dropout.keep_hidden(sh.drop_seed, sh.drop_hidden, sh.T, sh.H, _dropout.STREAM_MLP_OUT)
+    h1 = x + p_attn * m_attn
     p_mlp, cm = mlp_half_fwd(cfg, p, h1, row_bias_mlp)
-    y = h1 + p_mlp
-    return dict(y=y, h1=h1, p_attn=p_attn, p_mlp=p_mlp, cache=dict(attn=ca, mlp=cm))
+    y = h1 + p_mlp * m_mlp
+    return dict(y=y, h1=h1, p_attn=p_attn, p_mlp=p_mlp, cache=dict(attn=ca, mlp=cm, m_attn=m_attn, m_mlp=m_mlp))
 
 
 def layer_bwd(cfg, p, dy, cache, phase="both", row_bias_attn=True, row_bias_mlp=True):
@@ -278,9 +312,9 @@ def layer_bwd(cfg, p, dy, cache, phase="both", row_bias_attn=True, row_bias_mlp=
         return mlp_half_bwd(cfg, p, dy, cache["mlp"], row_bias_mlp)
     if phase != "both":
         raise ValueError(phase)
-    dh1_ln, gm = mlp_half_bwd(cfg, p, dy, cache["mlp"], row_bias_mlp)
+    dh1_ln, gm = mlp_half_bwd(cfg, p, dy * cache["m_mlp"], cache["mlp"], row_bias_mlp)
     dh1 = dy + dh1_ln
-    dx_ln, ga = attn_half_bwd(cfg, p, dh1, cache["attn"], row_bias_attn)
+    dx_ln, ga = attn_half_bwd(cfg, p, dh1 * cache["m_attn"], cache["attn"], row_bias_attn)
     dx = dh1 + dx_ln
     g = dict(ga)
     g.update(gm)

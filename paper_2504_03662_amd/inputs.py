@@ -39,6 +39,9 @@ class LayerShape:
     dtype: str = "f32"          # "f32" or "bf16"
     ln_eps: float = 1e-5
     gelu_tanh: bool = False     # tanh form of GELU instead of the erf form
+    drop_attn: int = 0          # dropout of attention probabilities, probability in 1/256ths (0 = none)
+    drop_hidden: int = 0        # dropout of each half's output before the residual, in 1/256ths
+    drop_seed: int = 0          # 64-bit seed of the dropout masks
 
     @property
     def head_dim(self):
