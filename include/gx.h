@@ -83,10 +83,13 @@ enum {
   GX_RECOMPUTE = 32,      /* backward: recompute the forward activations from x; `saved` unused */
   GX_GELU_TANH = 64,      /* feed-forward activation 0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))) instead of
                              the erf form; pass the same flag to the forward and the backward call */
-  GX_WGRAD_BF16 = 128     /* backward, bf16 configurations only: the four weight-matrix gradients (w_qkv, w_o,
+  GX_WGRAD_BF16 = 128,    /* backward, bf16 configurations only: the four weight-matrix gradients (w_qkv, w_o,
                              w_fc1, w_fc2 of gx_grads) point to bf16 buffers; each element is the fp32
                              accumulator rounded once (with GX_ACCUM_WGRAD: old bf16 value + accumulator, added
                              in fp32 and rounded once).  Bias and LayerNorm gradients stay fp32. */
+  GX_DROPOUT = 256        /* dropout variant: cfg->drop_attn, drop_hidden and drop_seed_* are read (without
+                             the flag they are ignored).  Pass the same values to the forward and the backward
+                             call.  Both passes then need a workspace (gx_layer_workspace_bytes). */
 };
 
 /* One rank's share of one block.  tp_rank is informational (which shard the caller passed). */
@@ -95,8 +98,24 @@ typedef struct {
   int32_t tp_attn, tp_ffn, tp_rank;
   int32_t seq, micro_batch;
   int32_t dtype;            /* gx_dtype */
-  int32_t flags;            /* GX_PHASE_* | GX_ROW_BIAS_* | GX_ACCUM_WGRAD | GX_RECOMPUTE | GX_GELU_TANH | GX_WGRAD_BF16 */
+  int32_t flags;            /* GX_PHASE_* | GX_ROW_BIAS_* | GX_ACCUM_WGRAD | GX_RECOMPUTE | GX_GELU_TANH | GX_WGRAD_BF16 |
+                               GX_DROPOUT */
   float ln_eps;             /* LayerNorm epsilon (inside the square root; biased variance) */
+  /* Dropout (only with GX_DROPOUT).  Probabilities are given in 1/256ths, 0..255.  Random bytes come
+   * from Philox4x32-10 keyed by the 64-bit seed (drop_seed_lo, drop_seed_hi); the 16 bytes of one
+   * counter (output words in order, least-significant byte first) serve 16 consecutive elements;
+   * an element is dropped iff its byte < the probability, and kept elements are multiplied by
+   * 256 / (256 - probability).
+   *   drop_attn  : attention probabilities P[b, head, i, j] after the softmax; counter
+   *                (i, j / 16, b * heads + global head, 1), byte j % 16, where the global head is
+   *                (tp_rank % tp_attn) * (heads / tp_attn) + local head, so that the ranks of a group
+   *                draw the masks of the unsharded layer.
+   *   drop_hidden: with both phases in one call, p_attn and p_mlp (bias included) before they are added
+   *                to the residual stream; counter (token, column / 16, 0, 2 for p_attn or 3 for p_mlp),
+   *                byte column % 16.  A single-phase call returns its partial sum undropped; the p_attn /
+   *                p_mlp extra outputs of a two-phase call are the undropped values too. */
+  int32_t drop_attn, drop_hidden;
+  uint32_t drop_seed_lo, drop_seed_hi;
 } gx_layer_cfg;
 
 /* Parameter shards, element type cfg->dtype.  Pointers of a phase that is not selected may be NULL. */
@@ -114,7 +133,8 @@ typedef struct {
 
 /* Host-only check of a configuration (no GPU needed): sizes positive, hidden % heads == 0,
  * heads % tp_attn == 0, ffn % tp_ffn == 0, 0 <= tp_rank < max(tp_attn, tp_ffn), at least one phase,
- * no unknown flag, GX_WGRAD_BF16 only with dtype bf16 (else GX_ERR_DTYPE), and the kernels' limits: bf16 needs head dim 64 or 128, hidden and Fl multiples of 8,
+ * no unknown flag, GX_WGRAD_BF16 only with dtype bf16 (else GX_ERR_DTYPE), with GX_DROPOUT both
+ * probabilities in 0..255 (else GX_ERR_SHAPE), and the kernels' limits: bf16 needs head dim 64 or 128, hidden and Fl multiples of 8,
  * hidden <= 8192; fp32 needs head dim <= 128 and hidden, Fl multiples of 4, hidden <= 4096,
  * seq <= 8192; every activation tensor must stay below 2 GiB. */
 gx_status gx_layer_validate(const gx_layer_cfg* cfg);
@@ -151,7 +171,8 @@ gx_status gx_layer_bwd(const gx_layer_cfg* cfg, const gx_params* params, const v
  * While enabled, every kernel launch site inside gx_layer_fwd / gx_layer_bwd is bracketed by a
  * pair of HIP events on the call's stream and tagged with a kernel class:
  *   GX_KC_LN_FWD, GX_KC_LN_BWD (incl. its two finishing sums), GX_KC_ATTN_FWD, GX_KC_ATTN_BWD (its
- *   three kernels together), GX_KC_COLSUM (both stages), and GX_KC_GEMM + 10 * layout + epilogue
+ *   three kernels together), GX_KC_COLSUM (both stages), GX_KC_DROPOUT (mask generation and the
+ *   dropout passes over a half's output or its gradient), and GX_KC_GEMM + 10 * layout + epilogue
  *   with layout 0 = A[M,K] B[K,N], 1 = A[M,K] B[N,K], 2 = A[K,M] B[K,N] and epilogue 0 = store,
  *   1 = +bias, 2 = +bias +residual, 3 = +bias then GELU, 4 = times GELU', 5 = fp32 store,
  *   6 = fp32 accumulate.
@@ -168,6 +189,7 @@ gx_status gx_layer_bwd(const gx_layer_cfg* cfg, const gx_params* params, const v
 gx_status gx_set_overlap(int on);
 
 enum { GX_KC_LN_FWD = 1, GX_KC_LN_BWD = 2, GX_KC_ATTN_FWD = 3, GX_KC_ATTN_BWD = 4, GX_KC_COLSUM = 5,
+       GX_KC_DROPOUT = 6,
        GX_KC_GEMM = 100 };
 gx_status gx_prof_enable(int on);
 int gx_prof_collect(int* kernel_class, float* ms, int capacity);

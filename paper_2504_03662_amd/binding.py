@@ -16,7 +16,7 @@ GX_OK = 0
 GX_F32, GX_BF16 = 0, 1
 GX_PHASE_ATTN, GX_PHASE_MLP = 1, 2
 GX_ROW_BIAS_ATTN, GX_ROW_BIAS_MLP = 4, 8
-GX_ACCUM_WGRAD, GX_RECOMPUTE, GX_GELU_TANH, GX_WGRAD_BF16 = 16, 32, 64, 128
+GX_ACCUM_WGRAD, GX_RECOMPUTE, GX_GELU_TANH, GX_WGRAD_BF16, GX_DROPOUT = 16, 32, 64, 128, 256
 
 PARAM_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
@@ -28,7 +28,9 @@ GX_KC_LN_FWD, GX_KC_LN_BWD, GX_KC_ATTN_FWD, GX_KC_ATTN_BWD, GX_KC_COLSUM, GX_KC_
 
 class LayerCfg(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("hidden", "heads", "ffn", "tp_attn", "tp_ffn", "tp_rank", "seq",
-                                               "micro_batch", "dtype", "flags")] + [("ln_eps", ctypes.c_float)]
+                                               "micro_batch", "dtype", "flags")] + [
+        ("ln_eps", ctypes.c_float), ("drop_attn", ctypes.c_int32), ("drop_hidden", ctypes.c_int32),
+        ("drop_seed_lo", ctypes.c_uint32), ("drop_seed_hi", ctypes.c_uint32)]
 
 
 class Params(ctypes.Structure):
@@ -128,8 +130,10 @@ def _ptr(t):
 
 
 def make_cfg(hidden, heads, ffn, tp_attn=1, tp_ffn=1, tp_rank=0, seq=1, micro_batch=1, dtype=GX_F32, flags=3,
-             ln_eps=1e-5):
-    return LayerCfg(hidden, heads, ffn, tp_attn, tp_ffn, tp_rank, seq, micro_batch, dtype, flags, ln_eps)
+             ln_eps=1e-5, drop_attn=0, drop_hidden=0, drop_seed=0):
+    """drop_attn / drop_hidden are probabilities in 1/256ths and only read with GX_DROPOUT in flags."""
+    return LayerCfg(hidden, heads, ffn, tp_attn, tp_ffn, tp_rank, seq, micro_batch, dtype, flags, ln_eps,
+                    drop_attn, drop_hidden, drop_seed & 0xFFFFFFFF, (drop_seed >> 32) & 0xFFFFFFFF)
 
 
 def _struct(cls, tensors):

@@ -132,11 +132,31 @@ constexpr int F_BQ = 128, F_BKV = 64;
 // SPLIT = 1: 4 wavefronts, one 64-row K/V tile per step.  SPLIT = 2 (few (sample, head) pairs, so
 // the longest query block is the critical path): 8 wavefronts, two tiles per step; wavefronts w
 // and w + 4 share 32 query rows, take alternate tiles, and merge their (max, sum, O) through LDS.
-template <int SPLIT>
+// Dropout of the probabilities: keep bits (1 = kept) of the whole launch, `wpr` 32-bit words per
+// row; row-major (a query's keys) for the forward and dQ kernels, column-major (a key's queries)
+// for the dK / dV kernel.  Kept probabilities are multiplied by `scale`.
+struct KeepArgs {
+  const unsigned* bits;
+  int wpr;
+  float scale;
+};
+// The 64 keep bits of a lane's two 32 x 32 accumulator tiles: zero the values whose bit is clear.
+// Accumulator register v of tile jt sits at bit 32 jt + 8 (v / 4) + 4 g + v % 4.
+GX_DEVINL void drop_unkept(f32x16 (&a)[2], unsigned long long kw, int g) {
+#pragma unroll
+  for (int jt = 0; jt < 2; jt++) {
+    const unsigned w = (unsigned)(kw >> (32 * jt)) >> (4 * g);
+#pragma unroll
+    for (int v = 0; v < 16; v++)
+      if (!((w >> (8 * (v >> 2) + (v & 3))) & 1u)) a[jt][v] = 0.f;
+  }
+}
+
+template <int SPLIT, bool DROP>
 __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_fwd_kernel(const bf16* __restrict__ qkv,
                                                                           bf16* __restrict__ ctx,
                                                                           float* __restrict__ lse, int S, int nl,
-                                                                          unsigned qkv_bytes) {
+                                                                          unsigned qkv_bytes, KeepArgs keep) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   constexpr int NW = 4 * SPLIT, ROWS = F_BKV * SPLIT, STAGE = 2 * ROWS * ROWB;   // K rows | V rows
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -177,6 +197,10 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_fwd_kernel(const 
     if (j0 <= iw + 31) {                               // wave-uniform: some key of the tile is visible
       const char* kt = smem + (t & 1) * STAGE + half * F_BKV * ROWB;
       const char* vt = kt + ROWS * ROWB;
+      unsigned long long kw = ~0ull;                    // keep bits of this query's 64 keys of the step
+      if (DROP && iw + l32 < S)
+        kw = *reinterpret_cast<const unsigned long long*>(
+            keep.bits + (((size_t)b * nl + h) * S + iw + l32) * keep.wpr + (j0 >> 5));
       f32x16 sacc[2];
 #pragma unroll
       for (int jt = 0; jt < 2; jt++) {
@@ -225,6 +249,7 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_fwd_kernel(const 
           psum += p;
         }
       lsum += psum;
+      if (DROP) drop_unkept(sacc, kw, g);              // the row sum above is the undropped one
       // O^T += V^T P^T, 16 keys per group
       bf16x8 pf[4];
 #pragma unroll
@@ -261,7 +286,7 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_fwd_kernel(const 
   lsum += __shfl_xor(lsum, 32, 64);
   const int i = iw + l32;
   if (i < S) {
-    const float inv = 1.0f / lsum;
+    const float inv = (DROP ? keep.scale : 1.0f) / lsum;
     bf16* orow = ctx + ((size_t)b * S + i) * Hl + h * DH;
 #pragma unroll
     for (int dt = 0; dt < DH / 32; dt++)
@@ -325,12 +350,14 @@ constexpr int KV_OFF_DO = KV_NQ * KV_TILE, KV_OFF_PX = KV_OFF_DO + KV_NDO * KV_T
 constexpr int KV_OFF_SINK = KV_OFF_PX + 2 * KV_PX, KV_SMEM = KV_OFF_SINK + 256;
 constexpr int KV_LOADS = 5;                                  // direct-to-LDS loads per wavefront per tile
 
+template <bool DROP>
 __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __restrict__ qkv,
                                                                   const bf16* __restrict__ dctx,
                                                                   const float* __restrict__ lse,
                                                                   const float* __restrict__ dsum,
                                                                   bf16* __restrict__ dqkv, int S, int nl,
-                                                                  unsigned qkv_bytes, unsigned dctx_bytes) {
+                                                                  unsigned qkv_bytes, unsigned dctx_bytes,
+                                                                  KeepArgs keep) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const bool role_v = wave < KV_PAIRS;
@@ -396,13 +423,26 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
   __builtin_amdgcn_s_waitcnt(0x0F70 | KV_LOADS);                  // tile t0 has landed, t0 + 1 may be in flight
   __syncthreads();
   const int j = jw + l32;
+  // dropout: this key's column of keep bits, one 64-bit word per query tile (both roles read it;
+  // a word is fetched one phase before its use, ahead of that phase's tile requests, so that
+  // waiting for it never waits for a tile)
+  const unsigned* kcol = DROP ? keep.bits + (((size_t)b * nl + h) * S + min(j, S - 1)) * keep.wpr : nullptr;
+  auto keep_word = [&](int t) -> unsigned long long {
+    return (t >= t0 && t < nt) ? *reinterpret_cast<const unsigned long long*>(kcol + 2 * t) : 0ull;
+  };
   // One loop per role (the branch is wavefront-uniform and both loops pass the same number of
   // barriers), so that neither role carries the other's addresses and fragments in registers.
   auto run = [&](auto role_tag) {
     constexpr bool ROLE_V = decltype(role_tag)::value;
     int qslot = 0, dslot = 0;                                     // ring positions of tile n
+    unsigned long long kw = 0, kw_next = 0;                       // role V: tile n; role K: tile n - 1
+    if (DROP && ROLE_V) kw_next = keep_word(t0);
 #pragma unroll 1
     for (int n = t0; n <= nt; n++) {
+      if (DROP) {
+        kw = kw_next;
+        kw_next = keep_word(ROLE_V ? n + 1 : n);
+      }
       stage_load(n + 2, (qslot + 2) & (KV_NQ - 1), dslot == 0 ? 2 : dslot - 1);
       const char* qt = smem + qslot * KV_TILE;                    // Q rows of tile n, then their D
       const char* dot = smem + KV_OFF_DO + dslot * KV_TILE;       // dO rows of tile n, then their lse
@@ -436,6 +476,11 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
               *reinterpret_cast<bf16x8*>(px + (n & 1) * KV_PX + (2 * sub + u) * 1024) = xf[2 * sub + u];
             }
           }
+          if (DROP) {                                             // dV takes the dropped probabilities
+            drop_unkept(sp, kw, g);
+#pragma unroll
+            for (int u = 0; u < 4; u++) xf[u] = pack_half(sp[u >> 1], u & 1);
+          }
           tr_product4<false>(acc, ct, coff, cf, xf);              // dV[j][d] += P^T dO
         }
       } else {
@@ -446,6 +491,13 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
           const unsigned ct = lds_addr(qp);
           cols_issue<0>(ct, coff, cf[0]);
           cols_issue<1>(ct, coff, cf[1]);
+          if (DROP) {                                             // gradient w.r.t. the undropped probabilities
+            drop_unkept(sp, kw, g);
+#pragma unroll
+            for (int sub = 0; sub < 2; sub++)
+#pragma unroll
+              for (int v = 0; v < 16; v++) sp[sub][v] *= keep.scale;
+          }
 #pragma unroll
           for (int sub = 0; sub < 2; sub++) {
             bf16x8 pb[2];
@@ -479,7 +531,7 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
   else run(std::false_type{});
   WAIT_VM0();   // requests for tiles beyond the last one (zero fill) must not outlive the workgroup's LDS
   // accumulator register v of lane l is row 8 (v/4) + 4 g + v%4, column l%32 of its 32x32 tile
-  const float oscale = role_v ? 1.f : scale;
+  const float oscale = role_v ? (DROP ? keep.scale : 1.f) : scale;
   bf16* obase = dqkv + (size_t)b * S * ld + h * DH + (role_v ? 2 * Hl : Hl);
 #pragma unroll
   for (int dt = 0; dt < DH / 32; dt++)
@@ -495,13 +547,13 @@ constexpr int Q_BQ = 128, Q_BKV = 64;
 
 // SPLIT as in the forward kernel; the two halves' dQ partial sums are added through LDS in a
 // fixed order (lower half + upper half).
-template <int SPLIT>
+template <int SPLIT, bool DROP>
 __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_bwd_dq_kernel(const bf16* __restrict__ qkv,
                                                                              const bf16* __restrict__ dctx,
                                                                              const float* __restrict__ lse,
                                                                              const float* __restrict__ dsum,
                                                                              bf16* __restrict__ dqkv, int S, int nl,
-                                                                             unsigned qkv_bytes) {
+                                                                             unsigned qkv_bytes, KeepArgs keep) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   constexpr int NW = 4 * SPLIT, ROWS = Q_BKV * SPLIT, STAGE = 2 * ROWS * ROWB;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -545,6 +597,10 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_bwd_dq_kernel(con
     if (j0 <= iw + 31) {
       const char* kt = smem + (t & 1) * STAGE + half * Q_BKV * ROWB;
       const char* vt = kt + ROWS * ROWB;
+      unsigned long long kw = ~0ull;                    // keep bits of this query's 64 keys of the step
+      if (DROP && i < S)
+        kw = *reinterpret_cast<const unsigned long long*>(
+            keep.bits + (((size_t)b * nl + h) * S + i) * keep.wpr + (j0 >> 5));
       f32x16 sacc[2], pacc[2];
 #pragma unroll
       for (int jt = 0; jt < 2; jt++) {
@@ -555,6 +611,13 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_bwd_dq_kernel(con
           sacc[jt] = MFMA(frag_rows(kt, 32 * jt + l32, s, g), qf[s], sacc[jt]);    // S^T[j][i]
           pacc[jt] = MFMA(frag_rows(vt, 32 * jt + l32, s, g), dof[s], pacc[jt]);   // dP^T[j][i]
         }
+      }
+      if (DROP) {                                      // gradient w.r.t. the undropped probabilities
+        drop_unkept(pacc, kw, g);
+#pragma unroll
+        for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+          for (int v = 0; v < 16; v++) pacc[jt][v] *= keep.scale;
       }
 #pragma unroll
       for (int jt = 0; jt < 2; jt++)
@@ -632,19 +695,29 @@ hipError_t fwd(const AttnArgs& a, hipStream_t s) {
   if (!attn_shape_ok(a)) return hipErrorInvalidValue;
   static bool configured = false;
   if (!configured) {
-    hipError_t e = set_smem(attn_fwd_kernel<1>, 4 * F_BKV * ROWB);
-    if (e == hipSuccess) e = set_smem(attn_fwd_kernel<2>, 8 * F_BKV * ROWB);
+    hipError_t e = set_smem(attn_fwd_kernel<1, false>, 4 * F_BKV * ROWB);
+    if (e == hipSuccess) e = set_smem(attn_fwd_kernel<2, false>, 8 * F_BKV * ROWB);
+    if (e == hipSuccess) e = set_smem(attn_fwd_kernel<1, true>, 4 * F_BKV * ROWB);
+    if (e == hipSuccess) e = set_smem(attn_fwd_kernel<2, true>, 8 * F_BKV * ROWB);
     if (e != hipSuccess) return e;
     configured = true;
   }
   const unsigned qkv_bytes = (unsigned)((size_t)a.B * a.S * 3 * a.nl * DH * 2);
+  const KeepArgs keep{a.rowbits, a.wpr, a.keep_scale};
+  const bool drop = a.rowbits != nullptr;
+  if (drop && a.wpr != 2 * cdiv(a.S, 64)) return hipErrorInvalidValue;
   dim3 grid(cdiv(a.S, F_BQ), a.nl, a.B);
-  if (split_keys(a))
-    hipLaunchKernelGGL(attn_fwd_kernel<2>, grid, dim3(512), 8 * F_BKV * ROWB, s, (const bf16*)a.qkv, (bf16*)a.ctx,
-                       a.lse, a.S, a.nl, qkv_bytes);
-  else
-    hipLaunchKernelGGL(attn_fwd_kernel<1>, grid, dim3(256), 4 * F_BKV * ROWB, s, (const bf16*)a.qkv, (bf16*)a.ctx,
-                       a.lse, a.S, a.nl, qkv_bytes);
+  auto go = [&](auto kernel, int threads, int smem) {
+    hipLaunchKernelGGL(kernel, grid, dim3(threads), smem, s, (const bf16*)a.qkv, (bf16*)a.ctx, a.lse, a.S, a.nl,
+                       qkv_bytes, keep);
+  };
+  if (split_keys(a)) {
+    if (drop) go(attn_fwd_kernel<2, true>, 512, 8 * F_BKV * ROWB);
+    else go(attn_fwd_kernel<2, false>, 512, 8 * F_BKV * ROWB);
+  } else {
+    if (drop) go(attn_fwd_kernel<1, true>, 256, 4 * F_BKV * ROWB);
+    else go(attn_fwd_kernel<1, false>, 256, 4 * F_BKV * ROWB);
+  }
   return hipGetLastError();
 }
 
@@ -656,12 +729,18 @@ hipError_t bwd(const AttnArgs& a, hipStream_t s, hipStream_t s_dq, hipEvent_t fo
   if (!attn_shape_ok(a)) return hipErrorInvalidValue;
   static bool configured = false;
   if (!configured) {
-    hipError_t e = set_smem(attn_bwd_dkv_kernel, KV_SMEM);
-    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<1>, 4 * Q_BKV * ROWB);
-    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<2>, 8 * Q_BKV * ROWB);
+    hipError_t e = set_smem(attn_bwd_dkv_kernel<false>, KV_SMEM);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel<true>, KV_SMEM);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<1, false>, 4 * Q_BKV * ROWB);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<2, false>, 8 * Q_BKV * ROWB);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<1, true>, 4 * Q_BKV * ROWB);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<2, true>, 8 * Q_BKV * ROWB);
     if (e != hipSuccess) return e;
     configured = true;
   }
+  const bool drop = a.rowbits != nullptr;
+  if (drop && (!a.colbits || a.wpr != 2 * cdiv(a.S, 64))) return hipErrorInvalidValue;
+  const KeepArgs keep_rows{a.rowbits, a.wpr, a.keep_scale}, keep_cols{a.colbits, a.wpr, a.keep_scale};
   const unsigned qkv_bytes = (unsigned)((size_t)a.B * a.S * 3 * a.nl * DH * 2);
   const unsigned dctx_bytes = qkv_bytes / 3;
   const long npair = (long)a.B * a.S * a.nl;
@@ -674,16 +753,25 @@ hipError_t bwd(const AttnArgs& a, hipStream_t s, hipStream_t s_dq, hipEvent_t fo
     if ((e = hipEventRecord(fork, s)) != hipSuccess) return e;
     if ((e = hipStreamWaitEvent(s_dq, fork, 0)) != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3(cdiv(a.S, KV_BJ), a.nl, a.B), dim3(64 * KV_NW), KV_SMEM, s,
-                     (const bf16*)a.qkv, (const bf16*)a.dctx, a.lse, a.dsum, (bf16*)a.dqkv, a.S, a.nl, qkv_bytes,
-                     dctx_bytes);
+  auto go_dkv = [&](auto kernel) {
+    hipLaunchKernelGGL(kernel, dim3(cdiv(a.S, KV_BJ), a.nl, a.B), dim3(64 * KV_NW), KV_SMEM, s, (const bf16*)a.qkv,
+                       (const bf16*)a.dctx, a.lse, a.dsum, (bf16*)a.dqkv, a.S, a.nl, qkv_bytes, dctx_bytes,
+                       keep_cols);
+  };
+  if (drop) go_dkv(attn_bwd_dkv_kernel<true>);
+  else go_dkv(attn_bwd_dkv_kernel<false>);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  if (split_keys(a))
-    hipLaunchKernelGGL(attn_bwd_dq_kernel<2>, dim3(cdiv(a.S, Q_BQ), a.nl, a.B), dim3(512), 8 * Q_BKV * ROWB, s_dq,
-                       (const bf16*)a.qkv, (const bf16*)a.dctx, a.lse, a.dsum, (bf16*)a.dqkv, a.S, a.nl, qkv_bytes);
-  else
-    hipLaunchKernelGGL(attn_bwd_dq_kernel<1>, dim3(cdiv(a.S, Q_BQ), a.nl, a.B), dim3(256), 4 * Q_BKV * ROWB, s_dq,
-                       (const bf16*)a.qkv, (const bf16*)a.dctx, a.lse, a.dsum, (bf16*)a.dqkv, a.S, a.nl, qkv_bytes);
+  auto go_dq = [&](auto kernel, int threads, int smem) {
+    hipLaunchKernelGGL(kernel, dim3(cdiv(a.S, Q_BQ), a.nl, a.B), dim3(threads), smem, s_dq, (const bf16*)a.qkv,
+                       (const bf16*)a.dctx, a.lse, a.dsum, (bf16*)a.dqkv, a.S, a.nl, qkv_bytes, keep_rows);
+  };
+  if (split_keys(a)) {
+    if (drop) go_dq(attn_bwd_dq_kernel<2, true>, 512, 8 * Q_BKV * ROWB);
+    else go_dq(attn_bwd_dq_kernel<2, false>, 512, 8 * Q_BKV * ROWB);
+  } else {
+    if (drop) go_dq(attn_bwd_dq_kernel<1, true>, 256, 4 * Q_BKV * ROWB);
+    else go_dq(attn_bwd_dq_kernel<1, false>, 256, 4 * Q_BKV * ROWB);
+  }
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (two) {
     if ((e = hipEventRecord(join, s_dq)) != hipSuccess) return e;

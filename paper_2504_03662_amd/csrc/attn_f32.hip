@@ -17,11 +17,29 @@ GX_DEVINL HeadView head_view(const float* qkv, int b, int h, int S, int nl, int 
   return HeadView{base, base + Hl, base + 2 * Hl, 3 * Hl};
 }
 
+// Dropout of the probabilities: keep bits of (sample, head) pair bh, row-major (bit j % 32 of word
+// j / 32 of query row i); a null array keeps everything.
+struct KeepBits {
+  const unsigned* row;   // this pair's [S][wpr] words, or null
+  int wpr;
+  float scale;           // multiplier of a kept probability
+  GX_DEVINL float factor(int i, int j) const {
+    if (!row) return 1.0f;
+    return ((row[(size_t)i * wpr + (j >> 5)] >> (j & 31)) & 1u) ? scale : 0.0f;
+  }
+};
+GX_DEVINL KeepBits keep_view(const unsigned* rowbits, int wpr, float scale, int b, int h, int S, int nl) {
+  return KeepBits{rowbits ? rowbits + ((size_t)b * nl + h) * S * wpr : nullptr, wpr, scale};
+}
+
 __global__ void __launch_bounds__(64) attn_fwd_f32_kernel(const float* __restrict__ qkv, float* __restrict__ ctx,
-                                                          float* __restrict__ lse, int S, int nl, int dh) {
+                                                          float* __restrict__ lse, int S, int nl, int dh,
+                                                          const unsigned* __restrict__ rowbits, int wpr,
+                                                          float keep_scale) {
   extern __shared__ float sc[];          // [S] scores of this row, then probabilities
   const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
   const HeadView hv = head_view(qkv, b, h, S, nl, dh);
+  const KeepBits kb = keep_view(rowbits, wpr, keep_scale, b, h, S, nl);
   const float scale = rsqrtf((float)dh);
   const float* qi = hv.q + (size_t)i * hv.ld;
   float mx = -INFINITY;
@@ -37,7 +55,7 @@ __global__ void __launch_bounds__(64) attn_fwd_f32_kernel(const float* __restric
   float sum = 0.f;
   for (int j = lane; j <= i; j += 64) {
     const float p = expf(sc[j] - mx);
-    sc[j] = p;
+    sc[j] = p * kb.factor(i, j);         // the normaliser below is the sum of the undropped values
     sum += p;
   }
   sum = wave_sum(sum);
@@ -56,10 +74,13 @@ __global__ void __launch_bounds__(64) attn_bwd_dq_f32_kernel(const float* __rest
                                                              const float* __restrict__ ctx,
                                                              const float* __restrict__ dctx,
                                                              const float* __restrict__ lse, float* __restrict__ dsum,
-                                                             float* __restrict__ dqkv, int S, int nl, int dh) {
+                                                             float* __restrict__ dqkv, int S, int nl, int dh,
+                                                             const unsigned* __restrict__ rowbits, int wpr,
+                                                             float keep_scale) {
   extern __shared__ float ds[];          // [S]
   const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
   const HeadView hv = head_view(qkv, b, h, S, nl, dh);
+  const KeepBits kb = keep_view(rowbits, wpr, keep_scale, b, h, S, nl);
   const int Hl = nl * dh;
   const float scale = rsqrtf((float)dh);
   const float* qi = hv.q + (size_t)i * hv.ld;
@@ -75,7 +96,7 @@ __global__ void __launch_bounds__(64) attn_bwd_dq_f32_kernel(const float* __rest
     const float* vj = hv.v + (size_t)j * hv.ld;
     float s = 0.f, dp = 0.f;
     for (int d = 0; d < dh; d++) { s = fmaf(qi[d], kj[d], s); dp = fmaf(doi[d], vj[d], dp); }
-    ds[j] = expf(s * scale - l) * (dp - dd);
+    ds[j] = expf(s * scale - l) * (dp * kb.factor(i, j) - dd);
   }
   __syncthreads();
   float* dq = dqkv + ((size_t)b * S + i) * 3 * Hl + h * dh;
@@ -91,8 +112,10 @@ __global__ void __launch_bounds__(64) attn_bwd_dkv_f32_kernel(const float* __res
                                                               const float* __restrict__ dctx,
                                                               const float* __restrict__ lse,
                                                               const float* __restrict__ dsum,
-                                                              float* __restrict__ dqkv, int S, int nl, int dh) {
-  extern __shared__ float sm[];          // p[S] | ds[S]
+                                                              float* __restrict__ dqkv, int S, int nl, int dh,
+                                                              const unsigned* __restrict__ rowbits, int wpr,
+                                                              float keep_scale) {
+  extern __shared__ float sm[];          // p[S] (as it multiplies V: dropped and rescaled) | ds[S]
   float* pp = sm;
   float* ds = sm + S;
   const int j = blockIdx.x, h = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
@@ -103,14 +126,16 @@ __global__ void __launch_bounds__(64) attn_bwd_dkv_f32_kernel(const float* __res
   const float* vj = hv.v + (size_t)j * hv.ld;
   const float* lrow = lse + ((size_t)b * nl + h) * S;
   const float* drow = dsum + ((size_t)b * nl + h) * S;
+  const KeepBits kb = keep_view(rowbits, wpr, keep_scale, b, h, S, nl);
   for (int i = j + lane; i < S; i += 64) {
     const float* qi = hv.q + (size_t)i * hv.ld;
     const float* doi = dctx + ((size_t)b * S + i) * Hl + h * dh;
     float s = 0.f, dp = 0.f;
     for (int d = 0; d < dh; d++) { s = fmaf(qi[d], kj[d], s); dp = fmaf(doi[d], vj[d], dp); }
     const float p = expf(s * scale - lrow[i]);
-    pp[i] = p;
-    ds[i] = p * (dp - drow[i]);
+    const float keep = kb.factor(i, j);
+    pp[i] = p * keep;
+    ds[i] = p * (dp * keep - drow[i]);
   }
   __syncthreads();
   float* dk = dqkv + ((size_t)b * S + j) * 3 * Hl + Hl + h * dh;
@@ -132,7 +157,7 @@ hipError_t attn_fwd_f32(const AttnArgs& a, hipStream_t s) {
   if (a.S > 8192) return hipErrorInvalidValue;
   dim3 grid(a.S, a.nl, a.B);
   hipLaunchKernelGGL(attn_fwd_f32_kernel, grid, dim3(64), a.S * sizeof(float), s, (const float*)a.qkv,
-                     (float*)a.ctx, a.lse, a.S, a.nl, a.dh);
+                     (float*)a.ctx, a.lse, a.S, a.nl, a.dh, a.rowbits, a.wpr, a.keep_scale);
   return hipGetLastError();
 }
 
@@ -140,11 +165,12 @@ hipError_t attn_bwd_f32(const AttnArgs& a, hipStream_t s) {
   if (a.S > 8192) return hipErrorInvalidValue;
   dim3 grid(a.S, a.nl, a.B);
   hipLaunchKernelGGL(attn_bwd_dq_f32_kernel, grid, dim3(64), a.S * sizeof(float), s, (const float*)a.qkv,
-                     (const float*)a.ctx, (const float*)a.dctx, a.lse, a.dsum, (float*)a.dqkv, a.S, a.nl, a.dh);
+                     (const float*)a.ctx, (const float*)a.dctx, a.lse, a.dsum, (float*)a.dqkv, a.S, a.nl, a.dh, a.rowbits,
+                     a.wpr, a.keep_scale);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(attn_bwd_dkv_f32_kernel, grid, dim3(64), 2 * a.S * sizeof(float), s, (const float*)a.qkv,
-                     (const float*)a.dctx, a.lse, a.dsum, (float*)a.dqkv, a.S, a.nl, a.dh);
+                     (const float*)a.dctx, a.lse, a.dsum, (float*)a.dqkv, a.S, a.nl, a.dh, a.rowbits, a.wpr, a.keep_scale);
   return hipGetLastError();
 }
 

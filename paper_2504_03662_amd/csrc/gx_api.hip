@@ -23,8 +23,10 @@ namespace {
 
 using namespace gx;
 
+static_assert(sizeof(gx_layer_cfg) == 15 * 4, "gx_layer_cfg is 15 packed 32-bit fields");
+
 constexpr int ALL_FLAGS = GX_PHASE_ATTN | GX_PHASE_MLP | GX_ROW_BIAS_ATTN | GX_ROW_BIAS_MLP | GX_ACCUM_WGRAD |
-                          GX_RECOMPUTE | GX_GELU_TANH | GX_WGRAD_BF16;
+                          GX_RECOMPUTE | GX_GELU_TANH | GX_WGRAD_BF16 | GX_DROPOUT;
 
 struct Dims {
   long T, H, Hl, Fl, S, B, nl, dh;
@@ -127,6 +129,54 @@ Work plan_work(const gx_layer_cfg& c, Arena& a) {
   return w;
 }
 
+// Dropout variant: what the configuration asks for and the scratch it needs.
+struct Drop {
+  bool attn = false, hidden = false;   // probabilities; the two halves' outputs (two-phase calls only)
+  int t_attn = 0, t_hidden = 0;        // drop probabilities in 1/256ths
+  unsigned k0 = 0, k1 = 0;             // generator key
+  int head0 = 0;                       // global index of this rank's first head
+};
+
+Drop drop_of(const gx_layer_cfg& c) {
+  Drop d;
+  if (!(c.flags & GX_DROPOUT)) return d;
+  const bool attn = c.flags & GX_PHASE_ATTN, mlp = c.flags & GX_PHASE_MLP;
+  d.t_attn = c.drop_attn;
+  d.t_hidden = c.drop_hidden;
+  d.k0 = c.drop_seed_lo;
+  d.k1 = c.drop_seed_hi;
+  d.attn = attn && c.drop_attn > 0;
+  d.hidden = attn && mlp && c.drop_hidden > 0;
+  d.head0 = (c.tp_rank % c.tp_attn) * (c.heads / c.tp_attn);
+  return d;
+}
+
+struct DropBufs {
+  unsigned *rowbits, *colbits;   // keep bits of the attention probabilities
+  void* partial;                 // a half's output before dropout, when the caller does not ask for it
+  void *dym, *dh1m;              // upstream gradients after the output masks
+};
+
+DropBufs plan_drop(const gx_layer_cfg& c, Arena& a, bool bwd) {
+  DropBufs b;
+  memset(&b, 0, sizeof(b));
+  const Drop dr = drop_of(c);
+  const Dims d = dims_of(c);
+  if (dr.attn) {
+    const size_t bytes = (size_t)d.B * d.nl * d.S * attn_mask_wpr((int)d.S) * 4;
+    b.rowbits = static_cast<unsigned*>(a.take(bytes));
+    if (bwd) b.colbits = static_cast<unsigned*>(a.take(bytes));
+  }
+  if (dr.hidden) {
+    if (!bwd || (c.flags & GX_RECOMPUTE)) b.partial = a.take(d.T * d.H * d.e);
+    if (bwd) {
+      b.dym = a.take(d.T * d.H * d.e);
+      b.dh1m = a.take(d.T * d.H * d.e);
+    }
+  }
+  return b;
+}
+
 gx_status validate(const gx_layer_cfg* c) {
   if (!c) return GX_ERR_NULL;
   if (c->dtype != GX_F32 && c->dtype != GX_BF16) return GX_ERR_DTYPE;
@@ -135,6 +185,8 @@ gx_status validate(const gx_layer_cfg* c) {
     return GX_ERR_SHAPE;
   if ((c->flags & ~ALL_FLAGS) || !(c->flags & (GX_PHASE_ATTN | GX_PHASE_MLP))) return GX_ERR_FLAGS;
   if ((c->flags & GX_WGRAD_BF16) && c->dtype != GX_BF16) return GX_ERR_DTYPE;
+  if ((c->flags & GX_DROPOUT) && (c->drop_attn < 0 || c->drop_attn > 255 || c->drop_hidden < 0 || c->drop_hidden > 255))
+    return GX_ERR_SHAPE;
   if (c->hidden % c->heads || c->heads % c->tp_attn || c->ffn % c->tp_ffn) return GX_ERR_DIVIS;
   const int tpmax = c->tp_attn > c->tp_ffn ? c->tp_attn : c->tp_ffn;
   if (c->tp_rank < 0 || c->tp_rank >= tpmax) return GX_ERR_SHAPE;
@@ -280,11 +332,37 @@ __global__ void fill_zero_kernel(float* p, int n) {
   if (i < n) p[i] = 0.f;
 }
 
+hipError_t dropout_p(const Dims& d, const Drop& dr, const void* in, const void* resid, void* out, unsigned stream,
+                     hipStream_t s) {
+  ProfScope ps(GX_KC_DROPOUT, s);
+  return dropout_rows(d.bf, in, resid, out, (int)d.T, (int)d.H, stream, dr.k0, dr.k1, dr.t_hidden, s);
+}
+
+// Keep bits of the attention probabilities for this call (both layouts for a backward pass).
+gx_status make_attn_mask(const gx_layer_cfg& c, const DropBufs& db, hipStream_t st) {
+  const Drop dr = drop_of(c);
+  if (!dr.attn) return GX_OK;
+  const Dims d = dims_of(c);
+  ProfScope ps(GX_KC_DROPOUT, st);
+  GX_TRY(attn_mask(db.rowbits, db.colbits, (int)d.B, (int)d.nl, (int)d.S, c.heads, dr.head0, dr.k0, dr.k1, dr.t_attn,
+                   st));
+  return GX_OK;
+}
+
+void set_attn_drop(AttnArgs& a, const Dims& d, const Drop& dr, const DropBufs& db) {
+  if (!dr.attn) return;
+  a.rowbits = db.rowbits;
+  a.colbits = db.colbits;
+  a.wpr = attn_mask_wpr((int)d.S);
+  a.keep_scale = 256.0f / (256.0f - (float)dr.t_attn);
+}
+
 // Forward kernel sequence.  `for_backward_only` skips the products whose results the backward
 // pass does not need (used when recomputing activations).
 gx_status run_fwd(const gx_layer_cfg& c, const gx_params& p, const void* x, void* y, void* p_attn, void* p_mlp,
-                  const Saved& sv, bool for_backward_only, hipStream_t st) {
+                  const Saved& sv, const DropBufs& db, bool for_backward_only, hipStream_t st) {
   const Dims d = dims_of(c);
+  const Drop dr = drop_of(c);
   const bool attn = c.flags & GX_PHASE_ATTN, mlp = c.flags & GX_PHASE_MLP;
   const void* h1 = x;
   if (attn) {
@@ -297,9 +375,18 @@ gx_status run_fwd(const gx_layer_cfg& c, const gx_params& p, const void* x, void
     memset(&a, 0, sizeof(a));
     a.qkv = sv.qkv; a.ctx = sv.ctx; a.lse = sv.lse;
     a.B = (int)d.B; a.S = (int)d.S; a.nl = (int)d.nl; a.dh = (int)d.dh;
+    set_attn_drop(a, d, dr, db);
     { ProfScope ps(GX_KC_ATTN_FWD, st);
     GX_TRY(d.bf ? attn_fwd_bf16(a, st) : attn_fwd_f32(a, st)); }
-    if (mlp) {
+    if (mlp && dr.hidden) {
+      // the half's output goes to memory undropped, then one pass drops it and adds the residual
+      void* pa = p_attn ? p_attn : db.partial;
+      GemmArgs o = gargs(sv.ctx, p.w_o, pa, d.T, d.H, d.Hl, d.Hl, d.H, d.H);
+      o.bias = (c.flags & GX_ROW_BIAS_ATTN) ? p.b_o : nullptr;
+      GX_TRY(gemm(d, LAY_NN, EPI_BIAS, o, st));
+      GX_TRY(dropout_p(d, dr, pa, x, sv.h1, 2u, st));
+      h1 = sv.h1;
+    } else if (mlp) {
       GemmArgs o = gargs(sv.ctx, p.w_o, sv.h1, d.T, d.H, d.Hl, d.Hl, d.H, d.H);
       o.bias = (c.flags & GX_ROW_BIAS_ATTN) ? p.b_o : nullptr;
       o.resid = x;
@@ -321,9 +408,13 @@ gx_status run_fwd(const gx_layer_cfg& c, const gx_params& p, const void* x, void
     f1.gelu_tanh = (c.flags & GX_GELU_TANH) ? 1 : 0;
     GX_TRY(gemm(d, LAY_NN, EPI_GELU, f1, st));
     if (!for_backward_only) {
-      GemmArgs f2 = gargs(sv.act, p.w_fc2, attn ? y : p_mlp, d.T, d.H, d.Fl, d.Fl, d.H, d.H);
+      void* pm = p_mlp ? p_mlp : db.partial;
+      GemmArgs f2 = gargs(sv.act, p.w_fc2, dr.hidden ? pm : attn ? y : p_mlp, d.T, d.H, d.Fl, d.Fl, d.H, d.H);
       f2.bias = (c.flags & GX_ROW_BIAS_MLP) ? p.b_fc2 : nullptr;
-      if (attn) {
+      if (dr.hidden) {
+        GX_TRY(gemm(d, LAY_NN, EPI_BIAS, f2, st));
+        GX_TRY(dropout_p(d, dr, pm, h1, y, 3u, st));
+      } else if (attn) {
         f2.resid = h1;
         f2.aux = p_mlp;
         GX_TRY(gemm(d, LAY_NN, EPI_RESID, f2, st));
@@ -348,8 +439,9 @@ gx_status bias_grad(const Dims& d, const gx_layer_cfg& c, bool enabled, const vo
 }
 
 gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, const void* dy, void* dx,
-                  const gx_grads& gr, const Saved& sv, const Work& w, hipStream_t st) {
+                  const gx_grads& gr, const Saved& sv, const Work& w, const DropBufs& db, hipStream_t st) {
   const Dims d = dims_of(c);
+  const Drop dr = drop_of(c);
   const bool attn = c.flags & GX_PHASE_ATTN, mlp = c.flags & GX_PHASE_MLP;
   const bool acc = c.flags & GX_ACCUM_WGRAD;
   // weight gradient A^T B into fp32 (store or add) or, on request, into bf16: a plain rounding
@@ -366,14 +458,19 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
   const void* dcur = dy;           // gradient arriving at the attention half's output
   if (mlp) {
     const void* h1 = attn ? sv.h1 : x;
-    // side: db2 needs only dy
-    // row-parallel FC2: bias and weight gradients need only dy and saved activations: side
+    // gradient reaching the feed-forward half's output: dy itself, or dy through that output's mask
+    const void* dp = dy;
+    if (dr.hidden) {
+      GX_TRY(dropout_p(d, dr, dy, nullptr, db.dym, 3u, st));
+      dp = db.dym;
+    }
+    // row-parallel FC2: bias and weight gradients need only dp and saved activations: side
     hipStream_t sd = fk.branch();
-    if ((s = bias_grad(d, c, c.flags & GX_ROW_BIAS_MLP, dy, d.H, w.part, gr.b_fc2, sd)) != GX_OK) return s;
-    GemmArgs w2 = gargs(sv.act, dy, gr.w_fc2, d.Fl, d.H, d.T, d.Fl, d.H, d.H);
+    if ((s = bias_grad(d, c, c.flags & GX_ROW_BIAS_MLP, dp, d.H, w.part, gr.b_fc2, sd)) != GX_OK) return s;
+    GemmArgs w2 = gargs(sv.act, dp, gr.w_fc2, d.Fl, d.H, d.T, d.Fl, d.H, d.H);
     GX_TRY(wgrad(w2, sd));
     // input gradient fused with GELU' on the caller's stream
-    GemmArgs dz = gargs(dy, p.w_fc2, w.dz, d.T, d.Fl, d.H, d.H, d.H, d.Fl);
+    GemmArgs dz = gargs(dp, p.w_fc2, w.dz, d.T, d.Fl, d.H, d.H, d.H, d.Fl);
     dz.z = sv.z;
     dz.gelu_tanh = (c.flags & GX_GELU_TANH) ? 1 : 0;
     GX_TRY(gemm(d, LAY_NT, EPI_DGELU, dz, st));
@@ -399,16 +496,22 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
   if (attn) {
     // row-parallel output projection: bias and weight gradients on the side (the weight gradient
     // has few tiles and overlaps the attention kernels), input gradient on the caller's stream
+    const void* dp = dcur;           // gradient reaching the attention half's output
+    if (dr.hidden) {
+      GX_TRY(dropout_p(d, dr, dcur, nullptr, db.dh1m, 2u, st));
+      dp = db.dh1m;
+    }
     hipStream_t sd = fk.branch();
-    if ((s = bias_grad(d, c, c.flags & GX_ROW_BIAS_ATTN, dcur, d.H, w.part, gr.b_o, sd)) != GX_OK) return s;
-    GemmArgs wo = gargs(sv.ctx, dcur, gr.w_o, d.Hl, d.H, d.T, d.Hl, d.H, d.H);
+    if ((s = bias_grad(d, c, c.flags & GX_ROW_BIAS_ATTN, dp, d.H, w.part, gr.b_o, sd)) != GX_OK) return s;
+    GemmArgs wo = gargs(sv.ctx, dp, gr.w_o, d.Hl, d.H, d.T, d.Hl, d.H, d.H);
     GX_TRY(wgrad(wo, sd));
-    GemmArgs dc = gargs(dcur, p.w_o, w.dctx, d.T, d.Hl, d.H, d.H, d.H, d.Hl);
+    GemmArgs dc = gargs(dp, p.w_o, w.dctx, d.T, d.Hl, d.H, d.H, d.H, d.Hl);
     GX_TRY(gemm(d, LAY_NT, EPI_STORE, dc, st));
     AttnArgs a;
     memset(&a, 0, sizeof(a));
     a.qkv = sv.qkv; a.ctx = sv.ctx; a.lse = sv.lse; a.dctx = w.dctx; a.dqkv = w.dqkv; a.dsum = w.dsum;
     a.B = (int)d.B; a.S = (int)d.S; a.nl = (int)d.nl; a.dh = (int)d.dh;
+    set_attn_drop(a, d, dr, db);
     { ProfScope ps(GX_KC_ATTN_BWD, st);
     GX_TRY(d.bf ? attn_bwd_bf16(a, st, fk.side != st ? g_side.s2 : st, g_side.attn_fork, g_side.attn_join) : attn_bwd_f32(a, st));
     if (d.bf && fk.side != st) fk.used = true; }
@@ -477,18 +580,20 @@ size_t gx_layer_saved_bytes(const gx_layer_cfg* cfg) {
 }
 
 size_t gx_layer_workspace_bytes(const gx_layer_cfg* cfg, int is_backward) {
-  if (validate(cfg) != GX_OK || !is_backward) return 0;
+  if (validate(cfg) != GX_OK) return 0;
   Arena a(nullptr);
-  plan_work(*cfg, a);
+  if (is_backward) plan_work(*cfg, a);
+  plan_drop(*cfg, a, is_backward != 0);
   return a.off;
 }
 
 gx_status gx_layer_fwd(const gx_layer_cfg* cfg, const gx_params* params, const void* x, void* y, void* p_attn,
                        void* p_mlp, void* saved, void* workspace, void* hip_stream) {
-  (void)workspace;
   gx_status s = validate(cfg);
   if (s != GX_OK) return s;
   if (!params || !x || !saved) return GX_ERR_NULL;
+  if (!workspace && gx_layer_workspace_bytes(cfg, 0) != 0) return GX_ERR_NULL;
+  if (misaligned(workspace)) return GX_ERR_ALIGN;
   const bool attn = cfg->flags & GX_PHASE_ATTN, mlp = cfg->flags & GX_PHASE_MLP;
   if (attn && mlp && !y) return GX_ERR_NULL;
   if (attn && !mlp && !p_attn) return GX_ERR_NULL;
@@ -499,7 +604,11 @@ gx_status gx_layer_fwd(const gx_layer_cfg* cfg, const gx_params* params, const v
   if ((s = check_arch()) != GX_OK) return s;
   Arena a(saved);
   const Saved sv = plan_saved(*cfg, a);
-  return run_fwd(*cfg, *params, x, y, p_attn, p_mlp, sv, false, static_cast<hipStream_t>(hip_stream));
+  Arena wa(workspace);
+  const DropBufs db = plan_drop(*cfg, wa, false);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if ((s = make_attn_mask(*cfg, db, st)) != GX_OK) return s;
+  return run_fwd(*cfg, *params, x, y, p_attn, p_mlp, sv, db, false, st);
 }
 
 gx_status gx_layer_bwd(const gx_layer_cfg* cfg, const gx_params* params, const void* x, const void* dy, void* dx,
@@ -516,13 +625,15 @@ gx_status gx_layer_bwd(const gx_layer_cfg* cfg, const gx_params* params, const v
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   Arena wa(workspace);
   const Work w = plan_work(*cfg, wa);
+  const DropBufs db = plan_drop(*cfg, wa, true);
   Arena sa(recompute ? w.recomputed : const_cast<void*>(saved));
   const Saved sv = plan_saved(*cfg, sa);
+  if ((s = make_attn_mask(*cfg, db, st)) != GX_OK) return s;
   if (recompute) {
-    s = run_fwd(*cfg, *params, x, nullptr, nullptr, nullptr, sv, true, st);
+    s = run_fwd(*cfg, *params, x, nullptr, nullptr, nullptr, sv, db, true, st);
     if (s != GX_OK) return s;
   }
-  return run_bwd(*cfg, *params, x, dy, dx, *grads, sv, w, st);
+  return run_bwd(*cfg, *params, x, dy, dx, *grads, sv, w, db, st);
 }
 
 const char* gx_status_str(gx_status s) {

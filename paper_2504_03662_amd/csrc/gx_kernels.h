@@ -52,6 +52,13 @@ struct AttnArgs {
   void* dqkv;         // bwd out, same layout as qkv
   float* dsum;        // bwd scratch: rowsum(dctx * ctx)
   int B, S, nl, dh;
+  // dropout of the probabilities (rowbits == nullptr: none): keep bits from attn_mask, row-major for
+  // the forward and dQ kernels, column-major for dK / dV (bf16 path; the fp32 path reads rowbits
+  // throughout), wpr words per row, kept probabilities multiplied by keep_scale
+  const unsigned* rowbits;
+  const unsigned* colbits;
+  int wpr;
+  float keep_scale;
 };
 hipError_t attn_fwd_bf16(const AttnArgs& a, hipStream_t s);
 // s_dq may equal s (everything in order on one stream); otherwise the dQ kernel runs on s_dq between
@@ -59,6 +66,18 @@ hipError_t attn_fwd_bf16(const AttnArgs& a, hipStream_t s);
 hipError_t attn_bwd_bf16(const AttnArgs& a, hipStream_t s, hipStream_t s_dq, hipEvent_t fork, hipEvent_t join);
 hipError_t attn_fwd_f32(const AttnArgs& a, hipStream_t s);
 hipError_t attn_bwd_f32(const AttnArgs& a, hipStream_t s);
+
+// Dropout (Philox4x32-10 bytes; an element is dropped iff its byte < t, t in 0..255).
+// Keep bits of the attention probabilities of B x nl (sample, local head) pairs, heads `head0`..
+// of a model with `heads` heads: rowbits / colbits are [B * nl * S * attn_mask_wpr(S)] words
+// (colbits may be null).  Counter (i, j / 16, b * heads + head0 + h, 1), byte j % 16.
+int attn_mask_wpr(int S);
+hipError_t attn_mask(unsigned* rowbits, unsigned* colbits, int B, int nl, int S, int heads, int head0, unsigned k0,
+                     unsigned k1, int t, hipStream_t s);
+// out = (resid ? resid : 0) + keep * 256 / (256 - t) * in over [rows, cols]; counter
+// (row, column / 16, 0, stream), byte column % 16.  out may alias in.
+hipError_t dropout_rows(bool bf16, const void* in, const void* resid, void* out, int rows, int cols,
+                        unsigned stream, unsigned k0, unsigned k1, int t, hipStream_t s);
 
 // Row-wise and column-sum kernels, templated on storage type through the `bf16` switch.
 // LayerNorm forward: y = g * (x - mean) * rstd + b; writes mean/rstd per row.

@@ -23,8 +23,10 @@ def cfg_of(shape: LayerShape, phase="both", row_bias_attn=True, row_bias_mlp=Tru
     flags |= gx.GX_RECOMPUTE if recompute else 0
     flags |= gx.GX_GELU_TANH if shape.gelu_tanh else 0
     flags |= gx.GX_WGRAD_BF16 if wgrad_bf16 else 0
+    flags |= gx.GX_DROPOUT if (shape.drop_attn or shape.drop_hidden) else 0
     return gx.make_cfg(shape.hidden, shape.heads, shape.ffn, shape.tp_attn, shape.tp_ffn, shape.tp_rank, shape.seq,
-                       shape.micro_batch, gx.GX_BF16 if shape.dtype == "bf16" else gx.GX_F32, flags, shape.ln_eps)
+                       shape.micro_batch, gx.GX_BF16 if shape.dtype == "bf16" else gx.GX_F32, flags, shape.ln_eps,
+                       shape.drop_attn, shape.drop_hidden, shape.drop_seed)
 
 
 def to_device(a, dtype, device="cuda:0"):
@@ -82,7 +84,9 @@ class DeviceLayer:
             p_attn = out if out is not None else self.empty_act()
         else:
             p_mlp = out if out is not None else self.empty_act()
-        gx.layer_fwd(cfg, self.params, x, y, p_attn, p_mlp, saved, None, torch.cuda.current_stream().cuda_stream)
+        nws = gx.layer_workspace_bytes(cfg, False)
+        ws = self._buf("work_fwd", nws) if nws else None
+        gx.layer_fwd(cfg, self.params, x, y, p_attn, p_mlp, saved, ws, torch.cuda.current_stream().cuda_stream)
         return dict(y=y, p_attn=p_attn, p_mlp=p_mlp)
 
     def backward(self, x, dy, phase="both", row_bias_attn=True, row_bias_mlp=True, accumulate=False, recompute=False,

@@ -43,7 +43,8 @@ def test_validate_accepts_the_graded_workloads(lib):
 
 
 @pytest.mark.parametrize("kw,status", [
-    (dict(hidden=0), 2), (dict(seq=-1), 2), (dict(dtype=7), 4), (dict(flags=0), 6), (dict(flags=3 | 1024), 6), (dict(flags=3 | 256), 6),
+    (dict(hidden=0), 2), (dict(seq=-1), 2), (dict(dtype=7), 4), (dict(flags=0), 6), (dict(flags=3 | 1024), 6), (dict(flags=3 | 512), 6),
+    (dict(flags=3 | gx.GX_DROPOUT, drop_attn=256), 2), (dict(flags=3 | gx.GX_DROPOUT, drop_hidden=-1), 2),
     (dict(dtype=gx.GX_F32, hidden=256, heads=4, ffn=1024, tp_attn=1, tp_ffn=1, flags=3 | gx.GX_WGRAD_BF16), 4),
     (dict(heads=33), 3), (dict(tp_attn=3), 3), (dict(ffn=16385), 3), (dict(tp_rank=4), 2),
     (dict(hidden=1024, heads=32), 2),                 # bf16 head dim 32 is not supported (64 and 128 are)
@@ -57,6 +58,25 @@ def test_validate_rejects(lib, kw, status):
 
 def test_bf16_weight_gradient_flag_is_accepted_for_bf16(lib):
     assert gx.layer_validate(_cfg(flags=3 | gx.GX_WGRAD_BF16 | gx.GX_ACCUM_WGRAD)) == gx.GX_OK
+
+
+def test_dropout_fields_and_workspace(lib):
+    # without the flag the fields are ignored, and the forward pass needs no workspace
+    assert gx.layer_validate(_cfg(drop_attn=999)) == gx.GX_OK
+    assert gx.layer_workspace_bytes(_cfg(), False) == 0
+    T, H, S, B, nl = 4096, 4096, 2048, 2, 8
+    bits = B * nl * S * (2 * (S // 64)) * 4                       # keep bits of the probabilities, one layout
+    both = _cfg(flags=3 | gx.GX_DROPOUT, drop_attn=26, drop_hidden=26, drop_seed=(5 << 32) | 7)
+    assert gx.layer_validate(both) == gx.GX_OK
+    assert (both.drop_seed_lo, both.drop_seed_hi) == (7, 5)
+    assert gx.layer_workspace_bytes(both, False) == bits + T * H * 2
+    plain_bwd = gx.layer_workspace_bytes(_cfg(), True)
+    assert gx.layer_workspace_bytes(both, True) == plain_bwd + 2 * bits + 2 * T * H * 2
+    # a lone half has no output dropout; a zero probability costs nothing
+    lone = _cfg(flags=gx.GX_PHASE_ATTN | gx.GX_DROPOUT, drop_attn=26, drop_hidden=26)
+    assert gx.layer_workspace_bytes(lone, False) == bits
+    none = _cfg(flags=3 | gx.GX_DROPOUT)
+    assert gx.layer_workspace_bytes(none, False) == 0
 
 
 def test_size_queries(lib):

@@ -147,6 +147,56 @@ def test_recompute_and_accumulate_flags(dtype):
         check("acc d" + n, to_host(layer.grads[n]), 2.0 * ref["grads"][n], TOL[dtype])
 
 
+# dropout variant: masks from the counter-based generator, drawn independently on both sides ------
+
+SEED64 = 0x1234567890ABCDEF
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("phase,recompute", [("both", False), ("both", True), ("attn", False)])
+def test_dropout_variant(dtype, phase, recompute):
+    # rank 1 of 2 attention ranks: the masks are those of global heads 2 and 3
+    hidden, heads = (256, 4) if dtype == "f32" else (512, 4)
+    shape = I.LayerShape(hidden, heads, 1096, 2, 1, 1, 150, 2, dtype, drop_attn=40, drop_hidden=30, drop_seed=SEED64)
+    params, x, dy = _case(shape, 98)
+    want = phase == "both" and not recompute
+    gpu, ref, _ = run_both(shape, params, x, dy, phase, recompute=recompute, want_partials=want)
+    compare(gpu, ref, TOL[dtype], phase, want_partials=want)
+    # and the masks matter: the plain layer is measurably elsewhere
+    plain = O.layer_fwd(shape.with_(drop_attn=0, drop_hidden=0), params, x, phase)
+    key = "y" if phase == "both" else "p_attn"
+    assert np.abs(plain[key] - ref[key]).max() > 4 * TOL[dtype] * np.abs(ref[key]).max()
+
+
+@pytest.mark.parametrize("heads,hidden", [(8, 1024), (8, 512)])
+def test_bf16_dropout_many_blocks_unsplit_kernels(heads, hidden):
+    # enough (sample, head, query block) units that the forward and dQ kernels run unsplit;
+    # several key blocks per workgroup of the dK/dV kernel; both head dimensions
+    shape = I.LayerShape(hidden, heads, 256, 1, 1, 0, 1100, 6, "bf16", drop_attn=64, drop_seed=77)
+    params, x, dy = _case(shape, 99)
+    gpu, ref, _ = run_both(shape, params, x, dy, "attn")
+    compare(gpu, ref, TOL["bf16"], "attn")
+
+
+def test_bf16_dropout_keeps_few():
+    # drop probability 200/256: the output is made of the few kept terms, so a misplaced mask
+    # bit anywhere (either bit layout) is a large error
+    shape = I.LayerShape(256, 2, 264, 1, 1, 0, 333, 2, "bf16", drop_attn=200, drop_hidden=200, drop_seed=3)
+    params, x, dy = _case(shape, 100)
+    gpu, ref, _ = run_both(shape, params, x, dy)
+    compare(gpu, ref, TOL["bf16"])
+
+
+def test_dropout_same_seed_same_result_other_seed_other_result():
+    shape = I.LayerShape(256, 2, 264, 1, 1, 0, 100, 2, "bf16", drop_attn=64, drop_hidden=64, drop_seed=11)
+    params, x, dy = _case(shape, 101)
+    xd = to_device(x, "bf16")
+    a = to_host(DeviceLayer(shape, params).forward(xd)["y"])
+    b = to_host(DeviceLayer(shape, params).forward(xd)["y"])
+    c = to_host(DeviceLayer(shape.with_(drop_seed=12), params).forward(xd)["y"])
+    assert np.array_equal(a, b) and not np.array_equal(a, c)
+
+
 def test_bf16_remainder_round_of_large_tiles():
     """Products a little over one or several rounds of 256 large tiles (here 17 x 17 = 289 for the
     FC1 / FC2 / out-proj outputs and weight gradients, 17 x 50 = 850 for the QKV weight gradient)
