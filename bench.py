@@ -60,7 +60,7 @@ def measured_traffic(workload, kernel):
     return m["bytes_per_launch"]
 
 
-CLASS_NAMES = {1: "ln_fwd", 2: "ln_bwd", 3: "attn_fwd", 4: "attn_bwd", 5: "colsum",
+CLASS_NAMES = {1: "ln_fwd", 2: "ln_bwd", 3: "attn_fwd", 4: "attn_bwd", 5: "colsum", 6: "dropout",
                101: "gemm_nn_bias", 102: "gemm_nn_resid", 103: "gemm_nn_gelu", 110: "gemm_nt_store",
                114: "gemm_nt_dgelu", 125: "gemm_tn_f32", 126: "gemm_tn_f32_acc",
                120: "gemm_tn_bf16", 122: "gemm_tn_bf16_acc"}
@@ -82,6 +82,9 @@ def main():
     ap.add_argument("--wgrad-bf16", action="store_true",
                     help="variant: weight-matrix gradients written as bf16 (GX_WGRAD_BF16) instead of fp32; "
                          "recorded in config.weight_grad")
+    ap.add_argument("--dropout", type=int, default=0, metavar="P256",
+                    help="variant: dropout of the attention probabilities and of each half's output with "
+                         "probability P256/256 (GX_DROPOUT); recorded in config.dropout_256ths")
     ap.add_argument("--neighbours", action="store_true",
                     help="also time the layer step's memory-bound neighbours at this workload's shapes (AdamW "
                          "update of the rank's parameters, slicing the rank's shard out of the whole block and "
@@ -101,6 +104,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs an MI355X: no GPU is visible")
     shape, blocks, mbs = I.WORKLOADS[args.workload]
+    if args.dropout:
+        shape = shape.with_(drop_attn=args.dropout, drop_hidden=args.dropout, drop_seed=20250403)
     case = {"C1": 1, "C2": 2, "C3": 3, "C4": 4, "C5": 5}[args.workload]
     plist = [I.rank_params(shape, case=case, block=k) for k in range(blocks)]
     stack = DeviceStack(shape, plist, wgrad_bf16=args.wgrad_bf16)
@@ -188,7 +193,8 @@ def main():
                       "tp_attn": shape.tp_attn, "tp_ffn": shape.tp_ffn, "tp_rank": shape.tp_rank, "seq": shape.seq,
                       "micro_batch": shape.micro_batch, "blocks": blocks, "micro_batches": mbs,
                       "schedule": "1F1B, full recompute" if pipelined else "fwd then bwd",
-                      "backward_overlap": not args.serial, "weight_grad": "bf16" if args.wgrad_bf16 else "f32"},
+                      "backward_overlap": not args.serial, "weight_grad": "bf16" if args.wgrad_bf16 else "f32",
+                      "dropout_256ths": args.dropout},
            "frac_of_mfma_peak": tflops / peak,
            "tokens_per_s_per_layer": shape.tokens * blocks * mbs / (ms * 1e-3),
            "model_tflop_per_step": flops / 1e12,

@@ -5,9 +5,9 @@
 // attention kernels hold the score tile in MFMA accumulator layouts (a lane of the forward and dQ
 // kernels owns 16 keys of one query, a lane of the dK/dV kernel 16 queries of one key) and
 // regenerating 16-byte counters in those layouts would cost several generator calls per element.
-// One wavefront covers 64 queries; per group of 16 keys every lane makes one generator call for
-// its query, keeps the 16 bits for the row-major array and contributes them to 16 wavefront
-// ballots, each of which is the column-major word pair "64 queries of one key".
+// One wavefront covers 64 queries and 128 keys; per group of 16 keys every lane makes one
+// generator call for its query, keeps the 16 bits for the row-major array and contributes them to
+// 16 wavefront ballots, each of which is the column-major word pair "64 queries of one key".
 //   rowbits[(bh * S + i) * wpr + j / 32]  bit j % 32  = keep(i, j)        (forward, dQ)
 //   colbits[(bh * S + j) * wpr + i / 32]  bit i % 32  = keep(i, j)        (dK / dV)
 // wpr = 2 * ceil(S / 64) words per row.  Only words that a causal kernel can touch are written:
@@ -50,17 +50,24 @@ GX_DEVINL unsigned keep_bits16(const Philox& r, unsigned t) {
   return bits;
 }
 
+// One wavefront: 64 queries x MASK_GROUPS groups of 16 keys.
+constexpr int MASK_GROUPS = 8;
+
 __global__ void __launch_bounds__(64) attn_mask_kernel(unsigned* __restrict__ rowbits, unsigned* __restrict__ colbits,
-                                                       int S, int wpr, int heads, int head0, unsigned k0,
+                                                       int S, int wpr, int nchunk, int heads, int head0, unsigned k0,
                                                        unsigned k1, unsigned t) {
-  const int lane = threadIdx.x, blk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int lane = threadIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int blk = blockIdx.x / nchunk, chunk = blockIdx.x % nchunk;
   const int nl = gridDim.y;
+  const int groups = min(4 * (blk + 1), 2 * wpr);      // 16-key groups up to the end of the diagonal tile
+  const int jg0 = chunk * MASK_GROUPS;
+  if (jg0 >= groups) return;                           // wavefront-uniform
+  const int jg1 = min(jg0 + MASK_GROUPS, groups);      // jg0, jg1 and groups are even
   const int i = 64 * blk + lane;
   const size_t bh = (size_t)b * nl + h;
   const unsigned c2 = (unsigned)(b * heads + head0 + h);
-  const int groups = min(4 * (blk + 1), 2 * wpr);      // 16-key groups up to the end of the diagonal tile
   unsigned word = 0;
-  for (int jg = 0; jg < groups; jg++) {
+  for (int jg = jg0; jg < jg1; jg++) {
     const unsigned kb = keep_bits16(philox4x32_10((unsigned)i, (unsigned)jg, c2, 1u, k0, k1), t);
     word |= kb << (16 * (jg & 1));
     if (jg & 1) {
@@ -82,37 +89,41 @@ __global__ void __launch_bounds__(64) attn_mask_kernel(unsigned* __restrict__ ro
 }
 
 template <typename T>
-struct Vec4;
+struct Vec16B;                       // 16 bytes of T
 template <>
-struct Vec4<float> {
+struct Vec16B<float> {
   using type = f32x4;
+  static constexpr int N = 4;
 };
 template <>
-struct Vec4<bf16> {
-  using type = bf16x4;
+struct Vec16B<bf16> {
+  using type = bf16x8;
+  static constexpr int N = 8;
 };
 
+// one lane: the 16 consecutive columns of one generator call, moved as 16-byte vectors
 template <typename T>
 __global__ void __launch_bounds__(256) dropout_rows_kernel(const T* __restrict__ in, const T* __restrict__ resid,
                                                            T* __restrict__ out, int rows, int cols, int groups,
                                                            unsigned stream, unsigned k0, unsigned k1, unsigned t,
                                                            float scale) {
-  using V = typename Vec4<T>::type;
+  using V = typename Vec16B<T>::type;
+  constexpr int N = Vec16B<T>::N;
   const long id = (long)blockIdx.x * 256 + threadIdx.x;
   if (id >= (long)rows * groups) return;
   const int r = (int)(id / groups), cg = (int)(id % groups);
   const unsigned kb = keep_bits16(philox4x32_10((unsigned)r, (unsigned)cg, 0u, stream, k0, k1), t);
 #pragma unroll
-  for (int q = 0; q < 4; q++) {
-    const int c = 16 * cg + 4 * q;
-    if (c >= cols) break;                                // cols is a multiple of 4
+  for (int q = 0; q < 16 / N; q++) {
+    const int c = 16 * cg + N * q;
+    if (c >= cols) break;                                // cols is a multiple of N
     const size_t idx = (size_t)r * cols + c;
     const V v = *reinterpret_cast<const V*>(in + idx);
     V o;
     if (resid) o = *reinterpret_cast<const V*>(resid + idx);
 #pragma unroll
-    for (int e = 0; e < 4; e++) {
-      const float x = ((kb >> (4 * q + e)) & 1u) ? (float)v[e] * scale : 0.f;
+    for (int e = 0; e < N; e++) {
+      const float x = ((kb >> (N * q + e)) & 1u) ? (float)v[e] * scale : 0.f;
       o[e] = (T)(resid ? (float)o[e] + x : x);
     }
     *reinterpret_cast<V*>(out + idx) = o;
@@ -126,14 +137,15 @@ int attn_mask_wpr(int S) { return 2 * cdiv(S, 64); }
 hipError_t attn_mask(unsigned* rowbits, unsigned* colbits, int B, int nl, int S, int heads, int head0, unsigned k0,
                      unsigned k1, int t, hipStream_t s) {
   if (!rowbits || S <= 0 || t < 0 || t > 255) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(attn_mask_kernel, dim3(cdiv(S, 64), nl, B), dim3(64), 0, s, rowbits, colbits, S,
-                     attn_mask_wpr(S), heads, head0, k0, k1, (unsigned)t);
+  const int wpr = attn_mask_wpr(S), nchunk = cdiv(2 * wpr, MASK_GROUPS);
+  hipLaunchKernelGGL(attn_mask_kernel, dim3(cdiv(S, 64) * nchunk, nl, B), dim3(64), 0, s, rowbits, colbits, S, wpr,
+                     nchunk, heads, head0, k0, k1, (unsigned)t);
   return hipGetLastError();
 }
 
 hipError_t dropout_rows(bool bf, const void* in, const void* resid, void* out, int rows, int cols, unsigned stream,
                         unsigned k0, unsigned k1, int t, hipStream_t s) {
-  if (t < 0 || t > 255 || (cols & 3)) return hipErrorInvalidValue;
+  if (t < 0 || t > 255 || (cols & (bf ? 7 : 3))) return hipErrorInvalidValue;
   const int groups = cdiv(cols, 16);
   const long n = (long)rows * groups;
   const float scale = 256.0f / (256.0f - (float)t);
