@@ -45,7 +45,7 @@ MEASURED_TRAFFIC = {
     # FETCH_SIZE x 1.9997 (copy calibration) + WRITE_SIZE x 1.0, averaged over the class's 4 launches per step:
     # dW2, dW1, dWqkv (256x256 tiles) 257.4 MB per launch on average, dWo (128x128 tiles) 117.5 MB
     ("C3", "gemm_tn_f32"): {"bytes_per_launch": 222.4e6, "algorithmic_bytes_per_launch": 109.1e6,
-                            "source_sha256": "0761d0f015268a95dddfb38de98d9482ef1f6eb4339cccc99e050c68f1a6fee8"},
+                            "source_sha256": "4694c533baa4d05f3e9a0c67d216c54974e43cfe14e72001be011b5255d7bb24"},
 }
 
 
