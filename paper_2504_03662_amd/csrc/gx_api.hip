@@ -384,7 +384,7 @@ gx_status run_fwd(const gx_layer_cfg& c, const gx_params& p, const void* x, void
       GemmArgs o = gargs(sv.ctx, p.w_o, pa, d.T, d.H, d.Hl, d.Hl, d.H, d.H);
       o.bias = (c.flags & GX_ROW_BIAS_ATTN) ? p.b_o : nullptr;
       GX_TRY(gemm(d, LAY_NN, EPI_BIAS, o, st));
-      GX_TRY(dropout_p(d, dr, pa, x, sv.h1, 2u, st));
+      GX_TRY(dropout_p(d, dr, pa, x, sv.h1, DROP_STREAM_ATTN_OUT, st));
       h1 = sv.h1;
     } else if (mlp) {
       GemmArgs o = gargs(sv.ctx, p.w_o, sv.h1, d.T, d.H, d.Hl, d.Hl, d.H, d.H);
@@ -413,7 +413,7 @@ gx_status run_fwd(const gx_layer_cfg& c, const gx_params& p, const void* x, void
       f2.bias = (c.flags & GX_ROW_BIAS_MLP) ? p.b_fc2 : nullptr;
       if (dr.hidden) {
         GX_TRY(gemm(d, LAY_NN, EPI_BIAS, f2, st));
-        GX_TRY(dropout_p(d, dr, pm, h1, y, 3u, st));
+        GX_TRY(dropout_p(d, dr, pm, h1, y, DROP_STREAM_MLP_OUT, st));
       } else if (attn) {
         f2.resid = h1;
         f2.aux = p_mlp;
@@ -461,7 +461,7 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     // gradient reaching the feed-forward half's output: dy itself, or dy through that output's mask
     const void* dp = dy;
     if (dr.hidden) {
-      GX_TRY(dropout_p(d, dr, dy, nullptr, db.dym, 3u, st));
+      GX_TRY(dropout_p(d, dr, dy, nullptr, db.dym, DROP_STREAM_MLP_OUT, st));
       dp = db.dym;
     }
     // row-parallel FC2: bias and weight gradients need only dp and saved activations: side
@@ -498,7 +498,7 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     // has few tiles and overlaps the attention kernels), input gradient on the caller's stream
     const void* dp = dcur;           // gradient reaching the attention half's output
     if (dr.hidden) {
-      GX_TRY(dropout_p(d, dr, dcur, nullptr, db.dh1m, 2u, st));
+      GX_TRY(dropout_p(d, dr, dcur, nullptr, db.dh1m, DROP_STREAM_ATTN_OUT, st));
       dp = db.dh1m;
     }
     hipStream_t sd = fk.branch();

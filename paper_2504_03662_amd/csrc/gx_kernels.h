@@ -75,7 +75,9 @@ int attn_mask_wpr(int S);
 hipError_t attn_mask(unsigned* rowbits, unsigned* colbits, int B, int nl, int S, int heads, int head0, unsigned k0,
                      unsigned k1, int t, hipStream_t s);
 // out = (resid ? resid : 0) + keep * 256 / (256 - t) * in over [rows, cols]; counter
-// (row, column / 16, 0, stream), byte column % 16.  out may alias in.
+// (row, column / 16, 0, stream), byte column % 16.  out may alias in.  The fourth counter word
+// separates the masks: 1 attention probabilities (attn_mask), 2 and 3 the two halves' outputs.
+constexpr unsigned DROP_STREAM_ATTN_OUT = 2, DROP_STREAM_MLP_OUT = 3;
 hipError_t dropout_rows(bool bf16, const void* in, const void* resid, void* out, int rows, int cols,
                         unsigned stream, unsigned k0, unsigned k1, int t, hipStream_t s);
 
