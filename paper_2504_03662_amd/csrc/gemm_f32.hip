@@ -1,13 +1,15 @@
-// fp32 GEMM for the full-precision configuration: a plain LDS-tiled kernel (64x64 tile, 4x4
-// outputs per thread, fp32 FMAs only) with the same layouts and epilogues as the bf16 family.
-// That configuration is a few GFLOP and launch-bound, so this kernel is written for exactness
-// (no reduced-precision shortcut anywhere), not for the matrix cores.
+// fp32 GEMM for the full-precision configuration: a plain LDS-tiled kernel (64x64x32 tile, 4x4
+// outputs per thread, fp32 FMAs only, next tile prefetched into registers) with the same layouts
+// and epilogues as the bf16 family.  That configuration is a few GFLOP with at most 64 tiles per
+// product, so this kernel is written for exactness (no reduced-precision shortcut anywhere), not
+// for the matrix cores.
 #include "gx_kernels.h"
 
 namespace gx {
 namespace {
 
-constexpr int TM = 64, TN = 64, TK = 16;
+constexpr int TM = 64, TN = 64, TK = 32;
+constexpr int PER = TM * TK / 256;       // elements of each operand tile per thread
 
 template <int LAY, int EPI>
 __global__ void __launch_bounds__(256) gemm_f32_kernel(GemmArgs g) {
@@ -24,25 +26,43 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(GemmArgs g) {
 #pragma unroll
     for (int j = 0; j < 4; j++) acc[i][j] = 0.f;
 
-  for (int k0 = 0; k0 < g.K; k0 += TK) {
-    // each thread brings 4 elements of each tile, walking the operand's contiguous index fastest
+  // each thread brings PER elements of each tile, walking the operand's contiguous index fastest;
+  // the next tile's elements are fetched into registers while the current tile is multiplied
+  auto a_pos = [&](int i, int& m, int& k) {
+    const int e = tid + 256 * i;
+    if (LAY == LAY_TN) { m = e & (TM - 1); k = e / TM; } else { k = e & (TK - 1); m = e / TK; }
+  };
+  auto b_pos = [&](int i, int& n, int& k) {
+    const int e = tid + 256 * i;
+    if (LAY == LAY_NT) { k = e & (TK - 1); n = e / TK; } else { n = e & (TN - 1); k = e / TN; }
+  };
+  float ra[PER], rb[PER];
+  auto fetch = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-      const int e = tid + 256 * i;
-      int m, k;
-      if (LAY == LAY_TN) { m = e & 63; k = e >> 6; } else { k = e & 15; m = e >> 4; }
-      float v = 0.f;
+    for (int i = 0; i < PER; i++) {
+      int m, k, n, kb;
+      a_pos(i, m, k);
+      b_pos(i, n, kb);
+      ra[i] = 0.f;
       if (m0 + m < g.M && k0 + k < g.K)
-        v = (LAY == LAY_TN) ? A[(size_t)(k0 + k) * g.lda + m0 + m] : A[(size_t)(m0 + m) * g.lda + k0 + k];
-      sa[k][m] = v;
-      int n, kb;
-      if (LAY == LAY_NT) { kb = e & 15; n = e >> 4; } else { n = e & 63; kb = e >> 6; }
-      float w = 0.f;
+        ra[i] = (LAY == LAY_TN) ? A[(size_t)(k0 + k) * g.lda + m0 + m] : A[(size_t)(m0 + m) * g.lda + k0 + k];
+      rb[i] = 0.f;
       if (n0 + n < g.N && k0 + kb < g.K)
-        w = (LAY == LAY_NT) ? B[(size_t)(n0 + n) * g.ldb + k0 + kb] : B[(size_t)(k0 + kb) * g.ldb + n0 + n];
-      sb[kb][n] = w;
+        rb[i] = (LAY == LAY_NT) ? B[(size_t)(n0 + n) * g.ldb + k0 + kb] : B[(size_t)(k0 + kb) * g.ldb + n0 + n];
+    }
+  };
+  fetch(0);
+  for (int k0 = 0; k0 < g.K; k0 += TK) {
+#pragma unroll
+    for (int i = 0; i < PER; i++) {
+      int m, k, n, kb;
+      a_pos(i, m, k);
+      b_pos(i, n, kb);
+      sa[k][m] = ra[i];
+      sb[kb][n] = rb[i];
     }
     __syncthreads();
+    if (k0 + TK < g.K) fetch(k0 + TK);
 #pragma unroll
     for (int k = 0; k < TK; k++) {
       float av[4], bv[4];
