@@ -321,6 +321,51 @@ def test_bitwise_reproducible():
         assert np.array_equal(a["grads"][n], c["grads"][n]), n
 
 
+@pytest.mark.parametrize("drop", [0, 48])
+def test_step_replays_from_a_captured_graph(drop):
+    """gx_layer_fwd / gx_layer_bwd only enqueue work (kernels, event records and waits on the
+    library's side streams), so a step can be captured into a HIP graph; every replay, with eager
+    work and synchronisations in between, must reproduce the eager result bit for bit."""
+    shape = I.LayerShape(512, 4, 1096, 1, 1, 0, 300, 2, "bf16", drop_attn=drop, drop_hidden=drop, drop_seed=9)
+    params, x, dy = _case(shape, 102)
+    layer = DeviceLayer(shape, params)
+    xd, dyd = to_device(x, "bf16"), to_device(dy, "bf16")
+    y, dx = layer.empty_act(), layer.empty_act()
+
+    def step():
+        layer.forward(xd, out=y)
+        layer.backward(xd, dyd, out=dx)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [to_host(y).copy(), to_host(dx).copy()] + [to_host(layer.grads[n]).copy() for n in I.PARAM_NAMES]
+
+    for _ in range(2):                       # first calls create streams, events and kernel attributes
+        step()
+    want = snapshot()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(3):
+        y.zero_()
+        dx.zero_()
+        for t in layer.grads.values():
+            t.fill_(3.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for a, b in zip(got, want):
+            assert np.array_equal(a, b)
+        step()                               # eager work between replays
+        torch.cuda.synchronize()
+
+
 def test_launch_timing_record():
     """gx_prof_*: every launch site of one forward + backward shows up once, in launch order, with a
     positive duration, and the record is cleared by the collect."""
