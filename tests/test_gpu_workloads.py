@@ -31,6 +31,17 @@ def test_c3_tp4_shard_full():
     print("C3 max-rel:", {k: f"{v[0]:.1e}" for k, v in report.items()})
 
 
+def test_c3_tp4_shard_full_with_dropout():
+    # the dropout variant at the benchmark's shape: 32 key tiles per row, split-key attention
+    # kernels, every keep-bit word of both layouts in use
+    shape, _, _ = I.WORKLOADS["C3"]
+    shape = shape.with_(drop_attn=26, drop_hidden=26, drop_seed=20250403)
+    params = I.rank_params(shape, case=3)
+    x, dy = I.activations(shape, case=3)
+    gpu, ref, _ = run_both(shape, params, x, dy)
+    compare(gpu, ref, TOLB)
+
+
 def test_c2_stack_of_four_blocks_full():
     shape, blocks, _ = I.WORKLOADS["C2"]
     plist = [I.rank_params(shape, case=2, block=k) for k in range(blocks)]
