@@ -337,13 +337,18 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
         } else if (EPI == EPI_GELU) {
           bf16x4 ga;
 #pragma unroll
-          for (int e = 0; e < 4; e++) ga[e] = (bf16)(g.gelu_tanh ? gelu_tanh_fast(x[e]) : gelu_fast(x[e]));
+          for (int e = 0; e < 4; e++) {
+            float y, dy;
+            if (g.gelu_tanh) gelu_tanh_both_fast(x[e], y, dy);
+            else gelu_both_fast(x[e], y, dy);
+            ga[e] = (bf16)y;
+            x[e] = dy;                                     // C receives gelu'(z)
+          }
           *reinterpret_cast<bf16x4*>(aux + idx) = ga;
         } else if (EPI == EPI_DGELU) {
           const bf16x4 zv = *reinterpret_cast<const bf16x4*>(zin + idx);
 #pragma unroll
-          for (int e = 0; e < 4; e++)
-            x[e] *= g.gelu_tanh ? gelu_tanh_grad_fast((float)zv[e]) : gelu_grad_fast((float)zv[e]);
+          for (int e = 0; e < 4; e++) x[e] *= (float)zv[e];
         }
 #pragma unroll
         for (int e = 0; e < 4; e++) o[e] = (bf16)x[e];

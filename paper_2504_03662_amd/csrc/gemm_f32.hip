@@ -104,10 +104,13 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(GemmArgs g) {
         C[idx] = x + resid[idx];
       } else if (EPI == EPI_GELU) {
         x += bv;
-        C[idx] = x;
-        aux[idx] = g.gelu_tanh ? gelu_tanh_f(x) : gelu_f(x);
+        float y, dy;
+        if (g.gelu_tanh) gelu_tanh_both_f(x, y, dy);
+        else gelu_both_f(x, y, dy);
+        C[idx] = dy;
+        aux[idx] = y;
       } else if (EPI == EPI_DGELU) {
-        C[idx] = x * (g.gelu_tanh ? gelu_tanh_grad_f(zin[idx]) : gelu_grad_f(zin[idx]));
+        C[idx] = x * zin[idx];
       } else {
         C[idx] += x;
       }

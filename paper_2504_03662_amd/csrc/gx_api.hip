@@ -66,7 +66,7 @@ struct Arena {
 // Activations the forward pass keeps for the backward pass.
 struct Saved {
   float *mean1, *rstd1, *lse, *mean2, *rstd2;
-  void *y1, *qkv, *ctx, *h1, *y2, *z, *act;
+  void *y1, *qkv, *ctx, *h1, *y2, *gelu_grad, *act;   // gelu_grad: gelu'(z) of the FC1 pre-activation z
 };
 
 Saved plan_saved(const gx_layer_cfg& c, Arena& a) {
@@ -86,7 +86,7 @@ Saved plan_saved(const gx_layer_cfg& c, Arena& a) {
     s.mean2 = static_cast<float*>(a.take(d.T * 4));
     s.rstd2 = static_cast<float*>(a.take(d.T * 4));
     s.y2 = a.take(d.T * d.H * d.e);
-    s.z = a.take(d.T * d.Fl * d.e);
+    s.gelu_grad = a.take(d.T * d.Fl * d.e);
     s.act = a.take(d.T * d.Fl * d.e);
   }
   return s;
@@ -402,7 +402,7 @@ gx_status run_fwd(const gx_layer_cfg& c, const gx_params& p, const void* x, void
   if (mlp) {
     { ProfScope ps(GX_KC_LN_FWD, st);
     GX_TRY(ln_fwd(d.bf, h1, p.ln2_g, p.ln2_b, sv.y2, sv.mean2, sv.rstd2, (int)d.T, (int)d.H, c.ln_eps, st)); }
-    GemmArgs f1 = gargs(sv.y2, p.w_fc1, sv.z, d.T, d.Fl, d.H, d.H, d.Fl, d.Fl);
+    GemmArgs f1 = gargs(sv.y2, p.w_fc1, sv.gelu_grad, d.T, d.Fl, d.H, d.H, d.Fl, d.Fl);
     f1.bias = p.b_fc1;
     f1.aux = sv.act;
     f1.gelu_tanh = (c.flags & GX_GELU_TANH) ? 1 : 0;
@@ -471,8 +471,7 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     GX_TRY(wgrad(w2, sd));
     // input gradient fused with GELU' on the caller's stream
     GemmArgs dz = gargs(dp, p.w_fc2, w.dz, d.T, d.Fl, d.H, d.H, d.H, d.Fl);
-    dz.z = sv.z;
-    dz.gelu_tanh = (c.flags & GX_GELU_TANH) ? 1 : 0;
+    dz.z = sv.gelu_grad;
     GX_TRY(gemm(d, LAY_NT, EPI_DGELU, dz, st));
     // column-parallel FC1: bias and weight gradients on the side once dz exists
     sd = fk.branch();

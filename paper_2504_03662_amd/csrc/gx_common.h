@@ -22,59 +22,45 @@ template <typename T> GX_DEVINL T from_f32(float v);
 template <> GX_DEVINL float from_f32<float>(float v) { return v; }
 template <> GX_DEVINL bf16 from_f32<bf16>(float v) { return (bf16)v; }   // round to nearest even
 
-// exact (erf) GELU and its derivative, fp32
-GX_DEVINL float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f)); }
-GX_DEVINL float gelu_grad_f(float z) {
-  float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752440f));
-  float pdf = 0.39894228040143267794f * __expf(-0.5f * z * z);
-  return cdf + z * pdf;
+// GELU and its derivative are evaluated together (they share the erf, or the sigmoid, and the
+// exponential): the FC1 epilogue stores gelu(z) for the next product and gelu'(z) for the backward
+// pass.  Exact (erf) form  gelu(z) = z Phi(z),  gelu'(z) = Phi(z) + z phi(z):
+// fp32 outputs use erff; bf16 outputs use erf by Abramowitz & Stegun 7.1.26 (|error| <= 1.5e-7:
+// one reciprocal, one exponential and a degree-5 polynomial).
+GX_DEVINL void gelu_both_f(float z, float& y, float& dy) {
+  const float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752440f));
+  y = z * cdf;
+  dy = fmaf(z * 0.39894228040143267794f, __expf(-0.5f * z * z), cdf);
 }
-
-// erf by Abramowitz & Stegun 7.1.26 (|error| <= 1.5e-7): one reciprocal, one exponential and a
-// degree-5 polynomial; returns erf(|x|) and exp(-x^2) so that the GELU derivative can share them.
-GX_DEVINL float erf_abs_as(float ax, float& e) {
+GX_DEVINL void gelu_both_fast(float z, float& y, float& dy) {
+  const float ax = fabsf(z) * 0.70710678118654752440f;
   const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
   float p = fmaf(1.061405429f, t, -1.453152027f);
   p = fmaf(p, t, 1.421413741f);
   p = fmaf(p, t, -0.284496736f);
   p = fmaf(p, t, 0.254829592f);
-  e = __expf(-ax * ax);
-  return fmaf(-p * t, e, 1.0f);
-}
-// GELU and its derivative on that erf; accurate to ~2e-7 absolute, for bf16 outputs
-GX_DEVINL float gelu_fast(float z) {
-  float e;
-  const float r = erf_abs_as(fabsf(z) * 0.70710678118654752440f, e);
-  return 0.5f * z * (1.0f + copysignf(r, z));
-}
-GX_DEVINL float gelu_grad_fast(float z) {
-  float e;
-  const float r = erf_abs_as(fabsf(z) * 0.70710678118654752440f, e);
-  return fmaf(z * 0.39894228040143267794f, e, 0.5f * (1.0f + copysignf(r, z)));
+  const float e = __expf(-ax * ax);                    // exp(-z^2 / 2)
+  const float cdf = 0.5f * (1.0f + copysignf(fmaf(-p * t, e, 1.0f), z));
+  y = z * cdf;
+  dy = fmaf(z * 0.39894228040143267794f, e, cdf);
 }
 
-// The tanh form of GELU, z * sigmoid(2u) with u = sqrt(2/pi) (z + 0.044715 z^3), and its derivative
-// s + 2 z s (1 - s) u'(z), s = sigmoid(2u); full-precision exponential and division for fp32
-// outputs, hardware exponential and reciprocal for bf16 outputs.
-GX_DEVINL float gelu_tanh_f(float z) {
-  const float u = 0.7978845608028654f * fmaf(0.044715f * z * z, z, z);
-  return z / (1.0f + expf(-2.0f * u));
-}
-GX_DEVINL float gelu_tanh_grad_f(float z) {
+// The tanh form, gelu(z) = z s with s = sigmoid(2u), u = sqrt(2/pi) (z + 0.044715 z^3), and
+// gelu'(z) = s + 2 z s (1 - s) u'(z): full-precision exponential and division for fp32 outputs,
+// hardware exponential and reciprocal for bf16 outputs.
+GX_DEVINL void gelu_tanh_both_f(float z, float& y, float& dy) {
   const float z2 = z * z;
   const float u = 0.7978845608028654f * fmaf(0.044715f * z2, z, z);
   const float s = 1.0f / (1.0f + expf(-2.0f * u));
-  return fmaf(2.0f * z * s * (1.0f - s), 0.7978845608028654f * fmaf(0.134145f, z2, 1.0f), s);
+  y = z * s;
+  dy = fmaf(2.0f * y * (1.0f - s), 0.7978845608028654f * fmaf(0.134145f, z2, 1.0f), s);
 }
-GX_DEVINL float gelu_tanh_fast(float z) {
-  const float u = 0.7978845608028654f * fmaf(0.044715f * z * z, z, z);
-  return z * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u));
-}
-GX_DEVINL float gelu_tanh_grad_fast(float z) {
+GX_DEVINL void gelu_tanh_both_fast(float z, float& y, float& dy) {
   const float z2 = z * z;
   const float u = 0.7978845608028654f * fmaf(0.044715f * z2, z, z);
   const float s = __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u));
-  return fmaf(2.0f * z * s * (1.0f - s), 0.7978845608028654f * fmaf(0.134145f, z2, 1.0f), s);
+  y = z * s;
+  dy = fmaf(2.0f * y * (1.0f - s), 0.7978845608028654f * fmaf(0.134145f, z2, 1.0f), s);
 }
 
 GX_DEVINL float wave_sum(float v) {

@@ -17,8 +17,8 @@ enum Epilogue {
   EPI_STORE = 0,   // C = acc                                   (storage type)
   EPI_BIAS,        // C = acc + bias[n]            (bias may be null)
   EPI_RESID,       // p = acc + bias[n]; aux = p if aux; C = resid + p
-  EPI_GELU,        // z = acc + bias[n]; C = z; aux = gelu(z)        (erf form, or tanh form if gelu_tanh)
-  EPI_DGELU,       // C = acc * gelu'(z[m,n])
+  EPI_GELU,        // z = acc + bias[n]; C = gelu'(z); aux = gelu(z)  (erf form, or tanh form if gelu_tanh)
+  EPI_DGELU,       // C = acc * z[m,n], z holding what EPI_GELU left in C
   EPI_F32,         // C (fp32) = acc
   EPI_F32_ACC      // C (fp32) += acc
 };
@@ -32,8 +32,8 @@ struct GemmArgs {
   const void* bias;    // [N], storage type
   const void* resid;   // [M, ldc], storage type
   void* aux;           // [M, ldc], storage type
-  const void* z;       // [M, ldc], storage type
-  int gelu_tanh;       // EPI_GELU / EPI_DGELU: tanh form of GELU instead of the erf form
+  const void* z;       // [M, ldc], storage type: EPI_DGELU's multiplier
+  int gelu_tanh;       // EPI_GELU: tanh form of GELU instead of the erf form
   // set by the bf16 launcher only (callers leave them 0): a launch that covers the super-tiles
   // (2 x 2 kernel tiles) numbered tile_first onwards in the tile walk, four workgroups each
   int tail, tile_first;
