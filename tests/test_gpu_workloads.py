@@ -87,8 +87,8 @@ def test_c4_mixed_degree_block_sampled_tokens():
         check("d" + n, to_host(layer.grads[n]), g, TOLB)
 
 
-def _run_stage(shape, plist, xs, dys):
-    stack = DeviceStack(shape, plist)
+def _run_stage(shape, plist, xs, dys, wgrad_bf16=False):
+    stack = DeviceStack(shape, plist, wgrad_bf16=wgrad_bf16)
     xd = [to_device(a, shape.dtype) for a in xs]
     dyd = [to_device(a, shape.dtype) for a in dys]
     ys, dxs, seen = {}, {}, False
@@ -135,3 +135,23 @@ def test_pipeline_stage_8_blocks_8_micro_batches_small_shape():
     for k in (0, blocks - 1):
         for n in I.PARAM_NAMES:
             check(f"block{k}.d{n}", to_host(stack.layers[k].grads[n]), tot[k][n], 2 * TOLB)
+
+
+def test_pipeline_stage_with_every_variant_at_once():
+    """Head dimension 64, tanh GELU, dropout, bf16 weight gradients, recomputation and gradient
+    accumulation together in the 1F1B schedule (2 blocks x 4 micro-batches, sharded shape)."""
+    shape = I.LayerShape(512, 8, 1024, 2, 2, 1, 200, 2, "bf16", gelu_tanh=True, drop_attn=32, drop_hidden=20,
+                         drop_seed=4242)
+    blocks, mbs = 2, 4
+    full = [I.full_params(shape.with_(tp_attn=1, tp_ffn=1), case=56, block=k, random_affine=True) for k in range(blocks)]
+    plist = [I.shard_params(shape, f) for f in full]
+    acts = [I.activations(shape, case=56, micro_batch_index=m) for m in range(mbs)]
+    xs, dys = [a[0] for a in acts], [a[1] for a in acts]
+    stack, ys, dxs = _run_stage(shape, plist, xs, dys, wgrad_bf16=True)
+    ys_ref, dxs_ref, tot = O.pipeline_stage(shape, plist, xs, dys)
+    for m in range(mbs):
+        check(f"y[{m}]", ys[m], ys_ref[m], TOLB)
+        check(f"dx[{m}]", dxs[m], dxs_ref[m], TOLB)
+    for k in range(blocks):
+        for n in I.PARAM_NAMES:
+            check(f"block{k}.d{n}", to_host(stack.layers[k].grads[n]), tot[k][n], TOLB)
