@@ -36,7 +36,12 @@
  *     columns [r*Hl, (r+1)*Hl) of each of Wq, Wk, Wv (resp. [r*Fl, (r+1)*Fl) of W1); its row shard
  *     is the same index range of the rows of Wo / W2.
  *   - Activations and parameters have the element type cfg->dtype (fp32, or bf16 with fp32
- *     accumulation); parameter gradients are always fp32.
+ *     accumulation); parameter gradients are fp32 (GX_WGRAD_BF16: the weight matrices' in bf16).
+ *   - Variants selected by flags: tanh-form GELU (GX_GELU_TANH), dropout of the attention
+ *     probabilities and of each half's output (GX_DROPOUT), recomputation of the activations in
+ *     the backward call (GX_RECOMPUTE), gradient accumulation (GX_ACCUM_WGRAD).  Since the calls
+ *     only enqueue kernels and event operations, a caller may capture them into a HIP graph after
+ *     one ordinary call has created the library's streams and events.
  *   - Calls only enqueue work (a hipStream_t, or NULL for the default stream); they never allocate
  *     device memory, free or synchronise the host, and results are bitwise reproducible run to
  *     run.  gx_layer_bwd forks part of its work (the weight gradients, the bias / LayerNorm
