@@ -85,6 +85,11 @@ def main():
     ap.add_argument("--dropout", type=int, default=0, metavar="P256",
                     help="variant: dropout of the attention probabilities and of each half's output with "
                          "probability P256/256 (GX_DROPOUT); recorded in config.dropout_256ths")
+    ap.add_argument("--zero-operands", action="store_true",
+                    help="diagnostic, not a benchmark: run the same step on all-zero activations, upstream "
+                         "gradients and parameters (every product multiplies zeros), which shows how fast the same kernels "
+                         "and launch sequence run when operand switching activity does not hold the clock down; "
+                         "recorded in \"data\"")
     ap.add_argument("--neighbours", action="store_true",
                     help="also time the layer step's memory-bound neighbours at this workload's shapes (AdamW "
                          "update of the rank's parameters, slicing the rank's shard out of the whole block and "
@@ -113,6 +118,9 @@ def main():
     acts = [I.activations(shape, case=case, micro_batch_index=m) for m in range(mbs)]
     xs = [to_device(a[0], shape.dtype) for a in acts]
     dys = [to_device(a[1], shape.dtype) for a in acts]
+    if args.zero_operands:
+        for t in xs + dys + [w for layer in stack.layers for w in layer.params.values()]:
+            t.zero_()
     pipelined = mbs > 1
     schedule = one_f_one_b(mbs, 3) if pipelined else [("F", 0), ("B", 0)]
 
@@ -188,7 +196,8 @@ def main():
 
     out = {"metric": "layer fwd+bwd TFLOP/s per GPU", "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
-           "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
+           "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype,
+           "data": "zeros (clock diagnostic, not a benchmark)" if args.zero_operands else "synthetic",
            "config": {"workload": args.workload, "hidden": shape.hidden, "heads": shape.heads, "ffn": shape.ffn,
                       "tp_attn": shape.tp_attn, "tp_ffn": shape.tp_ffn, "tp_rank": shape.tp_rank, "seq": shape.seq,
                       "micro_batch": shape.micro_batch, "blocks": blocks, "micro_batches": mbs,
