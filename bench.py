@@ -102,7 +102,7 @@ def main():
     import torch
     from paper_2504_03662_amd import binding as gx
     from paper_2504_03662_amd import inputs as I
-    from paper_2504_03662_amd.runtime import DeviceStack, one_f_one_b, to_device
+    from paper_2504_03662_amd.runtime import DeviceStack, StageSchedule, one_f_one_b, to_device
 
     gx.lib()                                         # fails loudly when the HIP library is missing
     gx.set_overlap(not args.serial)
@@ -124,15 +124,12 @@ def main():
     pipelined = mbs > 1
     schedule = one_f_one_b(mbs, 3) if pipelined else [("F", 0), ("B", 0)]
 
+    # pipelined stage: full activation recomputation, gradients summed over micro-batches; forward
+    # and backward passes of different micro-batches are issued on two streams (unless --serial)
+    runner = StageSchedule(stack, mbs, overlap=pipelined and not args.serial)
+
     def step():
-        seen = False
-        for kind, m in schedule:
-            if kind == "F":
-                stack.forward(xs[m], mb=m, keep_saved=not pipelined)
-            else:
-                # pipelined stage: full activation recomputation, gradients summed over micro-batches
-                stack.backward(dys[m], mb=m, recompute=pipelined, accumulate=pipelined and seen)
-                seen = True
+        runner.run(schedule, xs, dys, recompute=pipelined)
 
     if args.calibrate_copy:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0")
@@ -158,12 +155,17 @@ def main():
     # it alone can be held against the roofline
     torch.cuda.synchronize()
     gx.set_overlap(False)
-    step()
+    serial = StageSchedule(stack, mbs, overlap=False)
+
+    def step_serial():
+        serial.run(schedule, xs, dys, recompute=pipelined)
+
+    step_serial()
     gx.prof_enable(True)
     launches_per_step = None
     rec = []
     for _ in range(max(1, min(args.steps, 8))):
-        step()
+        step_serial()
         got = gx.prof_collect()
         launches_per_step = len(got)
         rec += got
@@ -201,7 +203,8 @@ def main():
            "config": {"workload": args.workload, "hidden": shape.hidden, "heads": shape.heads, "ffn": shape.ffn,
                       "tp_attn": shape.tp_attn, "tp_ffn": shape.tp_ffn, "tp_rank": shape.tp_rank, "seq": shape.seq,
                       "micro_batch": shape.micro_batch, "blocks": blocks, "micro_batches": mbs,
-                      "schedule": "1F1B, full recompute" if pipelined else "fwd then bwd",
+                      "schedule": ("1F1B, full recompute, forward and backward passes on two streams"
+                                   if runner.overlap else "1F1B, full recompute") if pipelined else "fwd then bwd",
                       "backward_overlap": not args.serial, "weight_grad": "bf16" if args.wgrad_bf16 else "f32",
                       "dropout_256ths": args.dropout},
            "frac_of_mfma_peak": tflops / peak,

@@ -145,3 +145,47 @@ def one_f_one_b(n_micro, depth_ahead):
         order.append(("B", b))
         b += 1
     return order
+
+
+class StageSchedule:
+    """Issues one pipeline stage's passes in a given order (e.g. one_f_one_b) on two streams:
+    forward passes on one, backward passes on the other, each backward pass ordered after the
+    forward pass of its own micro-batch.  A forward pass of a later micro-batch is independent of
+    the backward pass issued next to it (different activations, read-only weights), so the two
+    fill each other's idle compute units; weight gradients are still accumulated in the order of
+    the backward passes.  With `overlap=False` everything is issued on the current stream."""
+
+    def __init__(self, stack: DeviceStack, n_micro, overlap=True):
+        self.stack = stack
+        self.overlap = overlap
+        if overlap:
+            self.fwd_stream, self.bwd_stream = torch.cuda.Stream(), torch.cuda.Stream()
+            self.done = [torch.cuda.Event() for _ in range(n_micro)]
+
+    def run(self, order, xs, dys, recompute, after_forward=None, after_backward=None):
+        """xs / dys: device tensors per micro-batch.  The optional hooks run right after a pass
+        has been issued, with that pass's stream current (so a host copy made there waits for it)."""
+        cur = torch.cuda.current_stream()
+        if self.overlap:
+            self.fwd_stream.wait_stream(cur)
+            self.bwd_stream.wait_stream(cur)
+        seen = False
+        for kind, m in order:
+            if kind == "F":
+                with torch.cuda.stream(self.fwd_stream if self.overlap else cur):
+                    y = self.stack.forward(xs[m], mb=m, keep_saved=not recompute)
+                    if self.overlap:
+                        self.done[m].record()
+                    if after_forward:
+                        after_forward(m, y)
+            else:
+                with torch.cuda.stream(self.bwd_stream if self.overlap else cur):
+                    if self.overlap:
+                        torch.cuda.current_stream().wait_event(self.done[m])
+                    dx = self.stack.backward(dys[m], mb=m, recompute=recompute, accumulate=seen)
+                    seen = True
+                    if after_backward:
+                        after_backward(m, dx)
+        if self.overlap:
+            cur.wait_stream(self.fwd_stream)
+            cur.wait_stream(self.bwd_stream)

@@ -14,7 +14,7 @@ import torch
 
 from oracle import layer as O
 from paper_2504_03662_amd import inputs as I
-from paper_2504_03662_amd.runtime import DeviceLayer, DeviceStack, one_f_one_b, to_device, to_host
+from paper_2504_03662_amd.runtime import DeviceLayer, DeviceStack, StageSchedule, one_f_one_b, to_device, to_host
 from parity import TOL, check, compare, run_both
 
 pytestmark = pytest.mark.gpu
@@ -87,19 +87,20 @@ def test_c4_mixed_degree_block_sampled_tokens():
         check("d" + n, to_host(layer.grads[n]), g, TOLB)
 
 
-def _run_stage(shape, plist, xs, dys, wgrad_bf16=False):
+def _run_stage(shape, plist, xs, dys, wgrad_bf16=False, overlap=True):
+    """The stage as the benchmark runs it: 1F1B order, recomputation, accumulation, forward and
+    backward passes on two streams.  Results are cloned on the device in stream order and brought
+    to the host at the end, so that the passes really overlap."""
     stack = DeviceStack(shape, plist, wgrad_bf16=wgrad_bf16)
     xd = [to_device(a, shape.dtype) for a in xs]
     dyd = [to_device(a, shape.dtype) for a in dys]
-    ys, dxs, seen = {}, {}, False
-    for kind, m in one_f_one_b(len(xs), 3):
-        if kind == "F":
-            ys[m] = to_host(stack.forward(xd[m], mb=m, keep_saved=False))
-        else:
-            dxs[m] = to_host(stack.backward(dyd[m], mb=m, recompute=True, accumulate=seen))
-            seen = True
+    ys, dxs = {}, {}
+    runner = StageSchedule(stack, len(xs), overlap=overlap)
+    runner.run(one_f_one_b(len(xs), 3), xd, dyd, recompute=True,
+               after_forward=lambda m, y: ys.__setitem__(m, y.clone()),
+               after_backward=lambda m, dx: dxs.__setitem__(m, dx.clone()))
     torch.cuda.synchronize()
-    return stack, ys, dxs
+    return stack, {m: to_host(t) for m, t in ys.items()}, {m: to_host(t) for m, t in dxs.items()}
 
 
 def test_c5_pipeline_stage_full_shape_reduced_depth():
@@ -155,3 +156,18 @@ def test_pipeline_stage_with_every_variant_at_once():
     for k in range(blocks):
         for n in I.PARAM_NAMES:
             check(f"block{k}.d{n}", to_host(stack.layers[k].grads[n]), tot[k][n], TOLB)
+
+
+def test_two_stream_stage_schedule_equals_the_serial_one_bitwise():
+    shape = I.LayerShape(512, 4, 1096, 2, 1, 0, 300, 1, "bf16")
+    blocks, mbs = 3, 5
+    plist = [I.rank_params(shape, case=57, block=k) for k in range(blocks)]
+    acts = [I.activations(shape, case=57, micro_batch_index=m) for m in range(mbs)]
+    xs, dys = [a[0] for a in acts], [a[1] for a in acts]
+    a_stack, a_ys, a_dxs = _run_stage(shape, plist, xs, dys, overlap=True)
+    b_stack, b_ys, b_dxs = _run_stage(shape, plist, xs, dys, overlap=False)
+    for m in range(mbs):
+        assert np.array_equal(a_ys[m], b_ys[m]) and np.array_equal(a_dxs[m], b_dxs[m])
+    for k in range(blocks):
+        for n in I.PARAM_NAMES:
+            assert np.array_equal(to_host(a_stack.layers[k].grads[n]), to_host(b_stack.layers[k].grads[n])), (k, n)
