@@ -92,6 +92,10 @@ enum {
                              w_fc1, w_fc2 of gx_grads) point to bf16 buffers; each element is the fp32
                              accumulator rounded once (with GX_ACCUM_WGRAD: old bf16 value + accumulator, added
                              in fp32 and rounded once).  Bias and LayerNorm gradients stay fp32. */
+  GX_FWD_SAVED_ONLY = 512,/* forward: compute only what gx_layer_bwd needs, into `saved` (no FC2 product, no output
+                             projection of a lone attention phase); y, p_attn and p_mlp are not written and may
+                             be NULL.  For callers that recompute activations themselves, e.g. on another
+                             stream ahead of the backward pass; gx_layer_bwd ignores the flag. */
   GX_DROPOUT = 256        /* dropout variant: cfg->drop_attn, drop_hidden and drop_seed_* are read (without
                              the flag they are ignored).  Pass the same values to the forward and the backward
                              call.  Both passes then need a workspace (gx_layer_workspace_bytes). */

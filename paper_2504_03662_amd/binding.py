@@ -16,7 +16,7 @@ GX_OK = 0
 GX_F32, GX_BF16 = 0, 1
 GX_PHASE_ATTN, GX_PHASE_MLP = 1, 2
 GX_ROW_BIAS_ATTN, GX_ROW_BIAS_MLP = 4, 8
-GX_ACCUM_WGRAD, GX_RECOMPUTE, GX_GELU_TANH, GX_WGRAD_BF16, GX_DROPOUT = 16, 32, 64, 128, 256
+GX_ACCUM_WGRAD, GX_RECOMPUTE, GX_GELU_TANH, GX_WGRAD_BF16, GX_DROPOUT, GX_FWD_SAVED_ONLY = 16, 32, 64, 128, 256, 512
 
 PARAM_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")

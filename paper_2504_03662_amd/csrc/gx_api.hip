@@ -26,7 +26,7 @@ using namespace gx;
 static_assert(sizeof(gx_layer_cfg) == 15 * 4, "gx_layer_cfg is 15 packed 32-bit fields");
 
 constexpr int ALL_FLAGS = GX_PHASE_ATTN | GX_PHASE_MLP | GX_ROW_BIAS_ATTN | GX_ROW_BIAS_MLP | GX_ACCUM_WGRAD |
-                          GX_RECOMPUTE | GX_GELU_TANH | GX_WGRAD_BF16 | GX_DROPOUT;
+                          GX_RECOMPUTE | GX_GELU_TANH | GX_WGRAD_BF16 | GX_DROPOUT | GX_FWD_SAVED_ONLY;
 
 struct Dims {
   long T, H, Hl, Fl, S, B, nl, dh;
@@ -594,9 +594,12 @@ gx_status gx_layer_fwd(const gx_layer_cfg* cfg, const gx_params* params, const v
   if (!workspace && gx_layer_workspace_bytes(cfg, 0) != 0) return GX_ERR_NULL;
   if (misaligned(workspace)) return GX_ERR_ALIGN;
   const bool attn = cfg->flags & GX_PHASE_ATTN, mlp = cfg->flags & GX_PHASE_MLP;
-  if (attn && mlp && !y) return GX_ERR_NULL;
-  if (attn && !mlp && !p_attn) return GX_ERR_NULL;
-  if (!attn && mlp && !p_mlp) return GX_ERR_NULL;
+  const bool saved_only = cfg->flags & GX_FWD_SAVED_ONLY;
+  if (!saved_only) {
+    if (attn && mlp && !y) return GX_ERR_NULL;
+    if (attn && !mlp && !p_attn) return GX_ERR_NULL;
+    if (!attn && mlp && !p_mlp) return GX_ERR_NULL;
+  }
   if (misaligned(x) || misaligned(y) || misaligned(p_attn) || misaligned(p_mlp) || misaligned(saved))
     return GX_ERR_ALIGN;
   if ((s = check_params(*cfg, *params)) != GX_OK) return s;
@@ -607,6 +610,7 @@ gx_status gx_layer_fwd(const gx_layer_cfg* cfg, const gx_params* params, const v
   const DropBufs db = plan_drop(*cfg, wa, false);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if ((s = make_attn_mask(*cfg, db, st)) != GX_OK) return s;
+  if (saved_only) return run_fwd(*cfg, *params, x, nullptr, nullptr, nullptr, sv, db, true, st);
   return run_fwd(*cfg, *params, x, y, p_attn, p_mlp, sv, db, false, st);
 }
 

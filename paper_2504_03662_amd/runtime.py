@@ -15,7 +15,7 @@ WEIGHT_NAMES = ("w_qkv", "w_o", "w_fc1", "w_fc2")
 
 
 def cfg_of(shape: LayerShape, phase="both", row_bias_attn=True, row_bias_mlp=True, accumulate=False,
-           recompute=False, wgrad_bf16=False):
+           recompute=False, wgrad_bf16=False, saved_only=False):
     flags = _FLAG_OF_PHASE[phase]
     flags |= gx.GX_ROW_BIAS_ATTN if row_bias_attn else 0
     flags |= gx.GX_ROW_BIAS_MLP if row_bias_mlp else 0
@@ -24,6 +24,7 @@ def cfg_of(shape: LayerShape, phase="both", row_bias_attn=True, row_bias_mlp=Tru
     flags |= gx.GX_GELU_TANH if shape.gelu_tanh else 0
     flags |= gx.GX_WGRAD_BF16 if wgrad_bf16 else 0
     flags |= gx.GX_DROPOUT if (shape.drop_attn or shape.drop_hidden) else 0
+    flags |= gx.GX_FWD_SAVED_ONLY if saved_only else 0
     return gx.make_cfg(shape.hidden, shape.heads, shape.ffn, shape.tp_attn, shape.tp_ffn, shape.tp_rank, shape.seq,
                        shape.micro_batch, gx.GX_BF16 if shape.dtype == "bf16" else gx.GX_F32, flags, shape.ln_eps,
                        shape.drop_attn, shape.drop_hidden, shape.drop_seed)
@@ -72,11 +73,14 @@ class DeviceLayer:
         return torch.empty((self.shape.tokens, self.shape.hidden), dtype=self.tdtype, device=self.device)
 
     def forward(self, x, phase="both", row_bias_attn=True, row_bias_mlp=True, want_partials=False, saved_key="saved",
-                out=None):
-        cfg = cfg_of(self.shape, phase, row_bias_attn, row_bias_mlp)
+                out=None, saved_only=False, workspace_key="work_fwd"):
+        """saved_only: fill only the saved activations the backward pass needs (GX_FWD_SAVED_ONLY)."""
+        cfg = cfg_of(self.shape, phase, row_bias_attn, row_bias_mlp, saved_only=saved_only)
         saved = self._buf(saved_key, gx.layer_saved_bytes(cfg))
         y = p_attn = p_mlp = None
-        if phase == "both":
+        if saved_only:
+            pass
+        elif phase == "both":
             y = out if out is not None else self.empty_act()
             if want_partials:
                 p_attn, p_mlp = self.empty_act(), self.empty_act()
@@ -85,7 +89,7 @@ class DeviceLayer:
         else:
             p_mlp = out if out is not None else self.empty_act()
         nws = gx.layer_workspace_bytes(cfg, False)
-        ws = self._buf("work_fwd", nws) if nws else None
+        ws = self._buf(workspace_key, nws) if nws else None
         gx.layer_fwd(cfg, self.params, x, y, p_attn, p_mlp, saved, ws, torch.cuda.current_stream().cuda_stream)
         return dict(y=y, p_attn=p_attn, p_mlp=p_mlp)
 
@@ -118,9 +122,14 @@ class DeviceStack:
             layer.forward(ins[k], saved_key=("saved", mb) if keep_saved else "saved_scratch", out=ins[k + 1])
         return ins[-1]
 
-    def backward(self, dy, mb=0, recompute=False, accumulate=False):
+    def backward(self, dy, mb=0, recompute=False, accumulate=False, ahead=None):
+        """ahead: a stream on which the recomputation of block k-1 runs while block k's backward
+        pass runs on the current stream (two scratch blocks of saved activations per stack, shared
+        by all layers).  Without it, recomputation happens inside gx_layer_bwd (GX_RECOMPUTE)."""
         ins = self.inputs[mb]
         cur = dy
+        if recompute and ahead is not None:
+            return self._backward_recompute_ahead(ins, dy, accumulate, ahead)
         for k in reversed(range(len(self.layers))):
             layer = self.layers[k]
             dx = layer._bufs.get(("dx", k % 2))
@@ -128,6 +137,39 @@ class DeviceStack:
                 dx = layer._bufs[("dx", k % 2)] = layer.empty_act()
             cur = layer.backward(ins[k], cur, recompute=recompute, accumulate=accumulate, saved_key=("saved", mb),
                                  out=dx)
+        return cur
+
+    def _backward_recompute_ahead(self, ins, dy, accumulate, ahead):
+        main = torch.cuda.current_stream()
+        if not hasattr(self, "_rc"):
+            # scratch saved-activation blocks and forward workspaces are shared by all layers of the
+            # stack (same shape): slot k % 2, recycled when block k's backward pass has finished
+            self._rc = dict(filled=[torch.cuda.Event() for _ in self.layers],
+                            freed=[torch.cuda.Event() for _ in range(2)], bufs={})
+        rc = self._rc
+        ahead.wait_stream(main)                      # inputs of this micro-batch and earlier uses of the slots
+        n = len(self.layers)
+        cur = dy
+        for k in reversed(range(n)):
+            layer, slot = self.layers[k], k % 2
+            keys = (("rc", slot), ("rcw", slot))
+            with torch.cuda.stream(ahead):
+                if k + 2 < n:
+                    ahead.wait_event(rc["freed"][slot])
+                for key in keys:
+                    if key in rc["bufs"]:
+                        layer._bufs[key] = rc["bufs"][key]
+                layer.forward(ins[k], saved_key=keys[0], saved_only=True, workspace_key=keys[1])
+                for key in keys:
+                    if key in layer._bufs:
+                        rc["bufs"][key] = layer._bufs[key]
+                rc["filled"][k].record()
+            main.wait_event(rc["filled"][k])
+            dx = layer._bufs.get(("dx", k % 2))
+            if dx is None:
+                dx = layer._bufs[("dx", k % 2)] = layer.empty_act()
+            cur = layer.backward(ins[k], cur, recompute=False, accumulate=accumulate, saved_key=("rc", slot), out=dx)
+            rc["freed"][slot].record()
         return cur
 
 
@@ -153,13 +195,15 @@ class StageSchedule:
     forward pass of its own micro-batch.  A forward pass of a later micro-batch is independent of
     the backward pass issued next to it (different activations, read-only weights), so the two
     fill each other's idle compute units; weight gradients are still accumulated in the order of
-    the backward passes.  With `overlap=False` everything is issued on the current stream."""
+    the backward passes.  With recomputation, a third stream recomputes block k-1's activations
+    while block k's backward pass runs.  With `overlap=False` everything is issued on the current
+    stream and recomputation happens inside gx_layer_bwd."""
 
     def __init__(self, stack: DeviceStack, n_micro, overlap=True):
         self.stack = stack
         self.overlap = overlap
         if overlap:
-            self.fwd_stream, self.bwd_stream = torch.cuda.Stream(), torch.cuda.Stream()
+            self.fwd_stream, self.bwd_stream, self.ahead_stream = (torch.cuda.Stream() for _ in range(3))
             self.done = [torch.cuda.Event() for _ in range(n_micro)]
 
     def run(self, order, xs, dys, recompute, after_forward=None, after_backward=None):
@@ -182,7 +226,8 @@ class StageSchedule:
                 with torch.cuda.stream(self.bwd_stream if self.overlap else cur):
                     if self.overlap:
                         torch.cuda.current_stream().wait_event(self.done[m])
-                    dx = self.stack.backward(dys[m], mb=m, recompute=recompute, accumulate=seen)
+                    dx = self.stack.backward(dys[m], mb=m, recompute=recompute, accumulate=seen,
+                                             ahead=self.ahead_stream if self.overlap else None)
                     seen = True
                     if after_backward:
                         after_backward(m, dx)

@@ -43,7 +43,7 @@ def test_validate_accepts_the_graded_workloads(lib):
 
 
 @pytest.mark.parametrize("kw,status", [
-    (dict(hidden=0), 2), (dict(seq=-1), 2), (dict(dtype=7), 4), (dict(flags=0), 6), (dict(flags=3 | 1024), 6), (dict(flags=3 | 512), 6),
+    (dict(hidden=0), 2), (dict(seq=-1), 2), (dict(dtype=7), 4), (dict(flags=0), 6), (dict(flags=3 | 1024), 6), (dict(flags=3 | 2048), 6),
     (dict(flags=3 | gx.GX_DROPOUT, drop_attn=256), 2), (dict(flags=3 | gx.GX_DROPOUT, drop_hidden=-1), 2),
     (dict(dtype=gx.GX_F32, hidden=256, heads=4, ffn=1024, tp_attn=1, tp_ffn=1, flags=3 | gx.GX_WGRAD_BF16), 4),
     (dict(heads=33), 3), (dict(tp_attn=3), 3), (dict(ffn=16385), 3), (dict(tp_rank=4), 2),
@@ -58,6 +58,13 @@ def test_validate_rejects(lib, kw, status):
 
 def test_bf16_weight_gradient_flag_is_accepted_for_bf16(lib):
     assert gx.layer_validate(_cfg(flags=3 | gx.GX_WGRAD_BF16 | gx.GX_ACCUM_WGRAD)) == gx.GX_OK
+
+
+def test_saved_only_forward_flag(lib):
+    # same saved block with and without the flag; it asks for no workspace of its own
+    assert gx.layer_validate(_cfg(flags=3 | gx.GX_FWD_SAVED_ONLY)) == gx.GX_OK
+    assert gx.layer_saved_bytes(_cfg(flags=3 | gx.GX_FWD_SAVED_ONLY)) == gx.layer_saved_bytes(_cfg())
+    assert gx.layer_workspace_bytes(_cfg(flags=3 | gx.GX_FWD_SAVED_ONLY), False) == 0
 
 
 def test_dropout_fields_and_workspace(lib):
