@@ -9,18 +9,24 @@ from oracle import layer as O
 from paper_2504_03662_amd import inputs as I
 
 
-# known-answer vectors of Philox4x32-10 from the generator's reference distribution (Random123,
-# kat_vectors): counter words, key words -> output words
-KAT = [
-    ((0, 0, 0, 0), (0, 0), (0x6627e8d5, 0xe169c58d, 0xbc57ac4c, 0x9b00dbd8)),
-    ((0xffffffff,) * 4, (0xffffffff,) * 2, (0x408f276d, 0x41c83b0e, 0xa20bc7c6, 0x6d5451fd)),
-    ((0x243f6a88, 0x85a308d3, 0x13198a2e, 0x03707344), (0xa4093822, 0x299f31d0),
-     (0xd16cfe09, 0x94fdcceb, 0x5001e420, 0x24126ea1)),
-]
+def _kat():
+    """(counter, key, output) triples from tests/golden/philox4x32_10_kat.txt."""
+    import os
+    rows = []
+    with open(os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_kat.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                w = [int(t, 16) for t in line.split()]
+                rows.append((tuple(w[:4]), tuple(w[4:6]), tuple(w[6:])))
+    return rows
+
+
+KAT = _kat()
 
 
 @pytest.mark.parametrize("ctr,key,out", KAT)
 def test_philox_known_answers(ctr, key, out):
+    assert len(KAT) == 3
     got = D.philox4x32_10(*ctr, *key)
     assert tuple(int(w) for w in got) == out
 
