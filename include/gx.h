@@ -108,7 +108,7 @@ typedef struct {
   int32_t seq, micro_batch;
   int32_t dtype;            /* gx_dtype */
   int32_t flags;            /* GX_PHASE_* | GX_ROW_BIAS_* | GX_ACCUM_WGRAD | GX_RECOMPUTE | GX_GELU_TANH | GX_WGRAD_BF16 |
-                               GX_DROPOUT */
+                               GX_DROPOUT | GX_FWD_SAVED_ONLY */
   float ln_eps;             /* LayerNorm epsilon (inside the square root; biased variance) */
   /* Dropout (only with GX_DROPOUT).  Probabilities are given in 1/256ths, 0..255.  Random bytes come
    * from Philox4x32-10 keyed by the 64-bit seed (drop_seed_lo, drop_seed_hi); the 16 bytes of one
@@ -255,11 +255,15 @@ gx_status gx_params_merge(const gx_layer_cfg* cfg, const gx_params* shard, const
  * Layer-wise strategy plan (host only, no GPU involved).  The paper's strategy selector, in its
  * discovery phase (section 3, "Dynamic Strategy Selector"; section 2, "Layer-Specific Parallelism
  * Optimization"), prunes the candidate strategies with a decision tree and then runs a dynamic
- * program over the layers "given a performance model"; neither the model nor the recurrence is
+ * program over the layers, driven by a cost model; neither the model nor the recurrence is
  * printed, so the problem solved here is the plainest one of that shape:
  *     choose one of `strategies` per layer so that the layers' memories (each first rounded up
  *     to a multiple of mem_quantum_bytes when that is > 0) sum to at most mem_budget_bytes,
  *     minimising  sum_l time_ms[l][c_l] + sum_{l>0} switch_ms[c_{l-1}][c_l].
+ * Rounding rule: with q = mem_quantum_bytes > 0 a memory x becomes k * q for the least whole
+ * number k whose product k * q, formed in double precision, is not below x.  A memory that is
+ * such a product already stays as it is; one that exceeds it by a single unit in the last place
+ * moves up to (k + 1) * q; no tolerance is applied.
  * The cost table is what a sweep of gx_layer_fwd / gx_layer_bwd over shard shapes measures.
  * Pruning: strategies that cannot fit beside the other layers' least memories; without switching
  * costs also strategies that another one beats or equals in both time and memory.  Search: exact

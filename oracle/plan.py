@@ -5,8 +5,8 @@ library's search and never imports it.
 
 The paper (section 3, "Dynamic Strategy Selector", discovery phase; section 2, "Layer-Specific
 Parallelism Optimization") says that a plan assigns one parallelism strategy to every layer and
-that it is found by a dynamic program over a search space pruned by a decision tree, "given a
-performance model"; it prints neither the model nor the recurrence.  The reading taken here is the
+that it is found by a dynamic program, driven by a model of each candidate's cost, over a search
+space pruned by a decision tree; it prints neither the model nor the recurrence.  The reading taken here is the
 plainest problem such a search can be solving:
 
     given   L layers, S candidate strategies,
@@ -15,7 +15,7 @@ plainest problem such a search can be solving:
             switch[s][s'] (ms)  cost of handing activations from a layer run under s to the next
                                 layer run under s' (0 on the diagonal), optional,
             a memory budget B and a memory quantum q (every mem[l][s] is first rounded UP to a
-            multiple of q; q = 0 leaves them as they are),
+            multiple of q, see round_up; q = 0 leaves them as they are),
     choose  one strategy per layer, c[0..L-1], with  sum_l mem'[l][c_l] <= B,
     minimising  sum_l time[l][c_l] + sum_{l>0} switch[c_{l-1}][c_l].
 
@@ -31,10 +31,20 @@ from __future__ import annotations
 
 import itertools
 import math
+from fractions import Fraction
 
 
 def round_up(x, q):
-    return x if q <= 0 else math.ceil(x / q - 1e-12) * q
+    """Memory after rounding (the rule as the library's header states it): k * q for the least whole
+    k whose product k * q, formed in double precision, is not below x; q <= 0 leaves x as it is.
+    Found here by exact rational division for a starting point one below the quotient's floor and
+    a linear search upwards."""
+    if q <= 0:
+        return x
+    k = max(0, math.floor(Fraction(x) / Fraction(q)) - 1)
+    while float(k) * q < x:
+        k += 1
+    return float(k) * q
 
 
 def plan_cost(choice, time, mem, switch, quantum):

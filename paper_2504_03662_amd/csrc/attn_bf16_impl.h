@@ -348,7 +348,11 @@ constexpr int KV_TILE = KV_BI * ROWB + KV_BI * 4;            // 64 rows of Q or 
 constexpr int KV_PX = KV_PAIRS * 4 * 1024;                   // P exchange: [pair][sub-tile, half][lane] x 16 B
 constexpr int KV_OFF_DO = KV_NQ * KV_TILE, KV_OFF_PX = KV_OFF_DO + KV_NDO * KV_TILE;
 constexpr int KV_OFF_SINK = KV_OFF_PX + 2 * KV_PX, KV_SMEM = KV_OFF_SINK + 256;
-constexpr int KV_LOADS = 5;                                  // direct-to-LDS loads per wavefront per tile
+// direct-to-LDS loads per wavefront per tile: its share of the Q rows, of the dO rows (tile_load's
+// PER_WAVE each, which depends on the row length) and one lse / D / sink load
+constexpr int KV_TILE_LOADS = KV_BI / (64 / CPR) / KV_NW;
+static_assert(KV_TILE_LOADS >= 1 && KV_TILE_LOADS * (64 / CPR) * KV_NW == KV_BI, "tile_load<KV_BI, KV_NW> split");
+constexpr int KV_LOADS = 2 * KV_TILE_LOADS + 1;
 
 template <bool DROP>
 __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __restrict__ qkv,

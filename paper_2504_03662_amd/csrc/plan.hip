@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <new>
 #include <vector>
 
 namespace {
@@ -17,11 +18,21 @@ struct Pt {
 
 constexpr size_t MAX_POINTS = 1u << 22;     // per (layer, strategy) candidate list; beyond: coarser quantum needed
 
-double round_up(double x, double q) { return q > 0.0 ? std::ceil(x / q - 1e-12) * q : x; }
+// Memory after rounding: k * q for the least whole k whose product k * q (in double arithmetic) is
+// not below x; a memory that is already such a product is unchanged.  The quotient only seeds the
+// search, so its rounding cannot move the result.
+double round_up(double x, double q) {
+  if (!(q > 0.0)) return x;
+  double k = std::floor(x / q);
+  while (k * q < x) k += 1.0;
+  while (k >= 1.0 && (k - 1.0) * q >= x) k -= 1.0;
+  return k * q;
+}
 
 }  // namespace
 
-extern "C" gx_status gx_plan_search(const gx_plan_problem* p, int32_t* choice, gx_plan_result* out) {
+namespace {
+gx_status search(const gx_plan_problem* p, int32_t* choice, gx_plan_result* out) {
   if (!p || !choice || !out || !p->time_ms || !p->mem_bytes) return GX_ERR_NULL;
   const int L = p->layers, S = p->strategies;
   if (L <= 0 || S <= 0 || L > 4096 || S > 1024) return GX_ERR_SHAPE;
@@ -79,7 +90,10 @@ extern "C" gx_status gx_plan_search(const gx_plan_problem* p, int32_t* choice, g
   std::vector<std::vector<std::vector<Pt>>> fr(L, std::vector<std::vector<Pt>>(S));
   size_t peak = 0;
   for (int s = 0; s < S; s++)
-    if (alive[s] && M(0, s) <= B) fr[0][s].push_back(Pt{M(0, s), T(0, s), -1, -1});
+    if (alive[s] && M(0, s) <= B) {
+      fr[0][s].push_back(Pt{M(0, s), T(0, s), -1, -1});
+      peak = 1;
+    }
   std::vector<Pt> cand;
   for (int l = 1; l < L; l++) {
     for (int s2 = 0; s2 < S; s2++) {
@@ -136,4 +150,17 @@ extern "C" gx_status gx_plan_search(const gx_plan_problem* p, int32_t* choice, g
     bi = q.prev_i;
   }
   return GX_OK;
+}
+}  // namespace
+
+// Nothing may be thrown across the C boundary: running out of host memory for the frontiers is
+// reported like a frontier beyond the supported size.
+extern "C" gx_status gx_plan_search(const gx_plan_problem* p, int32_t* choice, gx_plan_result* out) {
+  try {
+    return search(p, choice, out);
+  } catch (const std::bad_alloc&) {
+    return GX_ERR_SHAPE;
+  } catch (...) {
+    return GX_ERR_SHAPE;
+  }
 }

@@ -1,13 +1,11 @@
 """GPU parity at the graded workloads' full shapes, in the launch configuration the benchmark
 times (same shapes, flags and schedules), against the fp64 CPU oracle.
 
-C3 is compared in full.  C2 runs its 4-block stack in full.  C4's feed-forward half is 11.5 TFLOP
-in fp64, so it is checked exactly on sampled tokens: the feed-forward half acts on each token
-independently, and with an upstream gradient that is zero outside the sampled tokens the oracle
-needs only those rows to produce every gradient of the full-size run.  C5's stage (8 blocks x 8
-micro-batches, 128 TFLOP) is cut to 2 blocks x 3 micro-batches at the full per-block shape, with
-the same 1F1B order, recomputation and gradient accumulation; the full 8 x 8 schedule is
-exercised at a small shape."""
+C3 and C4 are compared in full (every output element, every gradient).  C2 runs its 4-block
+stack in full.  C5's stage runs all 8 blocks at the full per-block shape with 2 micro-batches in
+1F1B order, recomputation and gradient accumulation, every block's gradients compared (the
+oracle's cost grows with the number of micro-batches, not the depth of the error chain, so the
+micro-batch count is what is cut); the full 8 x 8 schedule is exercised at a small shape."""
 import numpy as np
 import pytest
 import torch
@@ -59,32 +57,14 @@ def test_c2_stack_of_four_blocks_full():
             check(f"block{k}.d{n}", to_host(stack.layers[k].grads[n]), grads[k][n], TOLB)
 
 
-def test_c4_mixed_degree_block_sampled_tokens():
+def test_c4_mixed_degree_block_full():
     shape, _, _ = I.WORKLOADS["C4"]               # attention TP=8 shard, feed-forward unsharded
     params = I.rank_params(shape, case=4)
     x, dy = I.activations(shape, case=4)
-    rows = np.sort(np.random.default_rng(44).choice(shape.tokens, size=384, replace=False))
-    rows[0], rows[-1] = 0, shape.tokens - 1
-    dy_s = np.zeros_like(dy)
-    dy_s[rows] = dy[rows]
-    layer = DeviceLayer(shape, params)
-    xd = to_device(x, "bf16")
-    y = layer.forward(xd)["y"]
-    dx = layer.backward(xd, to_device(dy_s, "bf16"))
-    torch.cuda.synchronize()
-    # oracle: attention half in full, feed-forward half on the sampled tokens only
-    p_attn, ca = O.attn_half_fwd(shape, params, x)
-    h1 = x + p_attn
-    sub = shape.with_(seq=len(rows), micro_batch=1)
-    p_mlp, cm = O.mlp_half_fwd(sub, params, h1[rows])
-    check("y[sampled]", to_host(y)[rows], h1[rows] + p_mlp, TOLB)
-    dh1_rows, gm = O.mlp_half_bwd(sub, params, dy_s[rows], cm)
-    dh1 = dy_s.astype(np.float64)
-    dh1[rows] += dh1_rows
-    dx_ln, ga = O.attn_half_bwd(shape, params, dh1, ca)
-    check("dx", to_host(dx), dh1 + dx_ln, TOLB)
-    for n, g in {**ga, **gm}.items():
-        check("d" + n, to_host(layer.grads[n]), g, TOLB)
+    report = {}
+    gpu, ref, _ = run_both(shape, params, x, dy)
+    compare(gpu, ref, TOLB, report=report)
+    print("C4 max-rel / l2 / mixed:", {k: "%.1e %.1e %.1e" % v for k, v in report.items()})
 
 
 def _run_stage(shape, plist, xs, dys, wgrad_bf16=False, overlap=True):
@@ -103,20 +83,44 @@ def _run_stage(shape, plist, xs, dys, wgrad_bf16=False, overlap=True):
     return stack, {m: to_host(t) for m, t in ys.items()}, {m: to_host(t) for m, t in dxs.items()}
 
 
-def test_c5_pipeline_stage_full_shape_reduced_depth():
-    shape, _, _ = I.WORKLOADS["C5"]
-    blocks, mbs = 2, 3
+def _free_host_memory():
+    import gc
+    gc.collect()
+
+
+def test_c5_pipeline_stage_full_shape_full_depth():
+    """All 8 blocks at C5's per-block shape; 2 micro-batches, so that the 1F1B order, recomputation
+    and accumulation are all in play.  Prints the error of every block's gradients: the first
+    block's see the rounding of all eight."""
+    shape, blocks, _ = I.WORKLOADS["C5"]
+    mbs = 2
     plist = [I.rank_params(shape, case=5, block=k) for k in range(blocks)]
     acts = [I.activations(shape, case=5, micro_batch_index=m) for m in range(mbs)]
     xs, dys = [a[0] for a in acts], [a[1] for a in acts]
     stack, ys, dxs = _run_stage(shape, plist, xs, dys)
     ys_ref, dxs_ref, tot = O.pipeline_stage(shape, plist, xs, dys)
+    report = {}
+    failures = []
+
+    def chk(name, got, ref):
+        try:
+            check(name, got, ref, TOLB, report)
+        except AssertionError as e:
+            failures.append(str(e))
+
     for m in range(mbs):
-        check(f"y[{m}]", ys[m], ys_ref[m], TOLB)
-        check(f"dx[{m}]", dxs[m], dxs_ref[m], TOLB)
+        chk(f"y[{m}]", ys[m], ys_ref[m])
+        chk(f"dx[{m}]", dxs[m], dxs_ref[m])
     for k in range(blocks):
         for n in I.PARAM_NAMES:
-            check(f"block{k}.d{n}", to_host(stack.layers[k].grads[n]), tot[k][n], TOLB)
+            chk(f"block{k}.d{n}", to_host(stack.layers[k].grads[n]), tot[k][n])
+            tot[k][n] = None
+        _free_host_memory()
+    for k in range(blocks):
+        worst = max(I.PARAM_NAMES, key=lambda n: report[f"block{k}.d{n}"][0])
+        print(f"C5 block {k}: worst gradient d{worst} max-rel %.1e l2 %.1e mixed %.1e" % report[f"block{k}.d{worst}"])
+    print("C5 y/dx:", {k: "%.1e %.1e %.1e" % v for k, v in report.items() if not k.startswith("block")})
+    assert not failures, failures
 
 
 def test_pipeline_stage_8_blocks_8_micro_batches_small_shape():
@@ -128,14 +132,13 @@ def test_pipeline_stage_8_blocks_8_micro_batches_small_shape():
     xs, dys = [a[0] for a in acts], [a[1] for a in acts]
     stack, ys, dxs = _run_stage(shape, plist, xs, dys)
     ys_ref, dxs_ref, tot = O.pipeline_stage(shape, plist, xs, dys)
-    # eight stacked blocks compound the bf16 rounding of the residual stream: outputs are compared
-    # at the stated tolerance, gradients at twice it (documented with the tolerance derivation)
+    report = {}
     for m in range(mbs):
-        check(f"y[{m}]", ys[m], ys_ref[m], TOLB)
-        check(f"dx[{m}]", dxs[m], dxs_ref[m], 2 * TOLB)
-    for k in (0, blocks - 1):
+        check(f"y[{m}]", ys[m], ys_ref[m], TOLB, report)
+        check(f"dx[{m}]", dxs[m], dxs_ref[m], TOLB, report)
+    for k in range(blocks):
         for n in I.PARAM_NAMES:
-            check(f"block{k}.d{n}", to_host(stack.layers[k].grads[n]), tot[k][n], 2 * TOLB)
+            check(f"block{k}.d{n}", to_host(stack.layers[k].grads[n]), tot[k][n], TOLB, report)
 
 
 def test_pipeline_stage_with_every_variant_at_once():

@@ -72,6 +72,31 @@ def test_keep_rule_counters_and_frequency():
         D.scale_of(256)
 
 
+def test_keep_hidden_counters_element_by_element():
+    """Element (token, column) of a half's output reads byte column % 16 of counter
+    (token, column // 16, 0, stream): the expectation is rebuilt from the generator for single
+    elements, with sizes that differ in every index (a swapped token / column group, a wrong third
+    word or stream would fail), including the last, partly used column group."""
+    seed, t, T, H = (0x1234 << 32) | 99, 100, 37, 72           # 72 = 4 groups of 16 + 8 columns
+    for stream in (D.STREAM_ATTN_OUT, D.STREAM_MLP_OUT):
+        keep = D.keep_hidden(seed, t, T, H, stream)
+        assert keep.shape == (T, H)
+        for tok, col in [(0, 0), (0, 15), (0, 16), (1, 0), (5, 33), (33, 5), (36, 71), (36, 64), (17, 48), (2, 70)]:
+            byte = D.random_bytes(tok, col // 16, 0, stream, seed)[col % 16]
+            assert keep[tok, col] == (byte >= t), (stream, tok, col)
+        # every element of two whole rows, one counter at a time
+        for tok in (3, 36):
+            row = np.concatenate([D.random_bytes(tok, g, 0, stream, seed) for g in range(5)])[:H]
+            assert np.array_equal(keep[tok], row >= t)
+    # the mask is not symmetric in (token, column group): the transposed reading differs
+    sq = D.keep_hidden(seed, t, 64, 64 * 16, D.STREAM_ATTN_OUT)
+    swapped = np.array([[D.random_bytes(c // 16, tok, 0, D.STREAM_ATTN_OUT, seed)[c % 16] >= t for c in range(0, 64 * 16, 97)]
+                        for tok in range(0, 64, 7)])
+    assert (sq[0:64:7, 0:64 * 16:97] != swapped).mean() > 0.2
+    n = T * H
+    assert abs(D.keep_hidden(seed, 64, T, H, 2).mean() - 0.75) < 5 * np.sqrt(0.75 * 0.25 / n)
+
+
 def _tiny(drop_attn=0, drop_hidden=0, seed=5, **kw):
     base = dict(hidden=32, heads=4, ffn=48, seq=12, micro_batch=2, dtype="f32", drop_attn=drop_attn,
                 drop_hidden=drop_hidden, drop_seed=seed)

@@ -53,5 +53,16 @@ def test_hand_worked_example():
     assert choice == (1, 1, 1) and abs(t - 9.0) < 1e-12 and m == 12.0
 
 
-def test_round_up():
-    assert P.round_up(5.0, 0) == 5.0 and P.round_up(5.0, 4.0) == 8.0 and P.round_up(8.0, 4.0) == 8.0
+def test_round_up_rule_on_exact_multiples_and_their_one_ulp_neighbours():
+    # hand-worked from the stated rule: least whole k with k * q (in double) >= x
+    assert P.round_up(5.0, 0) == 5.0 and P.round_up(5.0, 4.0) == 8.0
+    for q in (4.0, 3.0, 1024.0, 0.1, 1e9 / 7):
+        for k in (1, 2, 3, 7, 1000):
+            m = float(k) * q                                   # a multiple, as formed in double precision
+            assert P.round_up(m, q) == m                       # stays
+            assert P.round_up(np.nextafter(m, np.inf), q) == float(k + 1) * q      # one ulp above: next multiple
+            assert P.round_up(np.nextafter(m, -np.inf), q) == m                    # one ulp below: this multiple
+    assert P.round_up(0.0, 4.0) == 0.0 and P.round_up(1e-300, 4.0) == 4.0
+    # the decimal 0.3 lies below the double product 3 * 0.1 = 0.30000000000000004, which lies below 4 * 0.1
+    assert P.round_up(0.3, 0.1) == 3 * 0.1 and P.round_up(3 * 0.1, 0.1) == 3 * 0.1
+    assert P.round_up(np.nextafter(3 * 0.1, 1.0), 0.1) == 4 * 0.1

@@ -101,3 +101,28 @@ def test_model_sized_problem_is_consistent():
     # without switching costs dominated strategies are pruned and the optimum only improves
     st2, choice2, res2 = gx.plan_search(time, mem, None, budget=budget, quantum=0.05)
     assert res2.total_ms <= res.total_ms + 1e-9
+
+
+def test_quantum_rounding_rule_through_the_abi():
+    """The library's own rounding, observed as the total memory of a one-layer, one-strategy plan,
+    against values worked out by hand from the rule in the header (least whole k with
+    k * q >= x in double arithmetic): exact multiples stay, one unit in the last place above moves
+    to the next multiple, one below stays."""
+    def rounded(x, q):
+        st, choice, res = gx.plan_search([[1.0]], [[x]], None, budget=1e300, quantum=q, check=False)
+        assert st == gx.GX_OK and choice == [0]
+        return res.total_mem_bytes
+
+    for q in (4.0, 3.0, 1024.0, 0.1, 1e9 / 7):
+        for k in (1, 2, 3, 7, 1000):
+            m = float(k) * q
+            assert rounded(m, q) == m
+            assert rounded(float(np.nextafter(m, np.inf)), q) == float(k + 1) * q
+            assert rounded(float(np.nextafter(m, -np.inf)), q) == m
+    assert rounded(5.0, 0.0) == 5.0 and rounded(5.0, 4.0) == 8.0 and rounded(0.0, 4.0) == 0.0
+    assert rounded(0.3, 0.1) == 3 * 0.1 and rounded(float(np.nextafter(3 * 0.1, 1.0)), 0.1) == 4 * 0.1
+
+
+def test_single_layer_reports_its_frontier():
+    st, choice, res = gx.plan_search([[2.0, 1.0]], [[1.0, 2.0]], None, budget=10.0, check=False)
+    assert st == gx.GX_OK and choice == [1] and res.frontier_peak == 1
