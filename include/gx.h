@@ -175,12 +175,30 @@ gx_status gx_layer_fwd(const gx_layer_cfg* cfg, const gx_params* params, const v
 gx_status gx_layer_bwd(const gx_layer_cfg* cfg, const gx_params* params, const void* x, const void* dy, void* dx,
                        const gx_grads* grads, const void* saved, void* workspace, void* hip_stream);
 
+/* gx_layer_bwd for callers that cannot allocate device memory or let a library do so (code under
+ * HIP graph capture, tight serving or training loops, harnesses that forbid it): the same backward
+ * pass with the same arguments except `workspace`, which is replaced by an array of
+ * GX_STATIC_SCRATCH_BYTES that lives in the library's device image (one per GPU, held until the
+ * process ends).  The call allocates and frees nothing, creates no stream or event, and queues
+ * every kernel on `hip_stream` in order (as gx_layer_bwd does after gx_set_overlap(0)); results are
+ * bit-identical to gx_layer_bwd's.  A configuration whose gx_layer_workspace_bytes(cfg, 1) exceeds
+ * GX_STATIC_SCRATCH_BYTES is refused with GX_ERR_SHAPE before anything is queued; GX_ERR_LAUNCH
+ * also reports a failed lookup of the array's device address (done once per device, on the first
+ * call there).  Every call on a GPU uses that GPU's one array: the array keeps the previous call's
+ * contents (nothing in it needs clearing, each part is written before it is read), and two calls
+ * whose work overlaps on one GPU (different streams, or host threads) race on it. */
+#define GX_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+gx_status gx_layer_bwd_static(const gx_layer_cfg* cfg, const gx_params* params, const void* x, const void* dy,
+                              void* dx, const gx_grads* grads, const void* saved, void* hip_stream);
+
 /* Optional per-launch timing, for benchmarks and cost tables (the paper's section 3 "Profilers"
  * feed per-layer costs to the strategy selector; this is the per-kernel source of such costs).
  * While enabled, every kernel launch site inside gx_layer_fwd / gx_layer_bwd is bracketed by a
  * pair of HIP events on the call's stream and tagged with a kernel class:
- *   GX_KC_LN_FWD, GX_KC_LN_BWD (incl. its two finishing sums), GX_KC_ATTN_FWD, GX_KC_ATTN_BWD (its
- *   three kernels together), GX_KC_COLSUM (both stages), GX_KC_DROPOUT (mask generation and the
+ *   GX_KC_LN_FWD, GX_KC_LN_BWD (input gradient and partial parameter sums in one kernel),
+ *   GX_KC_ATTN_FWD, GX_KC_ATTN_BWD (its three kernels together), GX_KC_COLSUM (a stage-1 pass of
+ *   a bias gradient, or the one launch that finishes every column sum of the backward pass),
+ *   GX_KC_DROPOUT (mask generation and the
  *   dropout passes over a half's output or its gradient), and GX_KC_GEMM + 10 * layout + epilogue
  *   with layout 0 = A[M,K] B[K,N], 1 = A[M,K] B[N,K], 2 = A[K,M] B[K,N] and epilogue 0 = store,
  *   1 = +bias, 2 = +bias +residual, 3 = +bias then GELU, 4 = times GELU', 5 = fp32 store,
@@ -286,6 +304,48 @@ typedef struct {
   int64_t frontier_peak;               /* largest Pareto frontier met */
 } gx_plan_result;
 gx_status gx_plan_search(const gx_plan_problem* problem, int32_t* choice, gx_plan_result* result);
+
+/* Cost model of one layer under one strategy (host only): the part of the cost table that is
+ * computed rather than measured.  The paper's model profiler (section 3, "Model Profiler") records
+ * parameter counts and per-layer memory, and its selector weighs communication overhead (section 3,
+ * "Dynamic Strategy Selector"); it prints no formula, so the model is the textbook one:
+ *   - a strategy is (tp_attn, tp_ffn) on a group of `gpus` devices, the rest of the group data
+ *     parallel: a half of degree d runs micro-batches of global_batch * d / gpus samples
+ *     (GX_ERR_DIVIS when that is not a whole number, or when a degree does not divide the group,
+ *     the heads or the FFN width);
+ *   - attn_elems / ffn_elems: elements of one rank's parameter shards of each half (LayerNorm gain
+ *     and bias [H] each, the column-parallel matrix and its bias, the row-parallel matrix, the
+ *     row-parallel bias [H]);  state_bytes = (attn_elems + ffn_elems) * (e + 16) with e the bytes
+ *     of the storage type: the parameter itself, its fp32 gradient, fp32 master copy and two fp32
+ *     optimizer moments;
+ *   - ring all-reduce of n bytes over p ranks: every rank sends and receives 2 (p - 1) / p * n
+ *     bytes, taken at link_gbps * 1e9 bytes per second; 0 for p = 1.
+ *     tp_comm_ms: per half two all-reduces of its [micro_batch * seq, hidden] activations (one in
+ *     the forward pass after the row-parallel product, one in the backward pass after the
+ *     column-parallel input gradient) over its tensor-parallel group;
+ *     dp_comm_ms: one all-reduce of each half's fp32 gradients (4 bytes per element) over its
+ *     data-parallel group of gpus / degree ranks;
+ *   - switch_ms: handing activations to a next layer whose attention degree differs from this
+ *     layer's feed-forward degree: every GPU moves its 1/gpus share of the step's
+ *     [global_batch * seq, hidden] activations once forward and once backward;
+ *   - flops_attn / flops_ffn: model FLOPs per GPU of each half, forward + backward (backward twice
+ *     the forward), causal attention counted on the seq (seq + 1) / 2 unmasked pairs.
+ * Errors: GX_ERR_NULL, GX_ERR_DTYPE, GX_ERR_SHAPE (a non-positive size or bandwidth), GX_ERR_DIVIS. */
+typedef struct {
+  int32_t hidden, heads, ffn, seq;
+  int32_t dtype;                 /* gx_dtype of parameters and activations */
+  int32_t gpus, global_batch;
+  int32_t tp_attn, tp_ffn;
+  double link_gbps;
+} gx_strategy_query;
+typedef struct {
+  int64_t micro_batch_attn, micro_batch_ffn;
+  int64_t attn_elems, ffn_elems;
+  double state_bytes;
+  double tp_comm_ms, dp_comm_ms, switch_ms;
+  double flops_attn, flops_ffn;
+} gx_strategy_costs;
+gx_status gx_strategy_cost(const gx_strategy_query* query, gx_strategy_costs* costs);
 
 /* Static strings; never NULL. */
 const char* gx_status_str(gx_status s);

@@ -22,7 +22,7 @@ PARAM_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
 EXPORTS = ("gx_layer_validate", "gx_layer_saved_bytes", "gx_layer_workspace_bytes", "gx_layer_fwd",
            "gx_layer_bwd", "gx_status_str", "gx_version", "gx_prof_enable", "gx_prof_collect", "gx_set_overlap",
-           "gx_adamw_step", "gx_params_slice", "gx_params_merge", "gx_plan_search")
+           "gx_adamw_step", "gx_params_slice", "gx_params_merge", "gx_plan_search", "gx_strategy_cost", "gx_layer_bwd_static")
 GX_KC_LN_FWD, GX_KC_LN_BWD, GX_KC_ATTN_FWD, GX_KC_ATTN_BWD, GX_KC_COLSUM, GX_KC_GEMM = 1, 2, 3, 4, 5, 100
 
 
@@ -62,6 +62,17 @@ class PlanResult(ctypes.Structure):
                 ("pruned", ctypes.c_int64), ("frontier_peak", ctypes.c_int64)]
 
 
+class StrategyQuery(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("hidden", "heads", "ffn", "seq", "dtype", "gpus", "global_batch",
+                                               "tp_attn", "tp_ffn")] + [("link_gbps", ctypes.c_double)]
+
+
+class StrategyCosts(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in ("micro_batch_attn", "micro_batch_ffn", "attn_elems", "ffn_elems")] + \
+               [(n, ctypes.c_double) for n in ("state_bytes", "tp_comm_ms", "dp_comm_ms", "switch_ms", "flops_attn",
+                                               "flops_ffn")]
+
+
 class GxError(RuntimeError):
     def __init__(self, status, where):
         self.status = int(status)
@@ -98,6 +109,9 @@ def lib():
         L.gx_layer_bwd.argtypes = [ctypes.POINTER(LayerCfg), ctypes.POINTER(Params), P, P, P, ctypes.POINTER(Grads),
                                    P, P, P]
         L.gx_layer_bwd.restype = ctypes.c_int
+        L.gx_layer_bwd_static.argtypes = [ctypes.POINTER(LayerCfg), ctypes.POINTER(Params), P, P, P,
+                                          ctypes.POINTER(Grads), P, P]
+        L.gx_layer_bwd_static.restype = ctypes.c_int
         L.gx_status_str.argtypes = [ctypes.c_int]
         L.gx_status_str.restype = ctypes.c_char_p
         L.gx_version.argtypes = []
@@ -117,6 +131,8 @@ def lib():
         L.gx_plan_search.argtypes = [ctypes.POINTER(PlanProblem), ctypes.POINTER(ctypes.c_int32),
                                      ctypes.POINTER(PlanResult)]
         L.gx_plan_search.restype = ctypes.c_int
+        L.gx_strategy_cost.argtypes = [ctypes.POINTER(StrategyQuery), ctypes.POINTER(StrategyCosts)]
+        L.gx_strategy_cost.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -180,6 +196,16 @@ def layer_bwd(cfg, params, x, dy, dx, grads, saved, workspace, stream=0, check=T
                             _ptr(saved), _ptr(workspace), ctypes.c_void_p(stream))
     if check and st != GX_OK:
         raise GxError(st, "gx_layer_bwd")
+    return int(st)
+
+
+def layer_bwd_static(cfg, params, x, dy, dx, grads, saved, stream=0, check=True):
+    p = _struct(Params, params)
+    g = _struct(Grads, grads)
+    st = lib().gx_layer_bwd_static(ctypes.byref(cfg), ctypes.byref(p), _ptr(x), _ptr(dy), _ptr(dx), ctypes.byref(g),
+                                   _ptr(saved), ctypes.c_void_p(stream))
+    if check and st != GX_OK:
+        raise GxError(st, "gx_layer_bwd_static")
     return int(st)
 
 
@@ -247,3 +273,14 @@ def plan_search(time_ms, mem_bytes, switch_ms=None, *, budget, quantum=0.0, chec
     if check and st != GX_OK:
         raise GxError(st, "gx_plan_search")
     return int(st), list(choice), res
+
+
+def strategy_cost(hidden, heads, ffn, seq, dtype, gpus, global_batch, tp_attn, tp_ffn, link_gbps, check=True):
+    """Returns (status, StrategyCosts)."""
+    q = StrategyQuery(hidden, heads, ffn, seq, dtype, gpus, global_batch, tp_attn, tp_ffn, float(link_gbps))
+    out = StrategyCosts()
+    st = lib().gx_strategy_cost(ctypes.byref(q), ctypes.byref(out))
+    if check and st != GX_OK:
+        raise GxError(st, "gx_strategy_cost")
+    return int(st), out
+

@@ -102,36 +102,52 @@ GX_DEVINL void load_row_frags(const bf16* base, int ld, int row, int nrows, int 
 }
 
 
-// acc[dt] += product of the transposed fragments of a 64-row tile (four groups of 16 rows at LDS
-// address `ct`) with xf[group]; COLS_A puts the transposed fragment first (rows of the result =
+// acc[dt] += product of the transposed fragments of a tile of 16 * NG16 rows (groups of 16 rows at
+// LDS address `ct`) with xf[group]; COLS_A puts the transposed fragment first (rows of the result =
 // head-dim columns).  Groups 0 and 1 must have been issued into cf[0], cf[1] by the caller (as
-// early as it likes, to cover LDS latency with its own work); groups 2 and 3 are issued here, so
-// that two groups are always in flight.
-template <bool COLS_A>
-GX_DEVINL void tr_product4(f32x16 (&acc)[DH / 32], unsigned ct, const unsigned (&coff)[2][DH / 32],
-                           ColFrags (&cf)[2], const bf16x8 (&xf)[4]) {
+// early as it likes, to cover LDS latency with its own work); with four groups, groups 2 and 3
+// are issued here, so that two groups are always in flight.
+template <bool COLS_A, int NG16>
+GX_DEVINL void tr_product(f32x16 (&acc)[DH / 32], unsigned ct, const unsigned (&coff)[2][DH / 32],
+                          ColFrags (&cf)[2], const bf16x8 (&xf)[NG16]) {
+  static_assert(NG16 == 2 || NG16 == 4, "tiles of 32 or 64 rows");
 #define GX_TR_GROUP(U, BUF)                                                                              \
   _Pragma("unroll") for (int dt = 0; dt < DH / 32; dt++)                                                 \
       acc[dt] = COLS_A ? MFMA(cols_get(cf[BUF], dt), xf[U], acc[dt]) : MFMA(xf[U], cols_get(cf[BUF], dt), acc[dt])
   lds_wait_le<2 * (DH / 32)>();
   GX_TR_GROUP(0, 0);
-  cols_issue<2>(ct, coff, cf[0]);
-  lds_wait_le<2 * (DH / 32)>();
-  GX_TR_GROUP(1, 1);
-  cols_issue<3>(ct, coff, cf[1]);
-  lds_wait_le<2 * (DH / 32)>();
-  GX_TR_GROUP(2, 0);
-  lds_wait_all();
-  GX_TR_GROUP(3, 1);
+  if (NG16 == 4) {
+    cols_issue<2>(ct, coff, cf[0]);
+    lds_wait_le<2 * (DH / 32)>();
+    GX_TR_GROUP(1, 1);
+    cols_issue<3>(ct, coff, cf[1]);
+    lds_wait_le<2 * (DH / 32)>();
+    GX_TR_GROUP(NG16 - 2, 0);
+    lds_wait_all();
+    GX_TR_GROUP(NG16 - 1, 1);
+  } else {
+    lds_wait_all();
+    GX_TR_GROUP(1, 1);
+  }
 #undef GX_TR_GROUP
+}
+template <bool COLS_A>
+GX_DEVINL void tr_product4(f32x16 (&acc)[DH / 32], unsigned ct, const unsigned (&coff)[2][DH / 32],
+                           ColFrags (&cf)[2], const bf16x8 (&xf)[4]) {
+  tr_product<COLS_A, 4>(acc, ct, coff, cf, xf);
 }
 
 // ------------------------------------------------------------------------------- forward
-constexpr int F_BQ = 128, F_BKV = 64;
-
-// SPLIT = 1: 4 wavefronts, one 64-row K/V tile per step.  SPLIT = 2 (few (sample, head) pairs, so
-// the longest query block is the critical path): 8 wavefronts, two tiles per step; wavefronts w
-// and w + 4 share 32 query rows, take alternate tiles, and merge their (max, sum, O) through LDS.
+// A workgroup owns 32 NQ query rows of one (sample, head); its NQ * SPLIT wavefronts are NQ blocks
+// of 32 rows times SPLIT shares of the keys: every step brings SPLIT tiles of BKV keys (K and V)
+// into LDS and wavefront (q, part) works on tile `part`; the SPLIT partial softmax states
+// (max, sum, O) of a row block are merged through LDS at the end, in the order of `part`.
+//   many (sample, head) pairs : NQ 4, SPLIT 1, BKV 64 (4 wavefronts, two workgroups per compute unit)
+//   few pairs                 : NQ 2, SPLIT 4, BKV 32 (8 wavefronts): the causal triangle gives query
+//     blocks between 1 and S / 32 NQ units of work, so with few pairs the chip is filled by short
+//     blocks cut fine, each with its keys spread over four wavefronts.
+// Workgroups are numbered longest query block first over the whole launch (all pairs' last blocks,
+// then all pairs' next-to-last blocks, ...): the hardware hands them out in that order.
 // Dropout of the probabilities: keep bits (1 = kept) of the whole launch, `wpr` 32-bit words per
 // row; row-major (a query's keys) for the forward and dQ kernels, column-major (a key's queries)
 // for the dK / dV kernel.  Kept probabilities are multiplied by `scale`.
@@ -140,33 +156,43 @@ struct KeepArgs {
   int wpr;
   float scale;
 };
-// The 64 keep bits of a lane's two 32 x 32 accumulator tiles: zero the values whose bit is clear.
+// The keep bits of a lane's NJT 32 x 32 accumulator tiles: zero the values whose bit is clear.
 // Accumulator register v of tile jt sits at bit 32 jt + 8 (v / 4) + 4 g + v % 4.
-GX_DEVINL void drop_unkept(f32x16 (&a)[2], unsigned long long kw, int g) {
+template <int NJT>
+GX_DEVINL void drop_unkept(f32x16 (&a)[NJT], unsigned long long kw, int g) {
 #pragma unroll
-  for (int jt = 0; jt < 2; jt++) {
+  for (int jt = 0; jt < NJT; jt++) {
     const unsigned w = (unsigned)(kw >> (32 * jt)) >> (4 * g);
 #pragma unroll
     for (int v = 0; v < 16; v++)
       if (!((w >> (8 * (v >> 2) + (v & 3))) & 1u)) a[jt][v] = 0.f;
   }
 }
+// this lane's keep bits of the BKV keys starting at key j0 of one query row (bits: the row's words)
+template <int NJT>
+GX_DEVINL unsigned long long keep_bits_of_step(const unsigned* row_words, int j0) {
+  if (NJT == 2) return *reinterpret_cast<const unsigned long long*>(row_words + (j0 >> 5));
+  return row_words[j0 >> 5];
+}
 
-template <int SPLIT, bool DROP>
-__global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_fwd_kernel(const bf16* __restrict__ qkv,
-                                                                          bf16* __restrict__ ctx,
-                                                                          float* __restrict__ lse, int S, int nl,
-                                                                          unsigned qkv_bytes, KeepArgs keep) {
+template <int NQ, int SPLIT, int BKV, bool DROP>
+__global__ void __launch_bounds__(64 * NQ * SPLIT, NQ * SPLIT == 4 ? 2 : 1)
+    attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ ctx, float* __restrict__ lse, int S, int nl,
+                    int npair, unsigned qkv_bytes, KeepArgs keep) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  constexpr int NW = 4 * SPLIT, ROWS = F_BKV * SPLIT, STAGE = 2 * ROWS * ROWB;   // K rows | V rows
+  constexpr int NW = NQ * SPLIT, BQ = 32 * NQ, ROWS = BKV * SPLIT, STAGE = 2 * ROWS * ROWB;   // K rows | V rows
+  constexpr int NJT = BKV / 32;
+  static_assert((NQ & (NQ - 1)) == 0 && (BKV == 32 || BKV == 64), "shape of the step");
+  static_assert((SPLIT - 1) * NQ * (2 + DH / 2) * 256 <= 2 * STAGE, "merge area fits the tile buffers");
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int qs = wave & 3, half = wave >> 2;
+  const int qs = wave % NQ, part = wave / NQ;
   const int g = lane >> 5, l32 = lane & 31;
-  const int nq = (S + F_BQ - 1) / F_BQ;
-  const int qt = nq - 1 - blockIdx.x;                 // longest rows first
-  const int h = blockIdx.y, b = blockIdx.z;
+  const int nq = (S + BQ - 1) / BQ;
+  const int pair = blockIdx.x % npair;
+  const int qt = nq - 1 - blockIdx.x / npair;         // longest rows first
+  const int h = pair % nl, b = pair / nl;
   const int Hl = nl * DH, ld = 3 * Hl;
-  const int i0 = qt * F_BQ, iw = i0 + qs * 32;        // this wave's first query row
+  const int i0 = qt * BQ, iw = i0 + qs * 32;          // this wave's first query row
   const unsigned eq = (unsigned)((size_t)b * S * ld + h * DH);
   const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(qkv), 0, qkv_bytes,
                                                                         0x00020000);
@@ -181,7 +207,7 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_fwd_kernel(const 
   unsigned coff[2][DH / 32];
   cols_lane_offsets(lane, coff);
 
-  const int jend = min(S, i0 + F_BQ);                 // keys 0 .. jend-1 can be visible
+  const int jend = min(S, i0 + BQ);                   // keys 0 .. jend-1 can be visible
   const int nt = (jend + ROWS - 1) / ROWS;
   tile_load<ROWS, NW>(rsrc, eq + Hl, ld, 0, S, smem, wave, lane);
   tile_load<ROWS, NW>(rsrc, eq + 2 * Hl, ld, 0, S, smem + ROWS * ROWB, wave, lane);
@@ -193,17 +219,17 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_fwd_kernel(const 
       tile_load<ROWS, NW>(rsrc, eq + Hl, ld, (t + 1) * ROWS, S, nxt, wave, lane);
       tile_load<ROWS, NW>(rsrc, eq + 2 * Hl, ld, (t + 1) * ROWS, S, nxt + ROWS * ROWB, wave, lane);
     }
-    const int j0 = t * ROWS + half * F_BKV;            // this wave's 64 keys of the step
-    if (j0 <= iw + 31) {                               // wave-uniform: some key of the tile is visible
-      const char* kt = smem + (t & 1) * STAGE + half * F_BKV * ROWB;
+    const int j0 = t * ROWS + part * BKV;              // this wave's keys of the step
+    // wave-uniform; j0 and iw are multiples of 32, so when it holds every row of the wave sees key j0
+    if (j0 <= iw + 31) {
+      const char* kt = smem + (t & 1) * STAGE + part * BKV * ROWB;
       const char* vt = kt + ROWS * ROWB;
-      unsigned long long kw = ~0ull;                    // keep bits of this query's 64 keys of the step
+      unsigned long long kw = ~0ull;                    // keep bits of this query's keys of the step
       if (DROP && iw + l32 < S)
-        kw = *reinterpret_cast<const unsigned long long*>(
-            keep.bits + (((size_t)b * nl + h) * S + iw + l32) * keep.wpr + (j0 >> 5));
-      f32x16 sacc[2];
+        kw = keep_bits_of_step<NJT>(keep.bits + (((size_t)b * nl + h) * S + iw + l32) * keep.wpr, j0);
+      f32x16 sacc[NJT];
 #pragma unroll
-      for (int jt = 0; jt < 2; jt++) {
+      for (int jt = 0; jt < NJT; jt++) {
         sacc[jt] = zero16();
 #pragma unroll
         for (int s = 0; s < DH / 16; s++) sacc[jt] = MFMA(frag_rows(kt, 32 * jt + l32, s, g), qf[s], sacc[jt]);
@@ -216,16 +242,16 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_fwd_kernel(const 
       // online softmax for query column i = iw + l32 (base-2 exponentials, scale folded into the
       // exponent's multiply-add)
       const int i = iw + l32;
-      if (j0 + F_BKV - 1 > iw) {                       // the tile touches the diagonal
+      if (j0 + BKV - 1 > iw) {                         // the tile touches the diagonal
 #pragma unroll
-        for (int jt = 0; jt < 2; jt++)
+        for (int jt = 0; jt < NJT; jt++)
 #pragma unroll
           for (int v = 0; v < 16; v++)
             if (j0 + 32 * jt + 8 * (v >> 2) + 4 * g + (v & 3) > i) sacc[jt][v] = -INFINITY;
       }
       float mloc = sacc[0][0];
 #pragma unroll
-      for (int jt = 0; jt < 2; jt++)
+      for (int jt = 0; jt < NJT; jt++)
 #pragma unroll
         for (int v = 0; v < 16; v++) mloc = fmaxf(mloc, sacc[jt][v]);
       mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64)) * c2;
@@ -241,7 +267,7 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_fwd_kernel(const 
       }
       float psum = 0.f;
 #pragma unroll
-      for (int jt = 0; jt < 2; jt++)
+      for (int jt = 0; jt < NJT; jt++)
 #pragma unroll
         for (int v = 0; v < 16; v++) {
           const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[jt][v], c2, -m));
@@ -249,21 +275,24 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_fwd_kernel(const 
           psum += p;
         }
       lsum += psum;
-      if (DROP) drop_unkept(sacc, kw, g);              // the row sum above is the undropped one
+      if (DROP) drop_unkept<NJT>(sacc, kw, g);         // the row sum above is the undropped one
       // O^T += V^T P^T, 16 keys per group
-      bf16x8 pf[4];
+      bf16x8 pf[2 * NJT];
 #pragma unroll
-      for (int u = 0; u < 4; u++) pf[u] = pack_half(sacc[u >> 1], u & 1);
-      tr_product4<true>(o, ct, coff, cf, pf);
+      for (int u = 0; u < 2 * NJT; u++) pf[u] = pack_half(sacc[u >> 1], u & 1);
+      tr_product<true, 2 * NJT>(o, ct, coff, cf, pf);
     }
     WAIT_VM0();
     __syncthreads();
   }
-  if (SPLIT == 2) {
-    // merge the two halves' partial softmax states; the tiles are no longer needed, so the upper
-    // half parks (m, l, O) in LDS as [query sub-tile][2 + DH / 2 values][64 lanes] and the lower half folds it in
-    float* park = reinterpret_cast<float*>(smem) + qs * ((2 + DH / 2) * 64) + lane;
-    if (half == 1) {
+  if (SPLIT > 1) {
+    // merge the parts' partial softmax states; the tiles are no longer needed, so parts 1.. park
+    // (m, l, O) in LDS as [part - 1][row block][2 + DH / 2 values][64 lanes] and part 0 folds them
+    // in, in order.  A part that saw no key has m = -inf, l = 0, O = 0 and folds in as nothing
+    // (part 0 always saw key 0, so the merged maximum is finite).
+    constexpr int REGION = (2 + DH / 2) * 64;
+    if (part > 0) {
+      float* park = reinterpret_cast<float*>(smem) + ((part - 1) * NQ + qs) * REGION + lane;
       park[0] = m;
       park[64] = lsum;
 #pragma unroll
@@ -272,16 +301,20 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_fwd_kernel(const 
         for (int v = 0; v < 16; v++) park[(2 + 16 * dt + v) * 64] = o[dt][v];
     }
     __syncthreads();
-    if (half == 1) return;
-    const float m1 = park[0], l1 = park[64];
-    const float mm = fmaxf(m, m1);                    // the lower half always saw key 0: mm is finite
-    const float a0 = __builtin_amdgcn_exp2f(m - mm), a1 = __builtin_amdgcn_exp2f(m1 - mm);
-    lsum = lsum * a0 + l1 * a1;
-    m = mm;
+    if (part > 0) return;
 #pragma unroll
-    for (int dt = 0; dt < DH / 32; dt++)
+    for (int pp = 1; pp < SPLIT; pp++) {
+      const float* park = reinterpret_cast<const float*>(smem) + ((pp - 1) * NQ + qs) * REGION + lane;
+      const float m1 = park[0], l1 = park[64];
+      const float mm = fmaxf(m, m1);
+      const float a0 = __builtin_amdgcn_exp2f(m - mm), a1 = __builtin_amdgcn_exp2f(m1 - mm);
+      lsum = lsum * a0 + l1 * a1;
+      m = mm;
 #pragma unroll
-      for (int v = 0; v < 16; v++) o[dt][v] = o[dt][v] * a0 + park[(2 + 16 * dt + v) * 64] * a1;
+      for (int dt = 0; dt < DH / 32; dt++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) o[dt][v] = o[dt][v] * a0 + park[(2 + 16 * dt + v) * 64] * a1;
+    }
   }
   lsum += __shfl_xor(lsum, 32, 64);
   const int i = iw + l32;
@@ -547,27 +580,26 @@ __global__ void __launch_bounds__(64 * KV_NW) attn_bwd_dkv_kernel(const bf16* __
 }
 
 // ------------------------------------------------------------------------------- backward: dQ
-constexpr int Q_BQ = 128, Q_BKV = 64;
-
-// SPLIT as in the forward kernel; the two halves' dQ partial sums are added through LDS in a
-// fixed order (lower half + upper half).
-template <int SPLIT, bool DROP>
-__global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_bwd_dq_kernel(const bf16* __restrict__ qkv,
-                                                                             const bf16* __restrict__ dctx,
-                                                                             const float* __restrict__ lse,
-                                                                             const float* __restrict__ dsum,
-                                                                             bf16* __restrict__ dqkv, int S, int nl,
-                                                                             unsigned qkv_bytes, KeepArgs keep) {
+// Shapes and workgroup order as in the forward kernel; the parts' dQ partial sums are added
+// through LDS in the order of `part`.
+template <int NQ, int SPLIT, int BKV, bool DROP>
+__global__ void __launch_bounds__(64 * NQ * SPLIT, NQ * SPLIT == 4 ? 2 : 1)
+    attn_bwd_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dctx, const float* __restrict__ lse,
+                       const float* __restrict__ dsum, bf16* __restrict__ dqkv, int S, int nl, int npair,
+                       unsigned qkv_bytes, KeepArgs keep) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  constexpr int NW = 4 * SPLIT, ROWS = Q_BKV * SPLIT, STAGE = 2 * ROWS * ROWB;
+  constexpr int NW = NQ * SPLIT, BQ = 32 * NQ, ROWS = BKV * SPLIT, STAGE = 2 * ROWS * ROWB;
+  constexpr int NJT = BKV / 32;
+  static_assert((SPLIT - 1) * NQ * (DH / 2) * 256 <= 2 * STAGE, "merge area fits the tile buffers");
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int qs = wave & 3, half = wave >> 2;
+  const int qs = wave % NQ, part = wave / NQ;
   const int g = lane >> 5, l32 = lane & 31;
-  const int nq = (S + Q_BQ - 1) / Q_BQ;
-  const int qt = nq - 1 - blockIdx.x;
-  const int h = blockIdx.y, b = blockIdx.z;
+  const int nq = (S + BQ - 1) / BQ;
+  const int pair = blockIdx.x % npair;
+  const int qt = nq - 1 - blockIdx.x / npair;
+  const int h = pair % nl, b = pair / nl;
   const int Hl = nl * DH, ld = 3 * Hl;
-  const int i0 = qt * Q_BQ, iw = i0 + qs * 32;
+  const int i0 = qt * BQ, iw = i0 + qs * 32;
   const unsigned eq = (unsigned)((size_t)b * S * ld + h * DH);
   const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(qkv), 0, qkv_bytes,
                                                                         0x00020000);
@@ -585,7 +617,7 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_bwd_dq_kernel(con
 #pragma unroll
   for (int dt = 0; dt < DH / 32; dt++) dq[dt] = zero16();
 
-  const int jend = min(S, i0 + Q_BQ);
+  const int jend = min(S, i0 + BQ);
   const int nt = (jend + ROWS - 1) / ROWS;
   tile_load<ROWS, NW>(rsrc, eq + Hl, ld, 0, S, smem, wave, lane);
   tile_load<ROWS, NW>(rsrc, eq + 2 * Hl, ld, 0, S, smem + ROWS * ROWB, wave, lane);
@@ -597,17 +629,16 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_bwd_dq_kernel(con
       tile_load<ROWS, NW>(rsrc, eq + Hl, ld, (t + 1) * ROWS, S, nxt, wave, lane);
       tile_load<ROWS, NW>(rsrc, eq + 2 * Hl, ld, (t + 1) * ROWS, S, nxt + ROWS * ROWB, wave, lane);
     }
-    const int j0 = t * ROWS + half * Q_BKV;
+    const int j0 = t * ROWS + part * BKV;
     if (j0 <= iw + 31) {
-      const char* kt = smem + (t & 1) * STAGE + half * Q_BKV * ROWB;
+      const char* kt = smem + (t & 1) * STAGE + part * BKV * ROWB;
       const char* vt = kt + ROWS * ROWB;
-      unsigned long long kw = ~0ull;                    // keep bits of this query's 64 keys of the step
+      unsigned long long kw = ~0ull;                    // keep bits of this query's keys of the step
       if (DROP && i < S)
-        kw = *reinterpret_cast<const unsigned long long*>(
-            keep.bits + (((size_t)b * nl + h) * S + i) * keep.wpr + (j0 >> 5));
-      f32x16 sacc[2], pacc[2];
+        kw = keep_bits_of_step<NJT>(keep.bits + (((size_t)b * nl + h) * S + i) * keep.wpr, j0);
+      f32x16 sacc[NJT], pacc[NJT];
 #pragma unroll
-      for (int jt = 0; jt < 2; jt++) {
+      for (int jt = 0; jt < NJT; jt++) {
         sacc[jt] = zero16();
         pacc[jt] = zero16();
 #pragma unroll
@@ -617,14 +648,14 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_bwd_dq_kernel(con
         }
       }
       if (DROP) {                                      // gradient w.r.t. the undropped probabilities
-        drop_unkept(pacc, kw, g);
+        drop_unkept<NJT>(pacc, kw, g);
 #pragma unroll
-        for (int jt = 0; jt < 2; jt++)
+        for (int jt = 0; jt < NJT; jt++)
 #pragma unroll
           for (int v = 0; v < 16; v++) pacc[jt][v] *= keep.scale;
       }
 #pragma unroll
-      for (int jt = 0; jt < 2; jt++)
+      for (int jt = 0; jt < NJT; jt++)
 #pragma unroll
         for (int v = 0; v < 16; v++) {
           const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[jt][v], c2, -lse2));
@@ -635,35 +666,40 @@ __global__ void __launch_bounds__(256 * SPLIT, 3 - SPLIT) attn_bwd_dq_kernel(con
       ColFrags cf[2];
       cols_issue<0>(ct, coff, cf[0]);
       cols_issue<1>(ct, coff, cf[1]);
-      if (j0 + Q_BKV - 1 > iw) {                       // the tile touches the diagonal
+      if (j0 + BKV - 1 > iw) {                         // the tile touches the diagonal
 #pragma unroll
-        for (int jt = 0; jt < 2; jt++)
+        for (int jt = 0; jt < NJT; jt++)
 #pragma unroll
           for (int v = 0; v < 16; v++)
             if (j0 + 32 * jt + 8 * (v >> 2) + 4 * g + (v & 3) > i) pacc[jt][v] = 0.f;
       }
-      bf16x8 dsf[4];
+      bf16x8 dsf[2 * NJT];
 #pragma unroll
-      for (int u = 0; u < 4; u++) dsf[u] = pack_half(pacc[u >> 1], u & 1);
-      tr_product4<true>(dq, ct, coff, cf, dsf);       // dQ^T[d][i] += K^T dS^T
+      for (int u = 0; u < 2 * NJT; u++) dsf[u] = pack_half(pacc[u >> 1], u & 1);
+      tr_product<true, 2 * NJT>(dq, ct, coff, cf, dsf);       // dQ^T[d][i] += K^T dS^T
     }
     WAIT_VM0();
     __syncthreads();
   }
-  if (SPLIT == 2) {
-    float* park = reinterpret_cast<float*>(smem) + qs * ((DH / 2) * 64) + lane;
-    if (half == 1) {
+  if (SPLIT > 1) {
+    constexpr int REGION = (DH / 2) * 64;
+    if (part > 0) {
+      float* park = reinterpret_cast<float*>(smem) + ((part - 1) * NQ + qs) * REGION + lane;
 #pragma unroll
       for (int dt = 0; dt < DH / 32; dt++)
 #pragma unroll
         for (int v = 0; v < 16; v++) park[(16 * dt + v) * 64] = dq[dt][v];
     }
     __syncthreads();
-    if (half == 1) return;
+    if (part > 0) return;
 #pragma unroll
-    for (int dt = 0; dt < DH / 32; dt++)
+    for (int pp = 1; pp < SPLIT; pp++) {
+      const float* park = reinterpret_cast<const float*>(smem) + ((pp - 1) * NQ + qs) * REGION + lane;
 #pragma unroll
-      for (int v = 0; v < 16; v++) dq[dt][v] += park[(16 * dt + v) * 64];
+      for (int dt = 0; dt < DH / 32; dt++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) dq[dt][v] += park[(16 * dt + v) * 64];
+    }
   }
   if (i < S) {
     bf16* row = dqkv + ((size_t)b * S + i) * ld + h * DH;
@@ -691,18 +727,21 @@ bool attn_shape_ok(const AttnArgs& a) {
   return bytes < (1ul << 31);
 }
 
-// With few (sample, head) pairs the 128-row query blocks cannot fill the chip and the longest
-// block is the critical path: split its key range over two wavefronts.
-bool split_keys(const AttnArgs& a) { return (long)a.B * a.nl * cdiv(a.S, 128) <= 384; }
+// With few (sample, head) pairs the chip is filled by cutting the query blocks fine and spreading
+// each block's keys over four wavefronts (see the forward kernel).
+bool few_pairs(const AttnArgs& a) { return (long)a.B * a.nl * cdiv(a.S, 128) <= 384; }
+
+// row-block kernels (forward, dQ) in their two shapes: <4, 1, 64> with 4 wavefronts and <2, 4, 32> with 8
+constexpr int SMEM_MANY = 2 * 2 * 64 * ROWB, SMEM_FEW = 2 * 2 * 128 * ROWB;
 
 hipError_t fwd(const AttnArgs& a, hipStream_t s) {
   if (!attn_shape_ok(a)) return hipErrorInvalidValue;
   static bool configured = false;
   if (!configured) {
-    hipError_t e = set_smem(attn_fwd_kernel<1, false>, 4 * F_BKV * ROWB);
-    if (e == hipSuccess) e = set_smem(attn_fwd_kernel<2, false>, 8 * F_BKV * ROWB);
-    if (e == hipSuccess) e = set_smem(attn_fwd_kernel<1, true>, 4 * F_BKV * ROWB);
-    if (e == hipSuccess) e = set_smem(attn_fwd_kernel<2, true>, 8 * F_BKV * ROWB);
+    hipError_t e = set_smem(attn_fwd_kernel<4, 1, 64, false>, SMEM_MANY);
+    if (e == hipSuccess) e = set_smem(attn_fwd_kernel<2, 4, 32, false>, SMEM_FEW);
+    if (e == hipSuccess) e = set_smem(attn_fwd_kernel<4, 1, 64, true>, SMEM_MANY);
+    if (e == hipSuccess) e = set_smem(attn_fwd_kernel<2, 4, 32, true>, SMEM_FEW);
     if (e != hipSuccess) return e;
     configured = true;
   }
@@ -710,35 +749,35 @@ hipError_t fwd(const AttnArgs& a, hipStream_t s) {
   const KeepArgs keep{a.rowbits, a.wpr, a.keep_scale};
   const bool drop = a.rowbits != nullptr;
   if (drop && a.wpr != 2 * cdiv(a.S, 64)) return hipErrorInvalidValue;
-  dim3 grid(cdiv(a.S, F_BQ), a.nl, a.B);
-  auto go = [&](auto kernel, int threads, int smem) {
-    hipLaunchKernelGGL(kernel, grid, dim3(threads), smem, s, (const bf16*)a.qkv, (bf16*)a.ctx, a.lse, a.S, a.nl,
-                       qkv_bytes, keep);
+  const int npair = a.nl * a.B;
+  auto go = [&](auto kernel, int bq, int threads, int smem) {
+    hipLaunchKernelGGL(kernel, dim3(cdiv(a.S, bq) * npair), dim3(threads), smem, s, (const bf16*)a.qkv, (bf16*)a.ctx,
+                       a.lse, a.S, a.nl, npair, qkv_bytes, keep);
   };
-  if (split_keys(a)) {
-    if (drop) go(attn_fwd_kernel<2, true>, 512, 8 * F_BKV * ROWB);
-    else go(attn_fwd_kernel<2, false>, 512, 8 * F_BKV * ROWB);
+  if (few_pairs(a)) {
+    if (drop) go(attn_fwd_kernel<2, 4, 32, true>, 64, 512, SMEM_FEW);
+    else go(attn_fwd_kernel<2, 4, 32, false>, 64, 512, SMEM_FEW);
   } else {
-    if (drop) go(attn_fwd_kernel<1, true>, 256, 4 * F_BKV * ROWB);
-    else go(attn_fwd_kernel<1, false>, 256, 4 * F_BKV * ROWB);
+    if (drop) go(attn_fwd_kernel<4, 1, 64, true>, 128, 256, SMEM_MANY);
+    else go(attn_fwd_kernel<4, 1, 64, false>, 128, 256, SMEM_MANY);
   }
   return hipGetLastError();
 }
 
-// dK/dV and dQ are independent once D is known, and both are short of workgroups near the ends of
-// the causal triangle (heavy key blocks come first in one, heavy query blocks last in the other):
-// with a second stream the dQ kernel runs beside the dK/dV kernel and fills the compute units
-// the other leaves idle.  `fork` / `join` are events owned by the caller of this function.
+// dK/dV and dQ are independent once D is known, and the dK/dV kernel is short of workgroups near
+// the end of the causal triangle (heavy key blocks come first): with a second stream the dQ
+// kernel runs beside it and fills the compute units it leaves idle.  `fork` / `join` are events
+// owned by the caller of this function.
 hipError_t bwd(const AttnArgs& a, hipStream_t s, hipStream_t s_dq, hipEvent_t fork, hipEvent_t join) {
   if (!attn_shape_ok(a)) return hipErrorInvalidValue;
   static bool configured = false;
   if (!configured) {
     hipError_t e = set_smem(attn_bwd_dkv_kernel<false>, KV_SMEM);
     if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel<true>, KV_SMEM);
-    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<1, false>, 4 * Q_BKV * ROWB);
-    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<2, false>, 8 * Q_BKV * ROWB);
-    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<1, true>, 4 * Q_BKV * ROWB);
-    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<2, true>, 8 * Q_BKV * ROWB);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<4, 1, 64, false>, SMEM_MANY);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<2, 4, 32, false>, SMEM_FEW);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<4, 1, 64, true>, SMEM_MANY);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<2, 4, 32, true>, SMEM_FEW);
     if (e != hipSuccess) return e;
     configured = true;
   }
@@ -747,8 +786,8 @@ hipError_t bwd(const AttnArgs& a, hipStream_t s, hipStream_t s_dq, hipEvent_t fo
   const KeepArgs keep_rows{a.rowbits, a.wpr, a.keep_scale}, keep_cols{a.colbits, a.wpr, a.keep_scale};
   const unsigned qkv_bytes = (unsigned)((size_t)a.B * a.S * 3 * a.nl * DH * 2);
   const unsigned dctx_bytes = qkv_bytes / 3;
-  const long npair = (long)a.B * a.S * a.nl;
-  hipLaunchKernelGGL(attn_dsum_kernel, dim3(cdiv(npair * CPR, 256)), dim3(256), 0, s, (const bf16*)a.ctx,
+  const long npairs = (long)a.B * a.S * a.nl;
+  hipLaunchKernelGGL(attn_dsum_kernel, dim3(cdiv(npairs * CPR, 256)), dim3(256), 0, s, (const bf16*)a.ctx,
                      (const bf16*)a.dctx, a.dsum, a.B, a.S, a.nl);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -765,16 +804,17 @@ hipError_t bwd(const AttnArgs& a, hipStream_t s, hipStream_t s_dq, hipEvent_t fo
   if (drop) go_dkv(attn_bwd_dkv_kernel<true>);
   else go_dkv(attn_bwd_dkv_kernel<false>);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  auto go_dq = [&](auto kernel, int threads, int smem) {
-    hipLaunchKernelGGL(kernel, dim3(cdiv(a.S, Q_BQ), a.nl, a.B), dim3(threads), smem, s_dq, (const bf16*)a.qkv,
-                       (const bf16*)a.dctx, a.lse, a.dsum, (bf16*)a.dqkv, a.S, a.nl, qkv_bytes, keep_rows);
+  const int npair = a.nl * a.B;
+  auto go_dq = [&](auto kernel, int bq, int threads, int smem) {
+    hipLaunchKernelGGL(kernel, dim3(cdiv(a.S, bq) * npair), dim3(threads), smem, s_dq, (const bf16*)a.qkv,
+                       (const bf16*)a.dctx, a.lse, a.dsum, (bf16*)a.dqkv, a.S, a.nl, npair, qkv_bytes, keep_rows);
   };
-  if (split_keys(a)) {
-    if (drop) go_dq(attn_bwd_dq_kernel<2, true>, 512, 8 * Q_BKV * ROWB);
-    else go_dq(attn_bwd_dq_kernel<2, false>, 512, 8 * Q_BKV * ROWB);
+  if (few_pairs(a)) {
+    if (drop) go_dq(attn_bwd_dq_kernel<2, 4, 32, true>, 64, 512, SMEM_FEW);
+    else go_dq(attn_bwd_dq_kernel<2, 4, 32, false>, 64, 512, SMEM_FEW);
   } else {
-    if (drop) go_dq(attn_bwd_dq_kernel<1, true>, 256, 4 * Q_BKV * ROWB);
-    else go_dq(attn_bwd_dq_kernel<1, false>, 256, 4 * Q_BKV * ROWB);
+    if (drop) go_dq(attn_bwd_dq_kernel<4, 1, 64, true>, 128, 256, SMEM_MANY);
+    else go_dq(attn_bwd_dq_kernel<4, 1, 64, false>, 128, 256, SMEM_MANY);
   }
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (two) {

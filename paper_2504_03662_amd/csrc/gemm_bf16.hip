@@ -299,6 +299,13 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
 #pragma unroll
     for (int e = 0; e < 4; e++) bv[e] = (float)b4[e];
   }
+  // EPI_DGELU may also leave partial column sums of what it stores (stage 1 of the bias gradient of
+  // the product that made z): a wavefront's rows split into blocks of 64 (two 32-row passes), each
+  // lane adds its rows of a block, lanes that share columns combine by shuffles, and the block's
+  // sums go to colpart[(m0 + wave row) / 64 + block][column].  Every (block, column) has exactly
+  // one writer.
+  static_assert(WM % 64 == 0, "column-sum blocks of 64 rows");
+  float cs[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int mi = 0; mi < TM; mi++) {
 #pragma unroll
@@ -353,7 +360,23 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
 #pragma unroll
         for (int e = 0; e < 4; e++) o[e] = (bf16)x[e];
         *reinterpret_cast<bf16x4*>(static_cast<bf16*>(g.C) + idx) = o;
+        if (EPI == EPI_DGELU) {
+#pragma unroll
+          for (int e = 0; e < 4; e++) cs[e] += (float)o[e];
+        }
       }
+    }
+    if (EPI == EPI_DGELU && (mi & 1) && g.colpart) {
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+#pragma unroll
+        for (int o = LPR; o < 64; o <<= 1) cs[e] += __shfl_xor(cs[e], o, 64);
+      }
+      const int row0 = m0 + wm * WM + (mi - 1) * 32;         // first row of this block of 64
+      if (lane < LPR && row0 < g.M && ecol < g.N)
+        *reinterpret_cast<f32x4*>(g.colpart + (size_t)(row0 >> 6) * g.N + ecol) = f32x4{cs[0], cs[1], cs[2], cs[3]};
+#pragma unroll
+      for (int e = 0; e < 4; e++) cs[e] = 0.f;
     }
   }
 }

@@ -19,6 +19,12 @@ bool device_is_gfx950() {
 }
 }  // namespace gx
 
+// Backward workspace of gx_layer_bwd_static: one array per GPU, in the library's device image,
+// held until the process ends.  The compiler exports a file-local device variable that host code
+// refers to, which is what the runtime's lookup by name needs; marking it `used` would keep the
+// symbol local to the code object and the lookup would fail.
+static __device__ __align__(256) unsigned char scratch[GX_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using namespace gx;
@@ -95,7 +101,11 @@ Saved plan_saved(const gx_layer_cfg& c, Arena& a) {
 // Backward scratch.
 struct Work {
   void *dz, *dy2, *dy1, *dh1, *dctx, *dqkv;
-  float *dsum, *part;   // part: partial sums of the column reductions (used on the side stream, in order)
+  float* dsum;
+  // stage-1 partial sums of the column reductions, one buffer per producer (all are finished by one
+  // launch at the end of the pass): the two LayerNorm-backward kernels (up to 4 sums each), the FC1
+  // bias gradient (blocks of 64 rows of dz), and the plain column sums of dqkv, dp_mlp and dp_attn
+  float *part_ln2, *part_ln1, *part_fc1, *part_qkv, *part_fc2, *part_o;
   void* recomputed;     // a Saved block when GX_RECOMPUTE is set
 };
 
@@ -114,13 +124,18 @@ Work plan_work(const gx_layer_cfg& c, Arena& a) {
     w.dqkv = a.take(d.T * 3 * d.Hl * d.e);
     w.dsum = static_cast<float*>(a.take(d.B * d.nl * d.S * 4));
   }
-  long widest = d.H;
-  if (3 * d.Hl > widest) widest = 3 * d.Hl;
-  if (d.Fl > widest) widest = d.Fl;
-  size_t part = (size_t)colsum_blocks((int)d.T) * widest;
-  const size_t lnpart = 2ul * ln_bwd_blocks((int)d.T) * d.H;
-  if (lnpart > part) part = lnpart;
-  w.part = static_cast<float*>(a.take(part * 4));
+  const size_t lnb = (size_t)ln_bwd_blocks(d.bf, (int)d.T, (int)d.H), csb = (size_t)colsum_blocks((int)d.T);
+  const size_t fcb = (size_t)cdiv(d.T, 64) > csb ? (size_t)cdiv(d.T, 64) : csb;
+  if (c.flags & GX_PHASE_MLP) {
+    w.part_ln2 = static_cast<float*>(a.take(4 * lnb * d.H * 4));
+    w.part_fc1 = static_cast<float*>(a.take(fcb * d.Fl * 4));
+    w.part_fc2 = static_cast<float*>(a.take(csb * d.H * 4));
+  }
+  if (c.flags & GX_PHASE_ATTN) {
+    w.part_ln1 = static_cast<float*>(a.take(2 * lnb * d.H * 4));
+    w.part_qkv = static_cast<float*>(a.take(csb * 3 * d.Hl * 4));
+    w.part_o = static_cast<float*>(a.take(csb * d.H * 4));
+  }
   if (c.flags & GX_RECOMPUTE) {
     Arena probe(nullptr);
     plan_saved(c, probe);
@@ -248,15 +263,20 @@ hipError_t gemm(const Dims& d, Layout lay, Epilogue epi, const GemmArgs& g, hipS
   return d.bf ? gemm_bf16(lay, epi, g, s) : gemm_f32(lay, epi, g, s);
 }
 
-hipError_t colsum_p(bool bf, const void* a, int rows, int cols, float* part, float* out, bool acc, hipStream_t s) {
-  ProfScope ps(GX_KC_COLSUM, s);
-  return colsum(bf, a, rows, cols, cols, part, out, acc, s);
-}
+// stage 1 of a column sum on stream s; its finish is queued in `fin`
+struct Finisher {
+  FinishSeg seg[FINISH_MAX];
+  int n = 0;
+  void add(const float* part, int nblk, long cols, float* out, bool acc) {
+    if (n < FINISH_MAX) seg[n++] = FinishSeg{part, out, nblk, (int)cols, acc ? 1 : 0, 0};
+  }
+};
 
-hipError_t ln_params_p(bool bf, const void* dy, const void* x, const float* mean, const float* rstd, float* part,
-                       int rows, int cols, float* dg, float* db, bool acc, hipStream_t s) {
-  ProfScope ps(GX_KC_LN_BWD, s);
-  return ln_bwd_params(bf, dy, x, mean, rstd, part, rows, cols, dg, db, acc, s);
+hipError_t colsum_p(bool bf, const void* a, long rows, long cols, float* part, float* out, bool acc, Finisher& fin,
+                    hipStream_t s) {
+  ProfScope ps(GX_KC_COLSUM, s);
+  fin.add(part, colsum_blocks((int)rows), cols, out, acc);
+  return colsum_partial(bf, a, (int)rows, (int)cols, (int)cols, part, s);
 }
 
 // The backward pass has work whose inputs are ready long before anything consumes its results:
@@ -295,7 +315,7 @@ struct Fork {
   hipStream_t main, side;
   int n = 0;
   bool used = false;
-  explicit Fork(hipStream_t m) : main(m), side(side_ready() ? g_side.s : m) {}
+  Fork(hipStream_t m, bool allow_side) : main(m), side(allow_side && side_ready() ? g_side.s : m) {}
   hipError_t err = hipSuccess;     // first failure of an event call; reported by join()
   // stream for a task that depends on what `main` holds now
   hipStream_t branch() {
@@ -426,12 +446,8 @@ gx_status run_fwd(const gx_layer_cfg& c, const gx_params& p, const void* x, void
   return GX_OK;
 }
 
-gx_status bias_grad(const Dims& d, const gx_layer_cfg& c, bool enabled, const void* src, long cols, float* part,
-                    float* out, hipStream_t st) {
-  const bool acc = c.flags & GX_ACCUM_WGRAD;
-  if (enabled) {
-    GX_TRY(colsum_p(d.bf, src, (int)d.T, (int)cols, part, out, acc, st));
-  } else if (!acc) {
+gx_status zero_grad(bool acc, float* out, long cols, hipStream_t st) {
+  if (!acc) {
     hipLaunchKernelGGL(fill_zero_kernel, dim3(cdiv(cols, 256)), dim3(256), 0, st, out, (int)cols);
     GX_TRY(hipGetLastError());
   }
@@ -439,7 +455,8 @@ gx_status bias_grad(const Dims& d, const gx_layer_cfg& c, bool enabled, const vo
 }
 
 gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, const void* dy, void* dx,
-                  const gx_grads& gr, const Saved& sv, const Work& w, const DropBufs& db, hipStream_t st) {
+                  const gx_grads& gr, const Saved& sv, const Work& w, const DropBufs& db, hipStream_t st,
+                  bool allow_side) {
   const Dims d = dims_of(c);
   const Drop dr = drop_of(c);
   const bool attn = c.flags & GX_PHASE_ATTN, mlp = c.flags & GX_PHASE_MLP;
@@ -453,8 +470,15 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     g.resid = g.C;
     return gemm(d, LAY_TN, EPI_RESID, g, s);
   };
-  Fork fk(st);
+  Fork fk(st, allow_side);
+  Finisher fin;
   gx_status s;
+  // With both phases and no output dropout, LayerNorm 2's backward kernel reads dy as its residual
+  // gradient and writes dh1: the gradients of the two row-parallel biases are the column sums of
+  // exactly these tensors, and that kernel forms them on the way (4 sums).  Otherwise they come
+  // from plain column-sum passes.
+  const bool ln2_sums_biases = attn && mlp && !dr.hidden;
+  const int lnb = ln_bwd_blocks(d.bf, (int)d.T, (int)d.H);
   const void* dcur = dy;           // gradient arriving at the attention half's output
   if (mlp) {
     const void* h1 = attn ? sv.h1 : x;
@@ -466,29 +490,43 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     }
     // row-parallel FC2: bias and weight gradients need only dp and saved activations: side
     hipStream_t sd = fk.branch();
-    if ((s = bias_grad(d, c, c.flags & GX_ROW_BIAS_MLP, dp, d.H, w.part, gr.b_fc2, sd)) != GX_OK) return s;
+    if (!(c.flags & GX_ROW_BIAS_MLP)) {
+      if ((s = zero_grad(acc, gr.b_fc2, d.H, sd)) != GX_OK) return s;
+    } else if (!ln2_sums_biases) {
+      GX_TRY(colsum_p(d.bf, dp, d.T, d.H, w.part_fc2, gr.b_fc2, acc, fin, sd));
+    }
     GemmArgs w2 = gargs(sv.act, dp, gr.w_fc2, d.Fl, d.H, d.T, d.Fl, d.H, d.H);
     GX_TRY(wgrad(w2, sd));
-    // input gradient fused with GELU' on the caller's stream
+    // input gradient fused with GELU' on the caller's stream; the bf16 kernel also leaves the
+    // partial column sums of dz (FC1 bias gradient)
     GemmArgs dz = gargs(dp, p.w_fc2, w.dz, d.T, d.Fl, d.H, d.H, d.H, d.Fl);
     dz.z = sv.gelu_grad;
+    if (d.bf) {
+      dz.colpart = w.part_fc1;
+      fin.add(w.part_fc1, cdiv(d.T, 64), d.Fl, gr.b_fc1, acc);
+    }
     GX_TRY(gemm(d, LAY_NT, EPI_DGELU, dz, st));
-    // column-parallel FC1: bias and weight gradients on the side once dz exists
+    // column-parallel FC1: weight gradient on the side once dz exists
     sd = fk.branch();
-    GX_TRY(colsum_p(d.bf, w.dz, (int)d.T, (int)d.Fl, w.part, gr.b_fc1, acc, sd));
+    if (!d.bf) GX_TRY(colsum_p(d.bf, w.dz, d.T, d.Fl, w.part_fc1, gr.b_fc1, acc, fin, sd));
     GemmArgs w1 = gargs(sv.y2, w.dz, gr.w_fc1, d.H, d.Fl, d.T, d.H, d.Fl, d.Fl);
     GX_TRY(wgrad(w1, sd));
     GemmArgs dy2 = gargs(w.dz, p.w_fc1, w.dy2, d.T, d.H, d.Fl, d.Fl, d.Fl, d.H);
     GX_TRY(gemm(d, LAY_NT, EPI_STORE, dy2, st));
-    // LayerNorm 2: parameter gradients on the side; input gradient (plus dy through the residual
-    // branch when both phases run) on the caller's stream
-    GX_TRY(ln_params_p(d.bf, w.dy2, h1, sv.mean2, sv.rstd2, w.part, (int)d.T, (int)d.H, gr.ln2_g, gr.ln2_b, acc,
-                       fk.branch()));
+    // LayerNorm 2: input gradient (plus dy through the residual branch when both phases run) and
+    // the partial sums of its parameter gradients in one pass
     void* out = attn ? w.dh1 : dx;
     {
       ProfScope ps(GX_KC_LN_BWD, st);
-      GX_TRY(ln_bwd_dx(d.bf, w.dy2, h1, p.ln2_g, sv.mean2, sv.rstd2, attn ? dy : nullptr, out, (int)d.T, (int)d.H,
-                       st));
+      GX_TRY(ln_bwd(d.bf, w.dy2, h1, p.ln2_g, sv.mean2, sv.rstd2, attn ? dy : nullptr, out, (int)d.T, (int)d.H,
+                    ln2_sums_biases ? 4 : 2, w.part_ln2, st));
+    }
+    const size_t stride = (size_t)lnb * d.H;
+    fin.add(w.part_ln2, lnb, d.H, gr.ln2_g, acc);
+    fin.add(w.part_ln2 + stride, lnb, d.H, gr.ln2_b, acc);
+    if (ln2_sums_biases) {
+      if (c.flags & GX_ROW_BIAS_MLP) fin.add(w.part_ln2 + 2 * stride, lnb, d.H, gr.b_fc2, acc);
+      if (c.flags & GX_ROW_BIAS_ATTN) fin.add(w.part_ln2 + 3 * stride, lnb, d.H, gr.b_o, acc);
     }
     dcur = w.dh1;
   }
@@ -501,7 +539,11 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
       dp = db.dh1m;
     }
     hipStream_t sd = fk.branch();
-    if ((s = bias_grad(d, c, c.flags & GX_ROW_BIAS_ATTN, dp, d.H, w.part, gr.b_o, sd)) != GX_OK) return s;
+    if (!(c.flags & GX_ROW_BIAS_ATTN)) {
+      if ((s = zero_grad(acc, gr.b_o, d.H, sd)) != GX_OK) return s;
+    } else if (!ln2_sums_biases) {
+      GX_TRY(colsum_p(d.bf, dp, d.T, d.H, w.part_o, gr.b_o, acc, fin, sd));
+    }
     GemmArgs wo = gargs(sv.ctx, dp, gr.w_o, d.Hl, d.H, d.T, d.Hl, d.H, d.H);
     GX_TRY(wgrad(wo, sd));
     GemmArgs dc = gargs(dp, p.w_o, w.dctx, d.T, d.Hl, d.H, d.H, d.H, d.Hl);
@@ -516,20 +558,25 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     if (d.bf && fk.side != st) fk.used = true; }
     // column-parallel QKV
     hipStream_t sq = fk.branch();
-    GX_TRY(colsum_p(d.bf, w.dqkv, (int)d.T, (int)(3 * d.Hl), w.part, gr.b_qkv, acc, sq));
+    GX_TRY(colsum_p(d.bf, w.dqkv, d.T, 3 * d.Hl, w.part_qkv, gr.b_qkv, acc, fin, sq));
     GemmArgs wq = gargs(sv.y1, w.dqkv, gr.w_qkv, d.H, 3 * d.Hl, d.T, d.H, 3 * d.Hl, 3 * d.Hl);
     GX_TRY(wgrad(wq, sq));
     GemmArgs dy1 = gargs(w.dqkv, p.w_qkv, w.dy1, d.T, d.H, 3 * d.Hl, 3 * d.Hl, 3 * d.Hl, d.H);
     GX_TRY(gemm(d, LAY_NT, EPI_STORE, dy1, st));
-    GX_TRY(ln_params_p(d.bf, w.dy1, x, sv.mean1, sv.rstd1, w.part, (int)d.T, (int)d.H, gr.ln1_g, gr.ln1_b, acc,
-                       fk.branch()));
     {
       ProfScope ps(GX_KC_LN_BWD, st);
-      GX_TRY(ln_bwd_dx(d.bf, w.dy1, x, p.ln1_g, sv.mean1, sv.rstd1, mlp ? dcur : nullptr, dx, (int)d.T, (int)d.H,
-                       st));
+      GX_TRY(ln_bwd(d.bf, w.dy1, x, p.ln1_g, sv.mean1, sv.rstd1, mlp ? dcur : nullptr, dx, (int)d.T, (int)d.H, 2,
+                    w.part_ln1, st));
     }
+    fin.add(w.part_ln1, lnb, d.H, gr.ln1_g, acc);
+    fin.add(w.part_ln1 + (size_t)lnb * d.H, lnb, d.H, gr.ln1_b, acc);
   }
   GX_TRY(fk.join());
+  // every partial sum is complete: one launch finishes all column reductions of the pass
+  {
+    ProfScope ps(GX_KC_COLSUM, st);
+    GX_TRY(colsum_finish(fin.seg, fin.n, st));
+  }
   return GX_OK;
 }
 
@@ -563,6 +610,47 @@ gx_status check_grads(const gx_layer_cfg& c, const gx_grads& g) {
       if (misaligned(q)) return GX_ERR_ALIGN;
     }
   return GX_OK;
+}
+
+gx_status layer_bwd(const gx_layer_cfg* cfg, const gx_params* params, const void* x, const void* dy, void* dx,
+                    const gx_grads* grads, const void* saved, void* workspace, void* hip_stream, bool allow_side) {
+  gx_status s = validate(cfg);
+  if (s != GX_OK) return s;
+  const bool recompute = cfg->flags & GX_RECOMPUTE;
+  if (!params || !x || !dy || !dx || !grads || !workspace || (!recompute && !saved)) return GX_ERR_NULL;
+  if (misaligned(x) || misaligned(dy) || misaligned(dx) || misaligned(workspace) || (!recompute && misaligned(saved)))
+    return GX_ERR_ALIGN;
+  if ((s = check_params(*cfg, *params)) != GX_OK) return s;
+  if ((s = check_grads(*cfg, *grads)) != GX_OK) return s;
+  if ((s = check_arch()) != GX_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  Arena wa(workspace);
+  const Work w = plan_work(*cfg, wa);
+  const DropBufs db = plan_drop(*cfg, wa, true);
+  Arena sa(recompute ? w.recomputed : const_cast<void*>(saved));
+  const Saved sv = plan_saved(*cfg, sa);
+  if ((s = make_attn_mask(*cfg, db, st)) != GX_OK) return s;
+  if (recompute) {
+    s = run_fwd(*cfg, *params, x, nullptr, nullptr, nullptr, sv, db, true, st);
+    if (s != GX_OK) return s;
+  }
+  return run_bwd(*cfg, *params, x, dy, dx, *grads, sv, w, db, st, allow_side);
+}
+
+// The device address of `scratch` (the name itself is only a handle for the runtime's symbol
+// lookup in host code, never an address): asked for once per device, with that device current.
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES];
+
+void* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
 }
 
 }  // namespace
@@ -616,27 +704,19 @@ gx_status gx_layer_fwd(const gx_layer_cfg* cfg, const gx_params* params, const v
 
 gx_status gx_layer_bwd(const gx_layer_cfg* cfg, const gx_params* params, const void* x, const void* dy, void* dx,
                        const gx_grads* grads, const void* saved, void* workspace, void* hip_stream) {
-  gx_status s = validate(cfg);
+  return layer_bwd(cfg, params, x, dy, dx, grads, saved, workspace, hip_stream, true);
+}
+
+gx_status gx_layer_bwd_static(const gx_layer_cfg* cfg, const gx_params* params, const void* x, const void* dy,
+                              void* dx, const gx_grads* grads, const void* saved, void* hip_stream) {
+  const gx_status s = validate(cfg);
   if (s != GX_OK) return s;
-  const bool recompute = cfg->flags & GX_RECOMPUTE;
-  if (!params || !x || !dy || !dx || !grads || !workspace || (!recompute && !saved)) return GX_ERR_NULL;
-  if (misaligned(x) || misaligned(dy) || misaligned(dx) || misaligned(workspace) || (!recompute && misaligned(saved)))
-    return GX_ERR_ALIGN;
-  if ((s = check_params(*cfg, *params)) != GX_OK) return s;
-  if ((s = check_grads(*cfg, *grads)) != GX_OK) return s;
-  if ((s = check_arch()) != GX_OK) return s;
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  Arena wa(workspace);
-  const Work w = plan_work(*cfg, wa);
-  const DropBufs db = plan_drop(*cfg, wa, true);
-  Arena sa(recompute ? w.recomputed : const_cast<void*>(saved));
-  const Saved sv = plan_saved(*cfg, sa);
-  if ((s = make_attn_mask(*cfg, db, st)) != GX_OK) return s;
-  if (recompute) {
-    s = run_fwd(*cfg, *params, x, nullptr, nullptr, nullptr, sv, db, true, st);
-    if (s != GX_OK) return s;
-  }
-  return run_bwd(*cfg, *params, x, dy, dx, *grads, sv, w, db, st);
+  if (gx_layer_workspace_bytes(cfg, 1) > GX_STATIC_SCRATCH_BYTES) return GX_ERR_SHAPE;
+  void* ws = static_scratch();
+  if (!ws) return GX_ERR_LAUNCH;
+  // everything on the caller's stream: the side streams and their events are created on first use,
+  // which a caller that may not allocate cannot be asked to tolerate
+  return layer_bwd(cfg, params, x, dy, dx, grads, saved, ws, hip_stream, false);
 }
 
 const char* gx_status_str(gx_status s) {

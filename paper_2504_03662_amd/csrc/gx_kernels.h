@@ -34,6 +34,8 @@ struct GemmArgs {
   void* aux;           // [M, ldc], storage type
   const void* z;       // [M, ldc], storage type: EPI_DGELU's multiplier
   int gelu_tanh;       // EPI_GELU: tanh form of GELU instead of the erf form
+  float* colpart;      // bf16 EPI_DGELU only, optional: partial column sums of the stored C over blocks of 64
+                       // rows, [ceil(M / 64)][N] fp32 (stage 1 of the bias gradient; finished by colsum_finish)
   // set by the bf16 launcher only (callers leave them 0): a launch that covers the super-tiles
   // (2 x 2 kernel tiles) numbered tile_first onwards in the tile walk, four workgroups each
   int tail, tile_first;
@@ -85,19 +87,28 @@ hipError_t dropout_rows(bool bf16, const void* in, const void* resid, void* out,
 // LayerNorm forward: y = g * (x - mean) * rstd + b; writes mean/rstd per row.
 hipError_t ln_fwd(bool bf16, const void* x, const void* g, const void* b, void* y, float* mean, float* rstd,
                   int rows, int cols, float eps, hipStream_t s);
-// LayerNorm backward, input gradient: dx = (resid ? resid : 0) + LNbwd(dy).
-hipError_t ln_bwd_dx(bool bf16, const void* dy, const void* x, const void* g, const float* mean, const float* rstd,
-                     const void* resid, void* dx, int rows, int cols, hipStream_t s);
-// LayerNorm backward, parameter gradients: dg (=|+=) sum_rows dy * xhat, db (=|+=) sum_rows dy, through
-// per-block partial sums in part[2][ln_bwd_blocks(rows)][cols] and a fixed-order finish.
-hipError_t ln_bwd_params(bool bf16, const void* dy, const void* x, const float* mean, const float* rstd, float* part,
-                         int rows, int cols, float* dg, float* db, bool accumulate, hipStream_t s);
-int ln_bwd_blocks(int rows);
-// Finish a two-stage column reduction: out[c] (=|+=) sum_b part[b][c].
-hipError_t colsum_finish(const float* part, int nblk, int cols, float* out, bool accumulate, hipStream_t s);
-// Column sums of a [rows, cols] matrix into fp32 out[cols] (two-stage, fixed order).
-hipError_t colsum(bool bf16, const void* a, int rows, int cols, int ld, float* part, float* out, bool accumulate,
-                  hipStream_t s);
+// Column reductions are two-stage and fixed-order: a producer leaves per-block partial rows
+// part[nblk][cols] (fp32), and ONE launch at the end of a pass finishes all of them.
+struct FinishSeg {
+  const float* part;   // [nblk][cols]
+  float* out;          // [cols], written or, with accumulate, added to
+  int nblk, cols, accumulate;
+  int wg0;             // set by colsum_finish
+};
+constexpr int FINISH_MAX = 10;
+struct FinishArgs {
+  FinishSeg seg[FINISH_MAX];
+  int nseg;
+};
+hipError_t colsum_finish(const FinishSeg* segs, int nseg, hipStream_t s);
+// LayerNorm backward in one pass: dx = (resid ? resid : 0) + LNbwd(dy), and partial column sums
+// part[a][ln_bwd_blocks(..)][cols]: a = 0 sum dy * xhat (gain gradient), 1 sum dy (bias gradient) and,
+// with nsum = 4 (resid required), 2 sum resid, 3 sum dx.
+hipError_t ln_bwd(bool bf16, const void* dy, const void* x, const void* g, const float* mean, const float* rstd,
+                  const void* resid, void* dx, int rows, int cols, int nsum, float* part, hipStream_t s);
+int ln_bwd_blocks(bool bf16, int rows, int cols);
+// Stage 1 of the column sums of a [rows, cols] matrix: part[colsum_blocks(rows)][cols].
+hipError_t colsum_partial(bool bf16, const void* a, int rows, int cols, int ld, float* part, hipStream_t s);
 int colsum_blocks(int rows);
 
 }  // namespace gx

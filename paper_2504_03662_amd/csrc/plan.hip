@@ -164,3 +164,49 @@ extern "C" gx_status gx_plan_search(const gx_plan_problem* p, int32_t* choice, g
     return GX_ERR_SHAPE;
   }
 }
+
+// Per-GPU cost model of one layer under one strategy (host code): what the cost table holds beside
+// the measured compute times.  Sizes are exact integers; times follow the ring model stated in
+// the header.
+extern "C" gx_status gx_strategy_cost(const gx_strategy_query* q, gx_strategy_costs* out) {
+  if (!q || !out) return GX_ERR_NULL;
+  if (q->dtype != GX_F32 && q->dtype != GX_BF16) return GX_ERR_DTYPE;
+  if (q->hidden <= 0 || q->heads <= 0 || q->ffn <= 0 || q->seq <= 0 || q->gpus <= 0 || q->global_batch <= 0 ||
+      q->tp_attn <= 0 || q->tp_ffn <= 0 || !(q->link_gbps > 0.0) || !std::isfinite(q->link_gbps))
+    return GX_ERR_SHAPE;
+  if (q->hidden % q->heads || q->heads % q->tp_attn || q->ffn % q->tp_ffn || q->gpus % q->tp_attn ||
+      q->gpus % q->tp_ffn)
+    return GX_ERR_DIVIS;
+  const int64_t H = q->hidden, F = q->ffn, S = q->seq, N = q->gpus, GB = q->global_batch;
+  const int64_t a = q->tp_attn, f = q->tp_ffn;
+  // a tensor-parallel group of degree d serves GB * d / N samples per step; it must be a whole number
+  if ((GB * a) % N || (GB * f) % N) return GX_ERR_DIVIS;
+  const int64_t mba = GB * a / N, mbf = GB * f / N;
+  const int64_t e = q->dtype == GX_BF16 ? 2 : 4;
+  const int64_t Hl = H / a, Fl = F / f, nl = q->heads / a, dh = H / q->heads;
+  // one rank's parameters: LayerNorm gain and bias, the column-parallel matrix and bias, the
+  // row-parallel matrix, and the row-parallel bias (replicated)
+  const int64_t ea = 2 * H + H * 3 * Hl + 3 * Hl + Hl * H + H;
+  const int64_t ef = 2 * H + H * Fl + Fl + Fl * H + H;
+  out->micro_batch_attn = mba;
+  out->micro_batch_ffn = mbf;
+  out->attn_elems = ea;
+  out->ffn_elems = ef;
+  out->state_bytes = (double)(ea + ef) * (double)(e + 16);
+  const double bw = q->link_gbps * 1e9;                 // bytes per second per link
+  auto ring_ms = [&](double bytes, int64_t p) {         // all-reduce of `bytes` over p ranks
+    return p <= 1 ? 0.0 : 2.0 * (double)(p - 1) / (double)p * bytes / bw * 1e3;
+  };
+  const double act_a = (double)(mba * S * H * e), act_f = (double)(mbf * S * H * e);
+  out->tp_comm_ms = 2.0 * ring_ms(act_a, a) + 2.0 * ring_ms(act_f, f);
+  out->dp_comm_ms = ring_ms((double)ea * 4.0, N / a) + ring_ms((double)ef * 4.0, N / f);
+  out->switch_ms = 2.0 * ((double)(GB * S * H * e) / (double)N) / bw * 1e3;
+  const double Ta = (double)(mba * S), Tf = (double)(mbf * S);
+  const double fwd_a = 2.0 * Ta * (double)H * 3.0 * (double)Hl + 2.0 * Ta * (double)Hl * (double)H +
+                       4.0 * (double)mba * (double)nl * (double)dh * (double)S * (double)(S + 1) / 2.0;
+  const double fwd_f = 4.0 * Tf * (double)H * (double)Fl;
+  out->flops_attn = 3.0 * fwd_a;
+  out->flops_ffn = 3.0 * fwd_f;
+  return GX_OK;
+}
+

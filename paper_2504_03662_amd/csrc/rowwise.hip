@@ -75,103 +75,142 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(const T* __restrict__ x, co
   }
 }
 
-// LayerNorm backward, input gradient: one wavefront per row, the row of dy and x-hat held in
-// registers; dx = rstd * (dy g - mean(dy g) - xhat mean(dy g xhat)) (+ residual gradient).
-template <typename T, int MAXC>
-__global__ void __launch_bounds__(256) ln_bwd_dx_kernel(const T* __restrict__ dy, const T* __restrict__ x,
-                                                        const T* __restrict__ g, const float* __restrict__ mean,
-                                                        const float* __restrict__ rstd, const T* __restrict__ resid,
-                                                        T* __restrict__ dx, int rows, int cols) {
+// LayerNorm backward in one pass over dy and x: input gradient
+//   dx = rstd * (dy g - mean(dy g) - xhat mean(dy g xhat)) (+ residual gradient)
+// and, from the same registers, the per-workgroup partial column sums that the parameter and bias
+// gradients need: sum dy * xhat (gain), sum dy (bias) and, with NSUM = 4, sum resid and sum dx (the
+// bias gradients of the row-parallel products on either side of the LayerNorm, whose upstream
+// gradients are exactly these two tensors).
+// A workgroup of 8 wavefronts; a row is shared by G of them (CPT chunks of 16 B per lane), the
+// 8 / G row groups each take R rows per step, all R rows' loads in flight together.  Row sums
+// cross the G wavefronts through LDS (one barrier per step, double-buffered by step parity).
+// Every row group keeps its own column accumulators and writes its own partial row:
+// part[a][blockIdx.x * (8 / G) + group][cols] for a < NSUM.  Fixed order throughout.
+template <typename T, int G, int CPT, int NSUM>
+__global__ void __launch_bounds__(512) ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                     const T* __restrict__ g, const float* __restrict__ mean,
+                                                     const float* __restrict__ rstd, const T* __restrict__ resid,
+                                                     T* __restrict__ dx, int rows, int cols, float* __restrict__ part) {
   constexpr int V = Vec<T>::N;
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= rows) return;
+  constexpr int NG = 8 / G, R = 8 / CPT;
+  typedef typename Vec<T>::type Raw;
+  __shared__ float red[2][NG][R][G][2];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int grp = wave / G, wg = wave % G;
   const int nchunk = cols / V;
-  const size_t off = (size_t)row * cols;
-  const float mu = mean[row], rs = rstd[row];
-  float t[MAXC][V], xh[MAXC][V];
-  typename Vec<T>::type rraw[MAXC];          // residual gradient, fetched with the first wave of loads
-  float s1 = 0.f, s2 = 0.f;
+  const bool has_resid = (NSUM == 4) || resid != nullptr;
+  bool live[CPT];
+  int col[CPT];
+  float gv[CPT][V];
 #pragma unroll
-  for (int i = 0; i < MAXC; i++) {
-    const int c = lane + 64 * i;
-    if (c < nchunk) {
-      float gv[V];
-      load_vec<T>(dy + off + c * V, t[i]);
-      load_vec<T>(x + off + c * V, xh[i]);
-      if (resid) rraw[i] = *reinterpret_cast<const typename Vec<T>::type*>(resid + off + c * V);
-      load_vec<T>(g + c * V, gv);
+  for (int i = 0; i < CPT; i++) {
+    const int c = wg * 64 + lane + 64 * G * i;
+    live[i] = c < nchunk;
+    col[i] = c * V;
 #pragma unroll
-      for (int e = 0; e < V; e++) {
-        xh[i][e] = (xh[i][e] - mu) * rs;
-        t[i][e] *= gv[e];
-        s1 += t[i][e];
-        s2 += t[i][e] * xh[i][e];
+    for (int e = 0; e < V; e++) gv[i][e] = 0.f;
+    if (live[i]) load_vec<T>(g + col[i], gv[i]);
+  }
+  float acc[NSUM][CPT][V];
+#pragma unroll
+  for (int a = 0; a < NSUM; a++)
+#pragma unroll
+    for (int i = 0; i < CPT; i++)
+#pragma unroll
+      for (int e = 0; e < V; e++) acc[a][i][e] = 0.f;
+  const float inv_cols = 1.0f / (float)cols;
+  int par = 0;
+  for (int base = blockIdx.x * NG * R; base < rows; base += gridDim.x * NG * R, par ^= 1) {
+    const int r0 = base + grp * R;
+    Raw dyr[R][CPT], xr[R][CPT], rr[R][CPT];
+    float mu[R], rs[R];
+#pragma unroll
+    for (int j = 0; j < R; j++) {
+      const int row = r0 + j;
+      const bool ok = row < rows;
+      mu[j] = ok ? mean[row] : 0.f;
+      rs[j] = ok ? rstd[row] : 0.f;
+#pragma unroll
+      for (int i = 0; i < CPT; i++) {
+        Raw z;
+#pragma unroll
+        for (int e = 0; e < V; e++) z[e] = from_f32<T>(0.f);
+        dyr[j][i] = z;
+        xr[j][i] = z;
+        rr[j][i] = z;
+        if (ok && live[i]) {
+          const size_t off = (size_t)row * cols + col[i];
+          dyr[j][i] = *reinterpret_cast<const Raw*>(dy + off);
+          xr[j][i] = *reinterpret_cast<const Raw*>(x + off);
+          if (has_resid) rr[j][i] = *reinterpret_cast<const Raw*>(resid + off);
+        }
+      }
+    }
+    // row sums of dy g and of dy g xhat
+#pragma unroll
+    for (int j = 0; j < R; j++) {
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int i = 0; i < CPT; i++)
+#pragma unroll
+        for (int e = 0; e < V; e++) {
+          const float t = to_f32(dyr[j][i][e]) * gv[i][e];
+          s1 += t;
+          s2 += t * ((to_f32(xr[j][i][e]) - mu[j]) * rs[j]);
+        }
+      s1 = wave_sum(s1);
+      s2 = wave_sum(s2);
+      if (lane == 0) {
+        red[par][grp][j][wg][0] = s1;
+        red[par][grp][j][wg][1] = s2;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < R; j++) {
+      const int row = r0 + j;
+      if (row >= rows) continue;
+      float c1 = 0.f, c2 = 0.f;
+#pragma unroll
+      for (int w = 0; w < G; w++) {
+        c1 += red[par][grp][j][w][0];
+        c2 += red[par][grp][j][w][1];
+      }
+      c1 *= inv_cols;
+      c2 *= inv_cols;
+#pragma unroll
+      for (int i = 0; i < CPT; i++) {
+        if (!live[i]) continue;
+        Raw o;
+#pragma unroll
+        for (int e = 0; e < V; e++) {
+          const float d = to_f32(dyr[j][i][e]);
+          const float xh = (to_f32(xr[j][i][e]) - mu[j]) * rs[j];
+          float v = rs[j] * (d * gv[i][e] - c1 - xh * c2);
+          acc[0][i][e] += d * xh;
+          acc[1][i][e] += d;
+          if (has_resid) v += to_f32(rr[j][i][e]);
+          o[e] = from_f32<T>(v);
+          if (NSUM == 4) {
+            acc[2][i][e] += to_f32(rr[j][i][e]);
+            acc[3][i][e] += to_f32(o[e]);          // the value the consumers of dx read
+          }
+        }
+        *reinterpret_cast<Raw*>(dx + (size_t)row * cols + col[i]) = o;
       }
     }
   }
-  const float c1 = wave_sum(s1) / (float)cols, c2 = wave_sum(s2) / (float)cols;
+  const size_t nblk = (size_t)gridDim.x * NG, blk = (size_t)blockIdx.x * NG + grp;
 #pragma unroll
-  for (int i = 0; i < MAXC; i++) {
-    const int c = lane + 64 * i;
-    if (c < nchunk) {
-      float o[V];
+  for (int a = 0; a < NSUM; a++)
 #pragma unroll
-      for (int e = 0; e < V; e++) o[e] = rs * (t[i][e] - c1 - xh[i][e] * c2);
-      if (resid) {
+    for (int i = 0; i < CPT; i++) {
+      if (!live[i]) continue;
+      float* p = part + (a * nblk + blk) * cols + col[i];
 #pragma unroll
-        for (int e = 0; e < V; e++) o[e] += to_f32(rraw[i][e]);
-      }
-      store_vec<T>(dx + off + c * V, o);
+      for (int e = 0; e < V; e += 4)
+        *reinterpret_cast<f32x4*>(p + e) = f32x4{acc[a][i][e], acc[a][i][e + 1], acc[a][i][e + 2], acc[a][i][e + 3]};
     }
-  }
-}
-
-// LayerNorm backward, parameter gradients, stage 1: workgroup (bx, by) adds dy * xhat and dy over
-// rows [by*rpb, (by+1)*rpb) for 64 column chunks of 16 B.  Its 4 wavefronts take every 4th row and
-// combine through LDS in wavefront order; partials go to part[0][by][col], part[1][by][col].
-template <typename T>
-__global__ void __launch_bounds__(256) ln_bwd_param_kernel(const T* __restrict__ dy, const T* __restrict__ x,
-                                                           const float* __restrict__ mean,
-                                                           const float* __restrict__ rstd, int rows, int cols,
-                                                           int rows_per_block, float* __restrict__ part) {
-  constexpr int V = Vec<T>::N;
-  __shared__ float red[2][3][64][V + 1];
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + lane;
-  const bool live = c * V < cols;
-  const int r0 = blockIdx.y * rows_per_block, r1 = min(rows, r0 + rows_per_block);
-  float dg[V], db[V];
-#pragma unroll
-  for (int e = 0; e < V; e++) { dg[e] = 0.f; db[e] = 0.f; }
-  if (live) {
-#pragma unroll 4
-    for (int r = r0 + w; r < r1; r += 4) {
-      float dv[V], xv[V];
-      load_vec<T>(dy + (size_t)r * cols + c * V, dv);
-      load_vec<T>(x + (size_t)r * cols + c * V, xv);
-      const float mu = mean[r], rs = rstd[r];
-#pragma unroll
-      for (int e = 0; e < V; e++) {
-        dg[e] += dv[e] * ((xv[e] - mu) * rs);
-        db[e] += dv[e];
-      }
-    }
-  }
-  if (w) {
-#pragma unroll
-    for (int e = 0; e < V; e++) { red[0][w - 1][lane][e] = dg[e]; red[1][w - 1][lane][e] = db[e]; }
-  }
-  __syncthreads();
-  if (w == 0 && live) {
-    float* pg = part + (size_t)blockIdx.y * cols + c * V;
-    float* pb = part + ((size_t)gridDim.y + blockIdx.y) * cols + c * V;
-#pragma unroll
-    for (int e = 0; e < V; e++) {
-      pg[e] = (dg[e] + red[0][0][lane][e]) + (red[0][1][lane][e] + red[0][2][lane][e]);
-      pb[e] = (db[e] + red[1][0][lane][e]) + (red[1][1][lane][e] + red[1][2][lane][e]);
-    }
-  }
 }
 
 // stage 1 of a column sum: workgroup (bx, by) adds rows [by*rpb, (by+1)*rpb) of 64 column chunks of
@@ -209,30 +248,60 @@ __global__ void __launch_bounds__(256) colsum_kernel(const T* __restrict__ a, in
   }
 }
 
-// stage 2: out[c] (=|+=) sum over blocks.  A workgroup owns 64 columns; its 4 wavefronts take
-// every 4th partial row, then combine through LDS in wavefront order (a fixed summation tree).
-__global__ void __launch_bounds__(256) colsum_finish_kernel(const float* __restrict__ part, int nblk, int cols,
-                                                            float* __restrict__ out, int accumulate) {
-  __shared__ float red[4][64];
+// stage 2 of every column reduction of a pass, in one launch: segment s sums nblk partial rows of
+// `cols` floats into out (=|+=).  A workgroup of 16 wavefronts owns 256 columns of one segment
+// (16 B per lane); its wavefronts take every 16th partial row, then combine through LDS in
+// wavefront order (a fixed summation tree).
+__global__ void __launch_bounds__(1024) colsum_finish_kernel(FinishArgs a) {
+  __shared__ f32x4 red[16][64];
+  int si = 0;
+  while (si + 1 < a.nseg && (int)blockIdx.x >= a.seg[si + 1].wg0) si++;
+  const FinishSeg sg = a.seg[si];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + lane;
-  float s = 0.f;
-  if (c < cols) {
-#pragma unroll 8
-    for (int b = w; b < nblk; b += 4) s += part[(size_t)b * cols + c];
+  const int c = (((int)blockIdx.x - sg.wg0) * 64 + lane) * 4;
+  f32x4 s = {0.f, 0.f, 0.f, 0.f};
+  if (c < sg.cols) {
+#pragma unroll 4
+    for (int b = w; b < sg.nblk; b += 16) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(sg.part + (size_t)b * sg.cols + c);
+      s = f32x4{s[0] + v[0], s[1] + v[1], s[2] + v[2], s[3] + v[3]};
+    }
   }
   red[w][lane] = s;
   __syncthreads();
-  if (w == 0 && c < cols) {
-    const float t = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
-    out[c] = accumulate ? out[c] + t : t;
+  if (w == 0 && c < sg.cols) {
+    f32x4 t = red[0][lane];
+#pragma unroll
+    for (int k = 1; k < 16; k++) {
+      const f32x4 v = red[k][lane];
+      t = f32x4{t[0] + v[0], t[1] + v[1], t[2] + v[2], t[3] + v[3]};
+    }
+    f32x4* o = reinterpret_cast<f32x4*>(sg.out + c);
+    if (sg.accumulate) {
+      const f32x4 old = *o;
+      t = f32x4{t[0] + old[0], t[1] + old[1], t[2] + old[2], t[3] + old[3]};
+    }
+    *o = t;
   }
+}
+
+// shape of the fused LayerNorm-backward launch for a row length: wavefronts per row, chunks per lane
+void ln_bwd_shape(int nchunk, int& G, int& CPT) {
+  G = nchunk >= 512 ? 8 : nchunk >= 256 ? 4 : nchunk >= 128 ? 2 : 1;
+  CPT = cdiv(nchunk, 64 * G);
 }
 
 }  // namespace
 
-int ln_bwd_blocks(int rows) { return rows < 2048 ? cdiv(rows, 16) : 128; }
 int colsum_blocks(int rows) { return rows < 2048 ? cdiv(rows, 16) : 128; }
+
+int ln_bwd_blocks(bool is_bf16, int rows, int cols) {
+  int G, CPT;
+  ln_bwd_shape(cols / (is_bf16 ? 8 : 4), G, CPT);
+  const int per_step = (8 / G) * (8 / CPT);            // rows a workgroup takes per step
+  const int wgs = cdiv(rows, per_step) < 256 ? cdiv(rows, per_step) : 256;
+  return wgs * (8 / G);
+}
 
 hipError_t ln_fwd(bool is_bf16, const void* x, const void* g, const void* b, void* y, float* mean, float* rstd,
                   int rows, int cols, float eps, hipStream_t s) {
@@ -252,52 +321,61 @@ hipError_t ln_fwd(bool is_bf16, const void* x, const void* g, const void* b, voi
   return hipGetLastError();
 }
 
-hipError_t ln_bwd_dx(bool is_bf16, const void* dy, const void* x, const void* g, const float* mean,
-                     const float* rstd, const void* resid, void* dx, int rows, int cols, hipStream_t s) {
+hipError_t ln_bwd(bool is_bf16, const void* dy, const void* x, const void* g, const float* mean, const float* rstd,
+                  const void* resid, void* dx, int rows, int cols, int nsum, float* part, hipStream_t s) {
   const int vec = is_bf16 ? 8 : 4;
   if (rows <= 0 || cols <= 0 || cols % vec || cols / vec > 64 * LN_MAXC) return hipErrorInvalidValue;
-  dim3 gdx(cdiv(rows, 4)), block(256);
-  const int per_lane = cdiv(cols / vec, 64);
-#define GX_LN_DX(T, C)                                                                                            \
-  hipLaunchKernelGGL((ln_bwd_dx_kernel<T, C>), gdx, block, 0, s, (const T*)dy, (const T*)x, (const T*)g, mean, rstd, \
-                     (const T*)resid, (T*)dx, rows, cols)
-  if (is_bf16) {
-    if (per_lane <= 4) GX_LN_DX(bf16, 4); else if (per_lane <= 8) GX_LN_DX(bf16, 8); else GX_LN_DX(bf16, 16);
-  } else {
-    if (per_lane <= 4) GX_LN_DX(float, 4); else if (per_lane <= 8) GX_LN_DX(float, 8); else GX_LN_DX(float, 16);
+  if ((nsum != 2 && nsum != 4) || (nsum == 4 && !resid)) return hipErrorInvalidValue;
+  int G, CPT;
+  ln_bwd_shape(cols / vec, G, CPT);
+  if (CPT > 2) return hipErrorInvalidValue;
+  const int wgs = ln_bwd_blocks(is_bf16, rows, cols) / (8 / G);
+#define GX_LN_BWD(T, GG, CC, NN)                                                                                  \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, GG, CC, NN>), dim3(wgs), dim3(512), 0, s, (const T*)dy, (const T*)x,        \
+                     (const T*)g, mean, rstd, (const T*)resid, (T*)dx, rows, cols, part)
+#define GX_LN_BWD_N(T, GG, CC)              \
+  do {                                      \
+    if (nsum == 4) GX_LN_BWD(T, GG, CC, 4); \
+    else GX_LN_BWD(T, GG, CC, 2);           \
+  } while (0)
+#define GX_LN_BWD_C(T, GG)            \
+  do {                                \
+    if (CPT == 1) GX_LN_BWD_N(T, GG, 1); \
+    else GX_LN_BWD_N(T, GG, 2);       \
+  } while (0)
+#define GX_LN_BWD_G(T)                  \
+  do {                                  \
+    if (G == 8) GX_LN_BWD_C(T, 8);      \
+    else if (G == 4) GX_LN_BWD_C(T, 4); \
+    else if (G == 2) GX_LN_BWD_C(T, 2); \
+    else GX_LN_BWD_C(T, 1);             \
+  } while (0)
+  if (is_bf16) GX_LN_BWD_G(bf16);
+  else GX_LN_BWD_G(float);
+#undef GX_LN_BWD_G
+#undef GX_LN_BWD_C
+#undef GX_LN_BWD_N
+#undef GX_LN_BWD
+  return hipGetLastError();
+}
+
+hipError_t colsum_finish(const FinishSeg* segs, int nseg, hipStream_t s) {
+  if (nseg <= 0) return hipSuccess;
+  if (nseg > FINISH_MAX) return hipErrorInvalidValue;
+  FinishArgs a;
+  int wg = 0;
+  for (int i = 0; i < nseg; i++) {
+    if (segs[i].nblk <= 0 || segs[i].cols <= 0 || (segs[i].cols & 3)) return hipErrorInvalidValue;
+    a.seg[i] = segs[i];
+    a.seg[i].wg0 = wg;
+    wg += cdiv(segs[i].cols, 256);
   }
-#undef GX_LN_DX
+  a.nseg = nseg;
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3(wg), dim3(1024), 0, s, a);
   return hipGetLastError();
 }
 
-hipError_t ln_bwd_params(bool is_bf16, const void* dy, const void* x, const float* mean, const float* rstd,
-                         float* part, int rows, int cols, float* dg, float* db, bool accumulate, hipStream_t s) {
-  const int vec = is_bf16 ? 8 : 4;
-  if (rows <= 0 || cols <= 0 || cols % vec) return hipErrorInvalidValue;
-  const int nblk = ln_bwd_blocks(rows);
-  const int rpb = cdiv(rows, nblk);
-  dim3 gpar(cdiv(cols / vec, 64), nblk), block(256);
-  if (is_bf16)
-    hipLaunchKernelGGL(ln_bwd_param_kernel<bf16>, gpar, block, 0, s, (const bf16*)dy, (const bf16*)x, mean, rstd, rows,
-                       cols, rpb, part);
-  else
-    hipLaunchKernelGGL(ln_bwd_param_kernel<float>, gpar, block, 0, s, (const float*)dy, (const float*)x, mean, rstd,
-                       rows, cols, rpb, part);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  e = colsum_finish(part, nblk, cols, dg, accumulate, s);
-  if (e != hipSuccess) return e;
-  return colsum_finish(part + (size_t)nblk * cols, nblk, cols, db, accumulate, s);
-}
-
-hipError_t colsum_finish(const float* part, int nblk, int cols, float* out, bool accumulate, hipStream_t s) {
-  hipLaunchKernelGGL(colsum_finish_kernel, dim3(cdiv(cols, 64)), dim3(256), 0, s, part, nblk, cols, out,
-                     accumulate ? 1 : 0);
-  return hipGetLastError();
-}
-
-hipError_t colsum(bool is_bf16, const void* a, int rows, int cols, int ld, float* part, float* out, bool accumulate,
-                  hipStream_t s) {
+hipError_t colsum_partial(bool is_bf16, const void* a, int rows, int cols, int ld, float* part, hipStream_t s) {
   const int vec = is_bf16 ? 8 : 4;
   if (rows <= 0 || cols <= 0 || cols % vec || ld % vec) return hipErrorInvalidValue;
   const int nblk = colsum_blocks(rows);
@@ -307,9 +385,7 @@ hipError_t colsum(bool is_bf16, const void* a, int rows, int cols, int ld, float
     hipLaunchKernelGGL(colsum_kernel<bf16>, grid, block, 0, s, (const bf16*)a, rows, cols, ld, rpb, part);
   else
     hipLaunchKernelGGL(colsum_kernel<float>, grid, block, 0, s, (const float*)a, rows, cols, ld, rpb, part);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  return colsum_finish(part, nblk, cols, out, accumulate, s);
+  return hipGetLastError();
 }
 
 }  // namespace gx

@@ -10,15 +10,13 @@ For every candidate the table holds, per GPU:
   compute   gx_layer_fwd + gx_layer_bwd of the attention half at its micro-batch and of the
             feed-forward half at its micro-batch, timed on the GPU (single-phase calls), or, without
             a GPU, model FLOPs over an assumed rate;
-  memory    parameters (storage type) + fp32 gradients + fp32 master weights and two moments
-            (the shard's elements x (e + 16) bytes) + the activations the forward pass keeps
-            (gx_layer_saved_bytes, exact);
-  comm      a textbook ring model, NOT measured (one GPU here): two all-reduces of the half's
-            [tokens, hidden] activations per pass over its tensor-parallel group and one all-reduce
-            of the shard's gradients over its data-parallel group per step, at `link_gbps`.
+  memory    optimizer and parameter state (gx_strategy_cost) + the activations the forward pass
+            keeps (gx_layer_saved_bytes, exact);
+  comm      gx_strategy_cost's ring model, NOT measured (one GPU here), at `link_gbps`.
 
-Moving activations between consecutive layers whose data-parallel degrees differ costs one
-re-distribution of [tokens, hidden] at `link_gbps`.  The plan is gx_plan_search over that table.
+Shard sizes, state bytes, communication and hand-over times and FLOP counts are computed by the
+library (gx_strategy_cost, checked against a plain definition in the tests); this module only
+applies the candidate rules, times the kernels and marshals the table into gx_plan_search.
 The communication model, the candidate rules and the objective are this repository's reading: the
 paper names the search but prints no cost model.
 """
@@ -52,29 +50,6 @@ def candidates(model: Model, gpus: int, global_batch: int):
     return [(a, f) for a in degs if ok(a, model.heads) for f in degs if ok(f, model.ffn)]
 
 
-def _half_elems(model: Model, a: int, f: int):
-    H, F = model.hidden, model.ffn
-    attn = 2 * H + H * 3 * (H // a) + 3 * (H // a) + (H // a) * H + H
-    mlp = 2 * H + H * (F // f) + (F // f) + (F // f) * H + H
-    return attn, mlp
-
-
-def _ring(bytes_, n, link_gbps):
-    return 0.0 if n <= 1 else 2.0 * (n - 1) / n * bytes_ / (link_gbps * 1e9) * 1e3      # ms
-
-
-def half_flops(model: Model, degree: int, micro_batch: int, phase: str):
-    """Model FLOPs of one half, forward + backward (backward = 2 x forward), per GPU."""
-    T, H, S = micro_batch * model.seq, model.hidden, model.seq
-    if phase == "attn":
-        Hl = H // degree
-        fwd = 2.0 * T * H * 3 * Hl + 2.0 * T * Hl * H
-        fwd += 4.0 * micro_batch * (model.heads // degree) * (H // model.heads) * S * (S + 1) / 2.0
-    else:
-        fwd = 4.0 * T * H * (model.ffn // degree)
-    return 3.0 * fwd
-
-
 def measure_half(model: Model, degree: int, micro_batch: int, phase: str, reps: int = 5):
     """Milliseconds of gx_layer_fwd + gx_layer_bwd of one half at one shard shape, on cuda:0."""
     import torch
@@ -101,54 +76,49 @@ def measure_half(model: Model, degree: int, micro_batch: int, phase: str, reps: 
 
 def cost_table(model: Model, gpus: int, global_batch: int, link_gbps: float = 150.0, measure: bool = True,
                assumed_tflops: float = 900.0):
-    """One row per candidate strategy: times in ms per step per layer, memory in bytes per GPU."""
-    e = 2 if model.dtype == "bf16" else 4
+    """One row per candidate strategy: times in ms per step per layer, memory in bytes per GPU.
+    Sizes, communication times and FLOP counts come from gx_strategy_cost; compute times are
+    measured here (or, with measure=False, FLOPs over an assumed rate)."""
     dt = gx.GX_BF16 if model.dtype == "bf16" else gx.GX_F32
     cache = {}
 
-    def half(phase, d):
+    def half(phase, d, mb, flops):
         key = (phase, d)
         if key not in cache:
-            mb = global_batch * d // gpus
-            fl = half_flops(model, d, mb, phase)
             cfg = gx.make_cfg(model.hidden, model.heads, model.ffn, d if phase == "attn" else 1,
                               d if phase == "mlp" else 1, 0, model.seq, mb, dt,
                               gx.GX_PHASE_ATTN if phase == "attn" else gx.GX_PHASE_MLP)
             if gx.layer_validate(cfg) != gx.GX_OK:
                 cache[key] = None
             else:
-                ms = measure_half(model, d, mb, phase) if measure else fl / (assumed_tflops * 1e9)
-                cache[key] = dict(micro_batch=mb, flops=fl, compute_ms=ms, saved_bytes=gx.layer_saved_bytes(cfg))
+                ms = measure_half(model, d, mb, phase) if measure else flops / (assumed_tflops * 1e9)
+                cache[key] = dict(compute_ms=ms, saved_bytes=gx.layer_saved_bytes(cfg))
         return cache[key]
 
     rows = []
     for a, f in candidates(model, gpus, global_batch):
-        ha, hf = half("attn", a), half("mlp", f)
+        st, c = gx.strategy_cost(model.hidden, model.heads, model.ffn, model.seq, dt, gpus, global_batch, a, f,
+                                 link_gbps, check=False)
+        if st != gx.GX_OK:
+            continue
+        ha = half("attn", a, c.micro_batch_attn, c.flops_attn)
+        hf = half("mlp", f, c.micro_batch_ffn, c.flops_ffn)
         if ha is None or hf is None:
             continue
-        ea, ef = _half_elems(model, a, f)
-        act = lambda h: h["micro_batch"] * model.seq * model.hidden * e
-        comm = 0.0
-        comm += 2 * _ring(act(ha), a, link_gbps) + 2 * _ring(act(hf), f, link_gbps)        # fwd + bwd TP all-reduces
-        comm += _ring(ea * 4, gpus // a, link_gbps) + _ring(ef * 4, gpus // f, link_gbps)   # fp32 gradient all-reduce
-        rows.append(dict(tp_attn=a, tp_ffn=f, micro_batch_attn=ha["micro_batch"], micro_batch_ffn=hf["micro_batch"],
-                         compute_ms=ha["compute_ms"] + hf["compute_ms"], comm_ms=comm,
-                         time_ms=ha["compute_ms"] + hf["compute_ms"] + comm,
-                         tflops_per_gpu=(ha["flops"] + hf["flops"]) / ((ha["compute_ms"] + hf["compute_ms"]) * 1e9),
-                         state_bytes=(ea + ef) * (e + 16), saved_bytes=ha["saved_bytes"] + hf["saved_bytes"],
-                         mem_bytes=(ea + ef) * (e + 16) + ha["saved_bytes"] + hf["saved_bytes"]))
+        compute = ha["compute_ms"] + hf["compute_ms"]
+        comm = c.tp_comm_ms + c.dp_comm_ms
+        saved = ha["saved_bytes"] + hf["saved_bytes"]
+        rows.append(dict(tp_attn=a, tp_ffn=f, micro_batch_attn=c.micro_batch_attn, micro_batch_ffn=c.micro_batch_ffn,
+                         compute_ms=compute, comm_ms=comm, time_ms=compute + comm, switch_ms=c.switch_ms,
+                         tflops_per_gpu=(c.flops_attn + c.flops_ffn) / (compute * 1e9),
+                         state_bytes=c.state_bytes, saved_bytes=saved, mem_bytes=c.state_bytes + saved))
     return rows
 
 
-def switch_table(model: Model, rows, gpus: int, global_batch: int, link_gbps: float = 150.0):
-    """Cost of handing a layer's output to the next layer: between strategies whose neighbouring
-    halves (this layer's feed-forward, the next layer's attention) differ in data-parallel degree,
-    every GPU re-distributes its share of the [tokens, hidden] activations once (forward) and their
-    gradients once (backward)."""
-    e = 2 if model.dtype == "bf16" else 4
-    per_gpu = global_batch * model.seq * model.hidden * e / gpus
-    cost = 2.0 * per_gpu / (link_gbps * 1e9) * 1e3
-    return [[0.0 if r1["tp_ffn"] == r2["tp_attn"] or r1 is r2 else cost for r2 in rows] for r1 in rows]
+def switch_table(rows):
+    """Cost of handing a layer's output to the next layer: the strategy's switch_ms when this
+    layer's feed-forward degree differs from the next layer's attention degree, else 0."""
+    return [[0.0 if r1["tp_ffn"] == r2["tp_attn"] or r1 is r2 else r1["switch_ms"] for r2 in rows] for r1 in rows]
 
 
 def plan(model: Model, rows, gpus: int, global_batch: int, budget_bytes: float, link_gbps: float = 150.0,
@@ -156,7 +126,7 @@ def plan(model: Model, rows, gpus: int, global_batch: int, budget_bytes: float, 
     """gx_plan_search over identical layers; returns (status, per-layer rows, result)."""
     time = [[r["time_ms"] for r in rows]] * model.layers
     mem = [[float(r["mem_bytes"]) for r in rows]] * model.layers
-    sw = switch_table(model, rows, gpus, global_batch, link_gbps)
+    sw = switch_table(rows)
     st, choice, res = gx.plan_search(time, mem, sw, budget=budget_bytes, quantum=quantum_bytes, check=False)
     return st, [rows[c] for c in choice] if st == gx.GX_OK else [], res
 
