@@ -82,8 +82,9 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(const T* __restrict__ x, co
 // bias gradients of the row-parallel products on either side of the LayerNorm, whose upstream
 // gradients are exactly these two tensors).
 // A workgroup of 8 wavefronts; a row is shared by G of them (CPT chunks of 16 B per lane), the
-// 8 / G row groups each take R rows per step, all R rows' loads in flight together.  Row sums
-// cross the G wavefronts through LDS (one barrier per step, double-buffered by step parity).
+// 8 / G row groups each take R rows per step; the next step's rows are fetched before this step's
+// are worked on, so loads, arithmetic and stores overlap.  Row sums cross the G wavefronts through
+// LDS (one barrier per step, double-buffered by step parity).
 // Every row group keeps its own column accumulators and writes its own partial row:
 // part[a][blockIdx.x * (8 / G) + group][cols] for a < NSUM.  Fixed order throughout.
 template <typename T, int G, int CPT, int NSUM>
@@ -92,7 +93,7 @@ __global__ void __launch_bounds__(512) ln_bwd_kernel(const T* __restrict__ dy, c
                                                      const float* __restrict__ rstd, const T* __restrict__ resid,
                                                      T* __restrict__ dx, int rows, int cols, float* __restrict__ part) {
   constexpr int V = Vec<T>::N;
-  constexpr int NG = 8 / G, R = 8 / CPT;
+  constexpr int NG = 8 / G, R = 4 / CPT;
   typedef typename Vec<T>::type Raw;
   __shared__ float red[2][NG][R][G][2];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -119,33 +120,39 @@ __global__ void __launch_bounds__(512) ln_bwd_kernel(const T* __restrict__ dy, c
 #pragma unroll
       for (int e = 0; e < V; e++) acc[a][i][e] = 0.f;
   const float inv_cols = 1.0f / (float)cols;
-  int par = 0;
-  for (int base = blockIdx.x * NG * R; base < rows; base += gridDim.x * NG * R, par ^= 1) {
-    const int r0 = base + grp * R;
+
+  // one step's rows of this row group, as they come from memory
+  struct Step {
     Raw dyr[R][CPT], xr[R][CPT], rr[R][CPT];
     float mu[R], rs[R];
+  };
+  auto fetch = [&](Step& st, int base) {
+    const int r0 = base + grp * R;
 #pragma unroll
     for (int j = 0; j < R; j++) {
       const int row = r0 + j;
       const bool ok = row < rows;
-      mu[j] = ok ? mean[row] : 0.f;
-      rs[j] = ok ? rstd[row] : 0.f;
+      st.mu[j] = ok ? mean[row] : 0.f;
+      st.rs[j] = ok ? rstd[row] : 0.f;
 #pragma unroll
       for (int i = 0; i < CPT; i++) {
         Raw z;
 #pragma unroll
         for (int e = 0; e < V; e++) z[e] = from_f32<T>(0.f);
-        dyr[j][i] = z;
-        xr[j][i] = z;
-        rr[j][i] = z;
+        st.dyr[j][i] = z;
+        st.xr[j][i] = z;
+        st.rr[j][i] = z;
         if (ok && live[i]) {
           const size_t off = (size_t)row * cols + col[i];
-          dyr[j][i] = *reinterpret_cast<const Raw*>(dy + off);
-          xr[j][i] = *reinterpret_cast<const Raw*>(x + off);
-          if (has_resid) rr[j][i] = *reinterpret_cast<const Raw*>(resid + off);
+          st.dyr[j][i] = *reinterpret_cast<const Raw*>(dy + off);
+          st.xr[j][i] = *reinterpret_cast<const Raw*>(x + off);
+          if (has_resid) st.rr[j][i] = *reinterpret_cast<const Raw*>(resid + off);
         }
       }
     }
+  };
+  auto process = [&](Step& st, int base, int par) {
+    const int r0 = base + grp * R;
     // row sums of dy g and of dy g xhat
 #pragma unroll
     for (int j = 0; j < R; j++) {
@@ -154,9 +161,9 @@ __global__ void __launch_bounds__(512) ln_bwd_kernel(const T* __restrict__ dy, c
       for (int i = 0; i < CPT; i++)
 #pragma unroll
         for (int e = 0; e < V; e++) {
-          const float t = to_f32(dyr[j][i][e]) * gv[i][e];
+          const float t = to_f32(st.dyr[j][i][e]) * gv[i][e];
           s1 += t;
-          s2 += t * ((to_f32(xr[j][i][e]) - mu[j]) * rs[j]);
+          s2 += t * ((to_f32(st.xr[j][i][e]) - st.mu[j]) * st.rs[j]);
         }
       s1 = wave_sum(s1);
       s2 = wave_sum(s2);
@@ -166,6 +173,15 @@ __global__ void __launch_bounds__(512) ln_bwd_kernel(const T* __restrict__ dy, c
       }
     }
     __syncthreads();
+    // the second walk starts again from the rows as loaded: keeping the first walk's products
+    // alive across the barrier instead would cost more registers than the two steps in flight
+#pragma unroll
+    for (int j = 0; j < R; j++)
+#pragma unroll
+      for (int i = 0; i < CPT; i++) {
+        asm volatile("" : "+v"(st.dyr[j][i]));
+        asm volatile("" : "+v"(st.xr[j][i]));
+      }
 #pragma unroll
     for (int j = 0; j < R; j++) {
       const int row = r0 + j;
@@ -184,21 +200,38 @@ __global__ void __launch_bounds__(512) ln_bwd_kernel(const T* __restrict__ dy, c
         Raw o;
 #pragma unroll
         for (int e = 0; e < V; e++) {
-          const float d = to_f32(dyr[j][i][e]);
-          const float xh = (to_f32(xr[j][i][e]) - mu[j]) * rs[j];
-          float v = rs[j] * (d * gv[i][e] - c1 - xh * c2);
+          const float d = to_f32(st.dyr[j][i][e]);
+          const float xh = (to_f32(st.xr[j][i][e]) - st.mu[j]) * st.rs[j];
+          float v = st.rs[j] * (d * gv[i][e] - c1 - xh * c2);
           acc[0][i][e] += d * xh;
           acc[1][i][e] += d;
-          if (has_resid) v += to_f32(rr[j][i][e]);
+          if (has_resid) v += to_f32(st.rr[j][i][e]);
           o[e] = from_f32<T>(v);
           if (NSUM == 4) {
-            acc[2][i][e] += to_f32(rr[j][i][e]);
+            acc[2][i][e] += to_f32(st.rr[j][i][e]);
             acc[3][i][e] += to_f32(o[e]);          // the value the consumers of dx read
           }
         }
         *reinterpret_cast<Raw*>(dx + (size_t)row * cols + col[i]) = o;
       }
     }
+  };
+  // two steps in registers: the next step's rows travel while this step's are worked on.  The LDS
+  // exchange alternates with the step parity, so one barrier per step suffices: a wavefront can
+  // only reach the write of step k + 2 after every wavefront has passed the barrier of step k + 1,
+  // i.e. has finished reading step k's sums.
+  const int stride = gridDim.x * NG * R;
+  Step s0, s1;
+  int base = blockIdx.x * NG * R;
+  if (base < rows) fetch(s0, base);
+  while (base < rows) {
+    if (base + stride < rows) fetch(s1, base + stride);
+    process(s0, base, 0);
+    base += stride;
+    if (base >= rows) break;
+    if (base + stride < rows) fetch(s0, base + stride);
+    process(s1, base, 1);
+    base += stride;
   }
   const size_t nblk = (size_t)gridDim.x * NG, blk = (size_t)blockIdx.x * NG + grp;
 #pragma unroll
@@ -298,7 +331,7 @@ int colsum_blocks(int rows) { return rows < 2048 ? cdiv(rows, 16) : 128; }
 int ln_bwd_blocks(bool is_bf16, int rows, int cols) {
   int G, CPT;
   ln_bwd_shape(cols / (is_bf16 ? 8 : 4), G, CPT);
-  const int per_step = (8 / G) * (8 / CPT);            // rows a workgroup takes per step
+  const int per_step = (8 / G) * (4 / CPT);            // rows a workgroup takes per step
   const int wgs = cdiv(rows, per_step) < 256 ? cdiv(rows, per_step) : 256;
   return wgs * (8 / G);
 }
