@@ -60,6 +60,149 @@ def measured_traffic(workload, kernel):
     return m["bytes_per_launch"]
 
 
+class ClockPowerSampler:
+    """Samples the shader clock (the starred line of amdgpu's pp_dpm_sclk) and the socket power (hwmon
+    power1_average or power1_input, microwatts) from sysfs in a thread while a region runs.  Reads
+    nothing but those files; reports null when the box does not expose them to this user."""
+
+    def __init__(self, period_s=0.01):
+        import glob
+        self.period = period_s
+        self.freq = self.power = None
+        for dev in sorted(glob.glob("/sys/class/drm/card*/device")):
+            f = os.path.join(dev, "pp_dpm_sclk")
+            if self._sclk(f) is None:
+                continue
+            self.freq = f
+            for q in sorted(glob.glob(os.path.join(dev, "hwmon/hwmon*/power1_average"))) + \
+                    sorted(glob.glob(os.path.join(dev, "hwmon/hwmon*/power1_input"))):
+                if self._number(q) is not None:
+                    self.power = q
+                    break
+            break
+        self.samples = []
+
+    @staticmethod
+    def _number(path):
+        try:
+            with open(path) as fh:
+                return float(fh.read().strip())
+        except (OSError, ValueError):
+            return None
+
+    @staticmethod
+    def _sclk(path):
+        """MHz of the current level: the line that ends in '*', e.g. '1: 1530Mhz *'."""
+        try:
+            with open(path) as fh:
+                for line in fh:
+                    if line.rstrip().endswith("*"):
+                        return float(line.split(":")[1].lower().replace("mhz", "").replace("*", "").strip())
+        except (OSError, ValueError, IndexError):
+            pass
+        return None
+
+    def __enter__(self):
+        import threading
+        self._stop = threading.Event()
+
+        def loop():
+            while not self._stop.is_set():
+                self.samples.append((self._sclk(self.freq), self._number(self.power) if self.power else None))
+                self._stop.wait(self.period)
+        self._t = threading.Thread(target=loop, daemon=True)
+        if self.freq:
+            self._t.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        if self.freq:
+            self._t.join()
+
+    def summary(self):
+        if not self.freq or not self.samples:
+            return None
+        f = [a for a, _ in self.samples if a]
+        w = [b / 1e6 for _, b in self.samples if b]
+        out = {"samples": len(self.samples), "source": [self.freq] + ([self.power] if self.power else [])}
+        if f:
+            out.update(sclk_mhz_min=min(f), sclk_mhz_mean=sum(f) / len(f), sclk_mhz_max=max(f))
+        if w:
+            out.update(power_w_min=min(w), power_w_mean=sum(w) / len(w), power_w_max=max(w))
+        return out
+
+
+def hbm_bound_figures(kernels, sh, both_phases=True):
+    """Adds GB/s against the 8 TB/s HBM peak to the bandwidth-bound kernel classes of one block pass
+    (algorithmic bytes: every operand read once, every result written once) and TFLOP/s against the
+    matrix peak to the attention classes (causal attention counted on the unmasked pairs; the
+    backward pass is 2.5 times the forward)."""
+    T, H, Hl = sh.tokens, sh.hidden, sh.hidden_local
+    e = 2 if sh.dtype == "bf16" else 4
+    peak = PEAK_BF16_TFLOPS if sh.dtype == "bf16" else PEAK_F32_TFLOPS
+    per_launch = {"ln_fwd": 2.0 * T * H * e,                 # x in, y out (statistics negligible)
+                  "ln_bwd": 4.0 * T * H * e,                 # dy, x, residual gradient in, dx out
+                  "colsum": None}
+    for name, k in kernels.items():
+        b = per_launch.get(name)
+        if b:
+            k["algorithmic_bytes_per_launch"] = b
+            k["GB/s"] = b / (k["avg_ms"] * 1e-3) / 1e9
+            k["frac_of_hbm_peak"] = k["GB/s"] / 8000.0
+    attn = 4.0 * sh.micro_batch * sh.local_heads * sh.head_dim * sh.seq * (sh.seq + 1) / 2.0
+    for name, mult in (("attn_fwd", 1.0), ("attn_bwd", 2.5)):
+        if name in kernels:
+            k = kernels[name]
+            k["TFLOP/s"] = attn * mult / (k["avg_ms"] * 1e-3) / 1e12
+            k["frac_of_mfma_peak"] = k["TFLOP/s"] / peak
+
+
+def run_peaks():
+    """Measured ceilings of this machine, as one JSON line: the register-only MFMA loop and the plain copy
+    of the library's measurement hooks, and, as context, the vendor library's GEMM (through
+    torch.matmul) on the C3 layer's product shapes with the same kind of operands (N(0,1) activations,
+    N(0, 0.02^2) weights) and with constant operands."""
+    import torch
+    from paper_2504_03662_amd import binding as gx
+    st = torch.cuda.current_stream().cuda_stream
+    scratch = torch.zeros(64, dtype=torch.float32, device="cuda:0")
+    out = {"mfma_loop_tflops": gx.peak_mfma(scratch, 20, st)}
+    n = 1 << 29
+    src = torch.ones(n // 4, dtype=torch.float32, device="cuda:0")
+    dst = torch.empty_like(src)
+    out["copy_gbps_read_plus_write"] = gx.peak_copy(src, dst, n, 20, st)
+    del src, dst
+
+    def timed(fn, reps=30):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    table = []
+    torch.manual_seed(0)
+    for (M, N, K) in [(4096, 4096, 4096), (4096, 3072, 4096), (4096, 4096, 1024), (4096, 1024, 4096)]:
+        for kind in ("normal", "ones"):
+            mk = (lambda *d: torch.randn(*d, device="cuda:0", dtype=torch.bfloat16)) if kind == "normal" else \
+                 (lambda *d: torch.ones(*d, device="cuda:0", dtype=torch.bfloat16))
+            a, at = mk(M, K), mk(K, M)
+            b, bt = mk(K, N) * (0.02 if kind == "normal" else 1.0), mk(N, K) * (0.02 if kind == "normal" else 1.0)
+            fl = 2.0 * M * N * K
+            table.append({"M": M, "N": N, "K": K, "operands": kind,
+                          "NN": fl / timed(lambda: torch.matmul(a, b)) / 1e9,
+                          "NT": fl / timed(lambda: torch.matmul(a, bt.t())) / 1e9,
+                          "TN": fl / timed(lambda: torch.matmul(at.t(), b)) / 1e9})
+    out["vendor_gemm_tflops"] = table
+    print(json.dumps(out))
+
+
 CLASS_NAMES = {1: "ln_fwd", 2: "ln_bwd", 3: "attn_fwd", 4: "attn_bwd", 5: "colsum", 6: "dropout",
                101: "gemm_nn_bias", 102: "gemm_nn_resid", 103: "gemm_nn_gelu", 110: "gemm_nt_store",
                114: "gemm_nt_dgelu", 125: "gemm_tn_f32", 126: "gemm_tn_f32_acc",
@@ -90,6 +233,12 @@ def main():
                          "gradients and parameters (every product multiplies zeros), which shows how fast the same kernels "
                          "and launch sequence run when operand switching activity does not hold the clock down; "
                          "recorded in \"data\"")
+    ap.add_argument("--peaks", action="store_true",
+                    help="instead of the benchmark: measure this box's ceilings (register-only MFMA loop, plain "
+                         "copy, the vendor library's GEMM on the layer's product shapes) and print them as JSON")
+    ap.add_argument("--sustain-seconds", type=float, default=2.0,
+                    help="after the timed region, keep running steps back to back for this long while sampling "
+                         "shader clock and socket power (reported under \"sustained\"; 0 to skip)")
     ap.add_argument("--neighbours", action="store_true",
                     help="also time the layer step's memory-bound neighbours at this workload's shapes (AdamW "
                          "update of the rank's parameters, slicing the rank's shard out of the whole block and "
@@ -108,6 +257,9 @@ def main():
     gx.set_overlap(not args.serial)
     if not torch.cuda.is_available():
         sys.exit("bench.py needs an MI355X: no GPU is visible")
+    if args.peaks:
+        run_peaks()
+        return
     shape, blocks, mbs = I.WORKLOADS[args.workload]
     if args.dropout:
         shape = shape.with_(drop_attn=args.dropout, drop_hidden=args.dropout, drop_seed=20250403)
@@ -141,11 +293,29 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    with ClockPowerSampler(0.002) as timed_sampler:
+        t0 = time.perf_counter()
+        marks[0].record()
+        for i in range(args.steps):
+            step()
+            marks[i + 1].record()                   # on the stream every step starts from and joins back to
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    sustained = None
+    if args.sustain_seconds > 0:
+        # back-to-back steps for a couple of seconds: what the chip holds once clocks and power settle
+        n_sus = max(args.steps, int(args.sustain_seconds * 1e3 / ms))
+        with ClockPowerSampler(0.01) as sus_sampler:
+            t1 = time.perf_counter()
+            for i in range(n_sus):
+                step()
+                if i % 64 == 63:
+                    torch.cuda.synchronize()        # bound the launch queue
+            torch.cuda.synchronize()
+            sus_ms = (time.perf_counter() - t1) * 1e3 / n_sus
+        sustained = {"steps": n_sus, "ms_per_step": sus_ms, "clock_power": sus_sampler.summary()}
     flops = model_flops(shape, blocks, mbs)
     tflops = flops / (ms * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if shape.dtype == "bf16" else PEAK_F32_TFLOPS
@@ -193,11 +363,19 @@ def main():
         / (gemm_ms * 1e-3) / 1e12 if not pipelined else None
     roofline = {"bound": "mfma", "kernel": CLASS_NAMES.get(dom, str(dom)), "achieved": achieved, "peak": peak,
                 "unit": "TFLOP/s", "frac": achieved / peak,
-                "traffic": measured_traffic(args.workload, CLASS_NAMES.get(dom, str(dom))), "avg_launch_ms": avg_ms,
+                "traffic": measured_traffic(args.workload, CLASS_NAMES.get(dom, str(dom))),
+                "traffic_source": "stored from profiles/ (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE); null when the "
+                                  "kernel source has changed since the counters were taken",
+                "avg_launch_ms": avg_ms,
                 "flops_per_launch": flops_per_launch, "all_gemms_tflops": gemm_tflops}
 
+    hbm_bound_figures(kernels, shape)
+    if sustained:
+        sustained["value"] = flops / (sustained["ms_per_step"] * 1e-3) / 1e12
     out = {"metric": "layer fwd+bwd TFLOP/s per GPU", "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,
-           "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+           "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
+           "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype,
            "data": "zeros (clock diagnostic, not a benchmark)" if args.zero_operands else "synthetic",
            "config": {"workload": args.workload, "hidden": shape.hidden, "heads": shape.heads, "ffn": shape.ffn,
@@ -210,7 +388,8 @@ def main():
            "frac_of_mfma_peak": tflops / peak,
            "tokens_per_s_per_layer": shape.tokens * blocks * mbs / (ms * 1e-3),
            "model_tflop_per_step": flops / 1e12,
-           "roofline": roofline, "kernels": kernels}
+           "roofline": roofline, "kernels": kernels,
+           "clock_power_timed_region": timed_sampler.summary(), "sustained": sustained}
 
     if args.neighbours:
         out["neighbours"] = neighbours(shape, stack, max(3, min(args.steps, 20)))

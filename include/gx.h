@@ -221,6 +221,20 @@ enum { GX_KC_LN_FWD = 1, GX_KC_LN_BWD = 2, GX_KC_ATTN_FWD = 3, GX_KC_ATTN_BWD = 
 gx_status gx_prof_enable(int on);
 int gx_prof_collect(int* kernel_class, float* ms, int capacity);
 
+/* Measured ceilings of the chip, to hold the layer's kernels against (benchmarks only; both calls
+ * create two HIP events, queue their work on `hip_stream`, wait for it and destroy the events):
+ *   gx_peak_mfma : `launches` launches of a register-only v_mfma_f32_32x32x16_bf16 loop (1024
+ *                       workgroups of 4 wavefronts, 4 independent accumulators each, no memory
+ *                       traffic); *tflops receives the sustained rate.  `scratch`: at least 64
+ *                       bytes of device memory (never written in practice).
+ *   gx_peak_copy      : `launches` copies of `bytes` (a multiple of 16) from src to dst, 16 bytes per
+ *                       lane, grid-stride; *gbytes_per_s receives read + write bytes per second.
+ * Errors: GX_ERR_NULL, GX_ERR_SHAPE (launches outside 1..1000, bytes), GX_ERR_ALIGN, GX_ERR_ARCH,
+ * GX_ERR_LAUNCH. */
+gx_status gx_peak_mfma(void* scratch, int launches, double* tflops, void* hip_stream);
+gx_status gx_peak_copy(const void* src, void* dst, size_t bytes, int launches, double* gbytes_per_s,
+                       void* hip_stream);
+
 /* ------------------------------------------------------------------------------------------
  * Neighbours of the layer step: the optimizer update and the re-partitioning of a block's
  * parameters between tensor-parallel degrees.  Both are memory-bound passes over device arrays.

@@ -22,7 +22,7 @@ PARAM_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
 EXPORTS = ("gx_layer_validate", "gx_layer_saved_bytes", "gx_layer_workspace_bytes", "gx_layer_fwd",
            "gx_layer_bwd", "gx_status_str", "gx_version", "gx_prof_enable", "gx_prof_collect", "gx_set_overlap",
-           "gx_adamw_step", "gx_params_slice", "gx_params_merge", "gx_plan_search", "gx_strategy_cost", "gx_layer_bwd_static")
+           "gx_adamw_step", "gx_params_slice", "gx_params_merge", "gx_plan_search", "gx_strategy_cost", "gx_layer_bwd_static", "gx_peak_mfma", "gx_peak_copy")
 GX_KC_LN_FWD, GX_KC_LN_BWD, GX_KC_ATTN_FWD, GX_KC_ATTN_BWD, GX_KC_COLSUM, GX_KC_GEMM = 1, 2, 3, 4, 5, 100
 
 
@@ -131,6 +131,10 @@ def lib():
         L.gx_plan_search.argtypes = [ctypes.POINTER(PlanProblem), ctypes.POINTER(ctypes.c_int32),
                                      ctypes.POINTER(PlanResult)]
         L.gx_plan_search.restype = ctypes.c_int
+        L.gx_peak_mfma.argtypes = [P, ctypes.c_int, ctypes.POINTER(ctypes.c_double), P]
+        L.gx_peak_mfma.restype = ctypes.c_int
+        L.gx_peak_copy.argtypes = [P, P, ctypes.c_size_t, ctypes.c_int, ctypes.POINTER(ctypes.c_double), P]
+        L.gx_peak_copy.restype = ctypes.c_int
         L.gx_strategy_cost.argtypes = [ctypes.POINTER(StrategyQuery), ctypes.POINTER(StrategyCosts)]
         L.gx_strategy_cost.restype = ctypes.c_int
         _lib = L
@@ -283,4 +287,22 @@ def strategy_cost(hidden, heads, ffn, seq, dtype, gpus, global_batch, tp_attn, t
     if check and st != GX_OK:
         raise GxError(st, "gx_strategy_cost")
     return int(st), out
+
+
+def peak_mfma(scratch, launches=20, stream=0):
+    """TFLOP/s of the register-only MFMA loop."""
+    out = ctypes.c_double()
+    st = lib().gx_peak_mfma(_ptr(scratch), int(launches), ctypes.byref(out), ctypes.c_void_p(stream))
+    if st != GX_OK:
+        raise GxError(st, "gx_peak_mfma")
+    return out.value
+
+
+def peak_copy(src, dst, nbytes, launches=20, stream=0):
+    """GB/s (read + write) of the plain copy."""
+    out = ctypes.c_double()
+    st = lib().gx_peak_copy(_ptr(src), _ptr(dst), int(nbytes), int(launches), ctypes.byref(out), ctypes.c_void_p(stream))
+    if st != GX_OK:
+        raise GxError(st, "gx_peak_copy")
+    return out.value
 
