@@ -473,48 +473,70 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
   Fork fk(st, allow_side);
   Finisher fin;
   gx_status s;
-  // With both phases and no output dropout, LayerNorm 2's backward kernel reads dy as its residual
-  // gradient and writes dh1: the gradients of the two row-parallel biases are the column sums of
-  // exactly these tensors, and that kernel forms them on the way (4 sums).  Otherwise they come
-  // from plain column-sum passes.
+  // The weight-gradient products only consume finished tensors, so they are handed to the side
+  // stream, beside the dependent chain on the caller's stream.  When they are handed over matters
+  // little (the large products simply share the chip with whatever runs beside them) but measurably:
+  // FC2's after the FC1 input gradient, FC1's and the output projection's after LayerNorm 2, QKV's
+  // after the attention kernels measured best at the benchmark's shard shape (about 1 % over
+  // handing each over as soon as its operands exist), and needs three fork points instead of four.
+  // Points: 0 start, 1 after dz, 2 after dy2, 3 after LayerNorm 2, 4 after dctx, 5 after attention,
+  // 6 after dy1; one character per product (dW2, dW1, dWo, dWqkv).
+  const char sched[5] = "2335";
   const bool ln2_sums_biases = attn && mlp && !dr.hidden;
   const int lnb = ln_bwd_blocks(d.bf, (int)d.T, (int)d.H);
-  const void* dcur = dy;           // gradient arriving at the attention half's output
+  const void* dp_mlp = dy;
+  const void* dp_attn = nullptr;
+  auto task = [&](int t, hipStream_t sd) -> gx_status {
+    if (t == 0) {        // dW2 (+ b_fc2)
+      if (!(c.flags & GX_ROW_BIAS_MLP)) { if ((s = zero_grad(acc, gr.b_fc2, d.H, sd)) != GX_OK) return s; }
+      else if (!ln2_sums_biases) GX_TRY(colsum_p(d.bf, dp_mlp, d.T, d.H, w.part_fc2, gr.b_fc2, acc, fin, sd));
+      GemmArgs w2 = gargs(sv.act, dp_mlp, gr.w_fc2, d.Fl, d.H, d.T, d.Fl, d.H, d.H);
+      GX_TRY(wgrad(w2, sd));
+    } else if (t == 1) { // dW1
+      if (!d.bf) GX_TRY(colsum_p(d.bf, w.dz, d.T, d.Fl, w.part_fc1, gr.b_fc1, acc, fin, sd));
+      GemmArgs w1 = gargs(sv.y2, w.dz, gr.w_fc1, d.H, d.Fl, d.T, d.H, d.Fl, d.Fl);
+      GX_TRY(wgrad(w1, sd));
+    } else if (t == 2) { // dWo (+ b_o)
+      if (!(c.flags & GX_ROW_BIAS_ATTN)) { if ((s = zero_grad(acc, gr.b_o, d.H, sd)) != GX_OK) return s; }
+      else if (!ln2_sums_biases) GX_TRY(colsum_p(d.bf, dp_attn, d.T, d.H, w.part_o, gr.b_o, acc, fin, sd));
+      GemmArgs wo = gargs(sv.ctx, dp_attn, gr.w_o, d.Hl, d.H, d.T, d.Hl, d.H, d.H);
+      GX_TRY(wgrad(wo, sd));
+    } else {             // dWqkv (+ b_qkv)
+      GX_TRY(colsum_p(d.bf, w.dqkv, d.T, 3 * d.Hl, w.part_qkv, gr.b_qkv, acc, fin, sd));
+      GemmArgs wq = gargs(sv.y1, w.dqkv, gr.w_qkv, d.H, 3 * d.Hl, d.T, d.H, 3 * d.Hl, 3 * d.Hl);
+      GX_TRY(wgrad(wq, sd));
+    }
+    return GX_OK;
+  };
+  auto point = [&](int k) -> gx_status {
+    hipStream_t sd = nullptr;
+    for (int t = 0; t < 4; t++) {
+      if (sched[t] - '0' != k) continue;
+      if ((t < 2 && !mlp) || (t >= 2 && !attn)) continue;
+      if (!sd) sd = fk.branch();
+      if ((s = task(t, sd)) != GX_OK) return s;
+    }
+    return GX_OK;
+  };
+  const void* dcur = dy;
   if (mlp) {
     const void* h1 = attn ? sv.h1 : x;
-    // gradient reaching the feed-forward half's output: dy itself, or dy through that output's mask
-    const void* dp = dy;
     if (dr.hidden) {
       GX_TRY(dropout_p(d, dr, dy, nullptr, db.dym, DROP_STREAM_MLP_OUT, st));
-      dp = db.dym;
+      dp_mlp = db.dym;
     }
-    // row-parallel FC2: bias and weight gradients need only dp and saved activations: side
-    hipStream_t sd = fk.branch();
-    if (!(c.flags & GX_ROW_BIAS_MLP)) {
-      if ((s = zero_grad(acc, gr.b_fc2, d.H, sd)) != GX_OK) return s;
-    } else if (!ln2_sums_biases) {
-      GX_TRY(colsum_p(d.bf, dp, d.T, d.H, w.part_fc2, gr.b_fc2, acc, fin, sd));
-    }
-    GemmArgs w2 = gargs(sv.act, dp, gr.w_fc2, d.Fl, d.H, d.T, d.Fl, d.H, d.H);
-    GX_TRY(wgrad(w2, sd));
-    // input gradient fused with GELU' on the caller's stream; the bf16 kernel also leaves the
-    // partial column sums of dz (FC1 bias gradient)
-    GemmArgs dz = gargs(dp, p.w_fc2, w.dz, d.T, d.Fl, d.H, d.H, d.H, d.Fl);
+    if ((s = point(0)) != GX_OK) return s;
+    GemmArgs dz = gargs(dp_mlp, p.w_fc2, w.dz, d.T, d.Fl, d.H, d.H, d.H, d.Fl);
     dz.z = sv.gelu_grad;
     if (d.bf) {
       dz.colpart = w.part_fc1;
       fin.add(w.part_fc1, cdiv(d.T, 64), d.Fl, gr.b_fc1, acc);
     }
     GX_TRY(gemm(d, LAY_NT, EPI_DGELU, dz, st));
-    // column-parallel FC1: weight gradient on the side once dz exists
-    sd = fk.branch();
-    if (!d.bf) GX_TRY(colsum_p(d.bf, w.dz, d.T, d.Fl, w.part_fc1, gr.b_fc1, acc, fin, sd));
-    GemmArgs w1 = gargs(sv.y2, w.dz, gr.w_fc1, d.H, d.Fl, d.T, d.H, d.Fl, d.Fl);
-    GX_TRY(wgrad(w1, sd));
+    if ((s = point(1)) != GX_OK) return s;
     GemmArgs dy2 = gargs(w.dz, p.w_fc1, w.dy2, d.T, d.H, d.Fl, d.Fl, d.Fl, d.H);
     GX_TRY(gemm(d, LAY_NT, EPI_STORE, dy2, st));
-    // LayerNorm 2: input gradient (plus dy through the residual branch when both phases run) and
-    // the partial sums of its parameter gradients in one pass
+    if ((s = point(2)) != GX_OK) return s;
     void* out = attn ? w.dh1 : dx;
     {
       ProfScope ps(GX_KC_LN_BWD, st);
@@ -529,40 +551,34 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
       if (c.flags & GX_ROW_BIAS_ATTN) fin.add(w.part_ln2 + 3 * stride, lnb, d.H, gr.b_o, acc);
     }
     dcur = w.dh1;
+    if (!attn)                       // a lone feed-forward half: no later point will come
+      for (int k = 3; k <= 6; k++)
+        if ((s = point(k)) != GX_OK) return s;
   }
   if (attn) {
-    // row-parallel output projection: bias and weight gradients on the side (the weight gradient
-    // has few tiles and overlaps the attention kernels), input gradient on the caller's stream
-    const void* dp = dcur;           // gradient reaching the attention half's output
+    dp_attn = dcur;
     if (dr.hidden) {
       GX_TRY(dropout_p(d, dr, dcur, nullptr, db.dh1m, DROP_STREAM_ATTN_OUT, st));
-      dp = db.dh1m;
+      dp_attn = db.dh1m;
     }
-    hipStream_t sd = fk.branch();
-    if (!(c.flags & GX_ROW_BIAS_ATTN)) {
-      if ((s = zero_grad(acc, gr.b_o, d.H, sd)) != GX_OK) return s;
-    } else if (!ln2_sums_biases) {
-      GX_TRY(colsum_p(d.bf, dp, d.T, d.H, w.part_o, gr.b_o, acc, fin, sd));
-    }
-    GemmArgs wo = gargs(sv.ctx, dp, gr.w_o, d.Hl, d.H, d.T, d.Hl, d.H, d.H);
-    GX_TRY(wgrad(wo, sd));
-    GemmArgs dc = gargs(dp, p.w_o, w.dctx, d.T, d.Hl, d.H, d.H, d.H, d.Hl);
+    if ((s = point(3)) != GX_OK) return s;
+    GemmArgs dc = gargs(dp_attn, p.w_o, w.dctx, d.T, d.Hl, d.H, d.H, d.H, d.Hl);
     GX_TRY(gemm(d, LAY_NT, EPI_STORE, dc, st));
+    if ((s = point(4)) != GX_OK) return s;
     AttnArgs a;
     memset(&a, 0, sizeof(a));
     a.qkv = sv.qkv; a.ctx = sv.ctx; a.lse = sv.lse; a.dctx = w.dctx; a.dqkv = w.dqkv; a.dsum = w.dsum;
     a.B = (int)d.B; a.S = (int)d.S; a.nl = (int)d.nl; a.dh = (int)d.dh;
     set_attn_drop(a, d, dr, db);
     { ProfScope ps(GX_KC_ATTN_BWD, st);
-    GX_TRY(d.bf ? attn_bwd_bf16(a, st, fk.side != st ? g_side.s2 : st, g_side.attn_fork, g_side.attn_join) : attn_bwd_f32(a, st));
-    if (d.bf && fk.side != st) fk.used = true; }
-    // column-parallel QKV
-    hipStream_t sq = fk.branch();
-    GX_TRY(colsum_p(d.bf, w.dqkv, d.T, 3 * d.Hl, w.part_qkv, gr.b_qkv, acc, fin, sq));
-    GemmArgs wq = gargs(sv.y1, w.dqkv, gr.w_qkv, d.H, 3 * d.Hl, d.T, d.H, 3 * d.Hl, 3 * d.Hl);
-    GX_TRY(wgrad(wq, sq));
+    // the dQ kernel follows the dK / dV kernel on the caller's stream: a stream of its own for it
+    // measured slightly slower (its workgroups cannot share a compute unit with the other kernel's)
+    GX_TRY(d.bf ? attn_bwd_bf16(a, st, st, g_side.attn_fork, g_side.attn_join) : attn_bwd_f32(a, st));
+    }
+    if ((s = point(5)) != GX_OK) return s;
     GemmArgs dy1 = gargs(w.dqkv, p.w_qkv, w.dy1, d.T, d.H, 3 * d.Hl, 3 * d.Hl, 3 * d.Hl, d.H);
     GX_TRY(gemm(d, LAY_NT, EPI_STORE, dy1, st));
+    if ((s = point(6)) != GX_OK) return s;
     {
       ProfScope ps(GX_KC_LN_BWD, st);
       GX_TRY(ln_bwd(d.bf, w.dy1, x, p.ln1_g, sv.mean1, sv.rstd1, mlp ? dcur : nullptr, dx, (int)d.T, (int)d.H, 2,
@@ -572,7 +588,6 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     fin.add(w.part_ln1 + (size_t)lnb * d.H, lnb, d.H, gr.ln1_b, acc);
   }
   GX_TRY(fk.join());
-  // every partial sum is complete: one launch finishes all column reductions of the pass
   {
     ProfScope ps(GX_KC_COLSUM, st);
     GX_TRY(colsum_finish(fin.seg, fin.n, st));

@@ -332,7 +332,10 @@ int ln_bwd_blocks(bool is_bf16, int rows, int cols) {
   int G, CPT;
   ln_bwd_shape(cols / (is_bf16 ? 8 : 4), G, CPT);
   const int per_step = (8 / G) * (4 / CPT);            // rows a workgroup takes per step
-  const int wgs = cdiv(rows, per_step) < 256 ? cdiv(rows, per_step) : 256;
+  // one workgroup per compute unit, but at least four steps each: every row group leaves a partial
+  // row of `cols` sums, which should stay a small fraction of the rows read
+  const int want = cdiv(rows, 4 * per_step);
+  const int wgs = want < 256 ? want : 256;
   return wgs * (8 / G);
 }
 
