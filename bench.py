@@ -237,8 +237,8 @@ def main():
                     help="instead of the benchmark: measure this box's ceilings (register-only MFMA loop, plain "
                          "copy, the vendor library's GEMM on the layer's product shapes) and print them as JSON")
     ap.add_argument("--sustain-seconds", type=float, default=2.0,
-                    help="after the timed region, keep running steps back to back for this long while sampling "
-                         "shader clock and socket power (reported under \"sustained\"; 0 to skip)")
+                    help="before the per-kernel pass and the timed region, run steps back to back for this long while "
+                         "sampling shader clock and socket power (reported under \"sustained\"; 0 to skip)")
     ap.add_argument("--neighbours", action="store_true",
                     help="also time the layer step's memory-bound neighbours at this workload's shapes (AdamW "
                          "update of the rank's parameters, slicing the rank's shard out of the whole block and "
