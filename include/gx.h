@@ -44,13 +44,13 @@
  *     one ordinary call has created the library's streams and events.
  *   - Calls only enqueue work (a hipStream_t, or NULL for the default stream); they never allocate
  *     device memory, free or synchronise the host, and results are bitwise reproducible run to
- *     run.  gx_layer_bwd forks part of its work (the weight gradients, the bias / LayerNorm
- *     parameter reductions and one attention kernel) onto two streams that the library creates on
- *     first use (default priority, non-blocking) and joins them back with events before returning:
- *     to the caller everything is ordered on `hip_stream` as if it had run there
- *     (gx_set_overlap(0) really runs it there).  Those streams with their events and the optional
- *     timing record of gx_prof_* are the only process-global state; because of them, calls from
- *     several host threads must not overlap.
+ *     run.  gx_layer_bwd forks part of its work (the weight-gradient products and the stage-1 sums
+ *     of a bias gradient) onto a stream that the library creates on first use (default priority,
+ *     non-blocking; one per host thread and device, with its events) and joins it back with events
+ *     before returning: to the caller everything is ordered on `hip_stream` as if it had run there
+ *     (gx_set_overlap(0) really runs it there).  Calls from different host threads may overlap;
+ *     two calls that share a `workspace` or `saved` block may not.  The gx_set_overlap switch and
+ *     the optional timing record of gx_prof_* are process-global.
  *   - Errors are returned as gx_status; nothing is thrown across the boundary.  Configuration and
  *     pointer checks happen before anything is enqueued.
  */

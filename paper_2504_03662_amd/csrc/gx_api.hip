@@ -288,40 +288,47 @@ hipError_t colsum_p(bool bf, const void* a, long rows, long cols, float* part, f
 // process (calls from several host threads must not overlap).
 struct SideStream {
   bool tried = false, ok = false;
-  hipStream_t s = nullptr, s2 = nullptr;
+  hipStream_t s = nullptr;
   hipEvent_t fork[8];
-  hipEvent_t join, attn_fork, attn_join;
-} g_side;
+  hipEvent_t join;
+};
+constexpr int MAX_DEVICES = 64;
+// one per host thread and device, created on first use and kept: calls from different host threads
+// never share a side stream or an event
+thread_local SideStream t_side[MAX_DEVICES];
 
 bool g_overlap = true;     // gx_set_overlap
 
-bool side_ready() {
-  if (!g_overlap) return false;
-  if (!g_side.tried) {
-    g_side.tried = true;
-    bool ok = hipStreamCreateWithFlags(&g_side.s, hipStreamNonBlocking) == hipSuccess;
-    ok = ok && hipStreamCreateWithFlags(&g_side.s2, hipStreamNonBlocking) == hipSuccess;
-    for (int i = 0; ok && i < 8; i++) ok = hipEventCreateWithFlags(&g_side.fork[i], hipEventDisableTiming) == hipSuccess;
-    ok = ok && hipEventCreateWithFlags(&g_side.join, hipEventDisableTiming) == hipSuccess;
-    ok = ok && hipEventCreateWithFlags(&g_side.attn_fork, hipEventDisableTiming) == hipSuccess;
-    ok = ok && hipEventCreateWithFlags(&g_side.attn_join, hipEventDisableTiming) == hipSuccess;
-    g_side.ok = ok;
+SideStream* side_ready() {
+  if (!g_overlap) return nullptr;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+  SideStream& sd = t_side[dev];
+  if (!sd.tried) {
+    sd.tried = true;
+    bool ok = hipStreamCreateWithFlags(&sd.s, hipStreamNonBlocking) == hipSuccess;
+    for (int i = 0; ok && i < 8; i++) ok = hipEventCreateWithFlags(&sd.fork[i], hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&sd.join, hipEventDisableTiming) == hipSuccess;
+    sd.ok = ok;
   }
-  return g_side.ok;
+  return sd.ok ? &sd : nullptr;
 }
 
 // Work queued on the side stream after everything queued so far on the caller's stream.
 struct Fork {
   hipStream_t main, side;
+  SideStream* ss;
   int n = 0;
   bool used = false;
-  Fork(hipStream_t m, bool allow_side) : main(m), side(allow_side && side_ready() ? g_side.s : m) {}
+  Fork(hipStream_t m, bool allow_side) : main(m), side(m), ss(allow_side ? side_ready() : nullptr) {
+    if (ss) side = ss->s;
+  }
   hipError_t err = hipSuccess;     // first failure of an event call; reported by join()
   // stream for a task that depends on what `main` holds now
   hipStream_t branch() {
     if (side != main && n < 8 && err == hipSuccess) {
-      err = hipEventRecord(g_side.fork[n], main);
-      if (err == hipSuccess) err = hipStreamWaitEvent(side, g_side.fork[n], 0);
+      err = hipEventRecord(ss->fork[n], main);
+      if (err == hipSuccess) err = hipStreamWaitEvent(side, ss->fork[n], 0);
       if (err != hipSuccess) return main;       // not ordered after the producer: stay on its stream
       n++;
       used = true;
@@ -332,9 +339,9 @@ struct Fork {
   hipError_t join() {
     if (err != hipSuccess) return err;
     if (!used) return hipSuccess;
-    hipError_t e = hipEventRecord(g_side.join, side);
+    hipError_t e = hipEventRecord(ss->join, side);
     if (e != hipSuccess) return e;
-    return hipStreamWaitEvent(main, g_side.join, 0);
+    return hipStreamWaitEvent(main, ss->join, 0);
   }
 };
 
@@ -573,7 +580,7 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
     { ProfScope ps(GX_KC_ATTN_BWD, st);
     // the dQ kernel follows the dK / dV kernel on the caller's stream: a stream of its own for it
     // measured slightly slower (its workgroups cannot share a compute unit with the other kernel's)
-    GX_TRY(d.bf ? attn_bwd_bf16(a, st, st, g_side.attn_fork, g_side.attn_join) : attn_bwd_f32(a, st));
+    GX_TRY(d.bf ? attn_bwd_bf16(a, st, st, nullptr, nullptr) : attn_bwd_f32(a, st));
     }
     if ((s = point(5)) != GX_OK) return s;
     GemmArgs dy1 = gargs(w.dqkv, p.w_qkv, w.dy1, d.T, d.H, 3 * d.Hl, 3 * d.Hl, 3 * d.Hl, d.H);
@@ -654,7 +661,6 @@ gx_status layer_bwd(const gx_layer_cfg* cfg, const gx_params* params, const void
 
 // The device address of `scratch` (the name itself is only a handle for the runtime's symbol
 // lookup in host code, never an address): asked for once per device, with that device current.
-constexpr int MAX_DEVICES = 64;
 void* g_scratch_ptr[MAX_DEVICES];
 
 void* static_scratch() {

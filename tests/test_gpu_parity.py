@@ -392,3 +392,39 @@ def test_launch_timing_record():
     assert sorted(c for c, _ in bwd) == sorted([gx.GX_KC_COLSUM] * 2 + [gx.GX_KC_LN_BWD] * 2 + [gx.GX_KC_ATTN_BWD]
                                                + [G + 25] * 4 + [G + 14] + [G + 10] * 3)
     assert all(t > 0 for _, t in fwd + bwd)
+
+
+def test_calls_from_two_host_threads_overlap_safely():
+    """Each host thread gets its own side stream and events: two threads that run forward +
+    backward passes at the same time, each on its own stream and buffers, get bit for bit what one
+    thread alone gets."""
+    import threading
+    shape = I.LayerShape(512, 4, 1096, 2, 1, 0, 300, 2, "bf16")
+    params, x, dy = _case(shape, 96)
+    xd, dyd = to_device(x, "bf16"), to_device(dy, "bf16")
+
+    def run(reps, out):
+        layer = DeviceLayer(shape, params)
+        with torch.cuda.stream(torch.cuda.Stream()):
+            for _ in range(reps):
+                y = layer.forward(xd)["y"]
+                dx = layer.backward(xd, dyd)
+            torch.cuda.current_stream().synchronize()
+        out.append((to_host(y), to_host(dx), {n: to_host(layer.grads[n]) for n in I.PARAM_NAMES}))
+
+    alone = []
+    run(1, alone)
+    torch.cuda.synchronize()
+    res = [[], []]
+    threads = [threading.Thread(target=run, args=(20, res[k])) for k in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    for r in res:
+        y, dx, g = r[0]
+        assert np.array_equal(y, alone[0][0]) and np.array_equal(dx, alone[0][1])
+        for n in I.PARAM_NAMES:
+            assert np.array_equal(g[n], alone[0][2][n]), n
+
