@@ -37,6 +37,7 @@ struct TileLoader {
   static constexpr int PER = R * BK / (512 * NWAVES);
   unsigned base[PER];   // k-invariant part of the lane's element offset, or OOB
   int kc[PER];          // K-major: k offset of the chunk; MN-major: k-row of the chunk
+  unsigned voff[PER];   // the same as a byte offset (or OOB): the vector offset of the cheap form
   __amdgpu_buffer_rsrc_t rsrc;
   int ld, K;
 
@@ -55,6 +56,7 @@ struct TileLoader {
         const int c = (lane % CPR) ^ swz_k<BK>(r);
         kc[i] = c * 8;
         base[i] = (origin + r < extent) ? (unsigned)((origin + r) * ld + c * 8) : OOB;
+        voff[i] = (base[i] != OOB) ? base[i] * 2u : OOB;
       } else {
         constexpr int CPR = R / 8;                 // 16 B chunks per k-row
         constexpr int KPI = 64 / CPR;              // k-rows per instruction
@@ -62,19 +64,31 @@ struct TileLoader {
         const int c = (lane % CPR) ^ swz_mn(kr);
         kc[i] = kr;
         base[i] = (origin + c * 8 < extent) ? (unsigned)(kr * ld + origin + c * 8) : OOB;
+        voff[i] = (base[i] != OOB) ? base[i] * 2u : OOB;
       }
     }
   }
-  // issue this wave's share of the tile starting at reduction index k0 into LDS at `dst`
+  // instruction i of this wave's share of the tile that starts at reduction index k0, into LDS at
+  // `dst`; lanes beyond the operand or beyond K get zeros
+  GX_DEVINL void issue_one(char* dst, int k0, int wave, int i) const {
+    unsigned off;
+    if (KMAJOR) off = (base[i] != OOB && k0 + kc[i] < K) ? (base[i] + (unsigned)k0) * 2u : OOB;
+    else        off = (base[i] != OOB && k0 + kc[i] < K) ? (base[i] + (unsigned)(k0 * ld)) * 2u : OOB;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(dst + (wave * PER + i) * 1024), 16, off, 0, 0,
+                                             0);
+  }
   GX_DEVINL void issue(char* dst, int k0, int wave) const {
 #pragma unroll
-    for (int i = 0; i < PER; i++) {
-      unsigned off;
-      if (KMAJOR) off = (base[i] != OOB && k0 + kc[i] < K) ? (base[i] + (unsigned)k0) * 2u : OOB;
-      else        off = (base[i] != OOB && k0 + kc[i] < K) ? (base[i] + (unsigned)(k0 * ld)) * 2u : OOB;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(dst + (wave * PER + i) * 1024), 16, off, 0, 0,
-                                               0);
-    }
+    for (int i = 0; i < PER; i++) issue_one(dst, k0, wave, i);
+  }
+  // The cheap form, for a tile that lies wholly inside K: the tile's reduction index goes into the
+  // instruction's scalar offset (which takes no part in the range check, hence the condition) and
+  // the lane's vector offset never changes, so a load costs no vector arithmetic at all.
+  GX_DEVINL unsigned tile_offset(int k0) const { return KMAJOR ? (unsigned)k0 * 2u : (unsigned)(k0 * ld) * 2u; }
+  GX_DEVINL void issue_inside(char* dst, unsigned tile_off, int wave, int i) const {
+    unsigned off = voff[i];
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(dst + (wave * PER + i) * 1024), 16, off,
+                                             tile_off, 0, 0);
   }
 };
 
@@ -118,7 +132,6 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
   constexpr int TM = BM / 64, TN = BN / 128;          // 32x32 accumulators per wave
   constexpr int WM = BM / 2, WN = BN / 4;             // wave tile
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
-  constexpr bool SPLIT_B = (STAGES == 2) && ((LAY == LAY_NT) || BM == 256);
   constexpr int KS = BK / 16;
   static_assert(KS % 2 == 0, "fragment double buffer assumes an even number of sub-steps");
   const int lane = threadIdx.x & 63;
@@ -209,43 +222,89 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
     }
   };
 
-  if (STAGES == 2) {
-    // double buffer: one tile in flight, waited for completely at each hand-over
+  if constexpr (STAGES == 2) {
+    // Double buffer, written as a fixed sequence of slots: every matrix instruction is followed by
+    // at most one fragment read and one tile load, and a scheduling barrier on either side keeps
+    // the compiler from regrouping them.  Left to itself it gathers a tile's loads and their address
+    // arithmetic into one block behind the workgroup barrier, during which both wavefronts of a
+    // SIMD leave the matrix pipe idle at the same moment (measured: 2 - 8 % per product).
+    //   sub-steps 0 .. KS-2: products of sub-step ks, fragments of sub-step ks + 1 requested
+    //   sub-step KS-1:       wait for tile kt + 1, workgroup barrier, then the products, the first
+    //                        fragments of tile kt + 1, and tile kt + 2 into the stage just retired
+    constexpr int SL = TM * TN, NF = TM + TN;
+    constexpr int PER = TileLoader<A_K, BM, BK>::PER;
+    static_assert(TileLoader<B_K, BN, BK>::PER == PER && 2 * PER <= SL && NF <= SL, "slots of a sub-step");
+    auto request_one = [&](const char* ta, const char* tb, int ks, int buf, int j) {
+      if (j < TM) {
+        if (A_K) fa[buf][j].full = frag_k<BK>(ta, wm * WM + j * 32 + l32, ks, grp);
+        else     frag_mn_issue<BM>(ta, wm * WM + j * 32, ks, lane, fa[buf][j]);
+      } else {
+        const int ni = j - TM;
+        if (B_K) fb[buf][ni].full = frag_k<BK>(tb, wn * WN + ni * 32 + l32, ks, grp);
+        else     frag_mn_issue<BN>(tb, wn * WN + ni * 32, ks, lane, fb[buf][ni]);
+      }
+    };
+    auto tile = [&](int kt, const bool inside) __attribute__((always_inline)) {
+      const int cur = kt & 1;
+      const char* ta = sa + cur * A_BYTES;
+      const char* tb = sb + cur * B_BYTES;
+      const char* na = sa + (cur ^ 1) * A_BYTES;
+      const char* nb = sb + (cur ^ 1) * B_BYTES;
+      const unsigned offa = la.tile_offset((kt + 2) * BK), offb = lb.tile_offset((kt + 2) * BK);
+#pragma unroll
+      for (int ks = 0; ks < KS; ks++) {
+        const int buf = ks & 1;
+        bf16x8 af[TM], bfr[TN];
+        if (!A_K || !B_K || ks == KS - 1) lds_wait_all();
+#pragma unroll
+        for (int mi = 0; mi < TM; mi++) af[mi] = A_K ? fa[buf][mi].full : frag_mn_finish(fa[buf][mi]);
+#pragma unroll
+        for (int ni = 0; ni < TN; ni++) bfr[ni] = B_K ? fb[buf][ni].full : frag_mn_finish(fb[buf][ni]);
+        if (ks == KS - 1) {
+          // every LDS read of tile kt by this wavefront has completed (lds_wait_all)
+          __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's share of tile kt + 1 has landed
+          __syncthreads();
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int sl = 0; sl < SL; sl++) {
+          const int mi = sl / TN, ni = sl % TN;
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ni], af[mi], acc[mi][ni], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          if (sl < NF) {
+            // past the last tile this reads a stage that holds zeros or a stale tile; never used
+            if (ks + 1 < KS) request_one(ta, tb, ks + 1, buf ^ 1, sl);
+            else request_one(na, nb, 0, buf ^ 1, sl);
+          }
+          if (ks == KS - 1 && sl >= SL - 2 * PER) {
+            const int i = sl - (SL - 2 * PER);
+            if (inside) {
+              if (i < PER) la.issue_inside(sa + cur * A_BYTES, offa, wave, i);
+              else lb.issue_inside(sb + cur * B_BYTES, offb, wave, i - PER);
+            } else {
+              // a ragged last tile, or nothing at all beyond K (every lane out of range: zeros, no
+              // memory traffic)
+              if (i < PER) la.issue_one(sa + cur * A_BYTES, (kt + 2) * BK, wave, i);
+              else lb.issue_one(sb + cur * B_BYTES, (kt + 2) * BK, wave, i - PER);
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    };
     la.issue(sa, 0, wave);
     lb.issue(sb, 0, wave);
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's LDS-DMA has landed
     __syncthreads();
-    if (nk > 1) {
-      la.issue(sa + A_BYTES, BK, wave);
-      lb.issue(sb + B_BYTES, BK, wave);
-    }
+    la.issue(sa + A_BYTES, BK, wave);
+    lb.issue(sb + B_BYTES, BK, wave);
     request(sa, sb, 0, 0);
-    for (int kt = 0; kt < nk; kt++) {
-      const int cur = kt & 1;
-      const char* ta = sa + cur * A_BYTES;
-      const char* tb = sb + cur * B_BYTES;
-#pragma unroll
-      for (int ks = 0; ks < KS; ks++) {
-        substep(ks, [&](int buf) {
-          if (ks + 1 < KS) {
-            request(ta, tb, ks + 1, buf ^ 1);
-          } else {
-            // every LDS read of this tile by this wavefront has completed (lds_wait_all)
-            __builtin_amdgcn_s_waitcnt(0x0F70);
-            __syncthreads();
-            if (kt + 2 < nk) {
-              la.issue(sa + cur * A_BYTES, (kt + 2) * BK, wave);
-              if (!SPLIT_B) lb.issue(sb + cur * B_BYTES, (kt + 2) * BK, wave);
-            }
-            if (kt + 1 < nk) request(sa + (cur ^ 1) * A_BYTES, sb + (cur ^ 1) * B_BYTES, 0, buf ^ 1);
-          }
-          // the B half of a prefetch may go out one sub-step after the A half, so that the
-          // wavefronts of a SIMD do not all sit in the load issue queue at once
-          if (SPLIT_B && ks == 0 && kt >= 1 && kt + 1 < nk)
-            lb.issue(sb + (cur ^ 1) * B_BYTES, (kt + 1) * BK, wave);
-        });
-      }
-    }
+    const int ninside = max(0, g.K / BK - 2);   // tiles kt whose prefetch target kt + 2 lies wholly inside K
+    for (int kt = 0; kt < ninside; kt++) tile(kt, true);
+    for (int kt = ninside; kt < nk; kt++) tile(kt, false);
+    // the zero-fill requests of the last two tiles must have landed before the staging below reuses LDS
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
   } else {
     // ring of STAGES tiles, STAGES - 1 in flight.  Loads in flight are counted per wavefront, LPT
     // per tile; tiles beyond K are requested like any other (every lane out of range: zeros, no
