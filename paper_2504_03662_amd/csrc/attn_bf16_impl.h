@@ -38,6 +38,39 @@ GX_DEVINL void tile_load(__amdgpu_buffer_rsrc_t rsrc, unsigned elem0, int ld, in
   }
 }
 
+// The same load for a kernel that brings in many tiles of one column block: the lane's byte offsets
+// within a tile are worked out once, and a tile that lies wholly inside the rows puts its first
+// row into the instruction's scalar offset (which takes no part in the range check, hence the
+// condition), so that a load costs no vector arithmetic; a ragged last tile takes tile_load().
+template <int ROWS, int NW>
+struct TileStream {
+  static constexpr int RPI = 64 / CPR, PER_WAVE = ROWS / RPI / NW;
+  static_assert(PER_WAVE >= 1, "tile too small for the workgroup");
+  unsigned voff[PER_WAVE];
+  GX_DEVINL void init(unsigned elem0, int ld, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; i++) {
+      const int r = RPI * (wave * PER_WAVE + i) + lane / CPR;
+      const int c = (lane % CPR) ^ swz(r);
+      voff[i] = (elem0 + (unsigned)(r * ld + c * 8)) * 2u;
+    }
+  }
+  GX_DEVINL void load(__amdgpu_buffer_rsrc_t rsrc, unsigned elem0, int ld, int row0, int nrows, char* dst, int wave,
+                      int lane) const {
+    if (row0 + ROWS <= nrows) {
+      const unsigned so = (unsigned)(row0 * ld) * 2u;
+#pragma unroll
+      for (int i = 0; i < PER_WAVE; i++) {
+        unsigned off = voff[i];
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(dst + (wave * PER_WAVE + i) * 1024), 16, off,
+                                                 so, 0, 0);
+      }
+    } else {
+      tile_load<ROWS, NW>(rsrc, elem0, ld, row0, nrows, dst, wave, lane);
+    }
+  }
+};
+
 // MFMA operand whose 32 rows are tile rows r0..r0+31 and whose reduction index is the head
 // dimension (step s covers d = 16 s .. 16 s + 15)
 GX_DEVINL bf16x8 frag_rows(const char* tile, int r, int s, int g) {
@@ -175,6 +208,63 @@ GX_DEVINL unsigned long long keep_bits_of_step(const unsigned* row_words, int j0
   return row_words[j0 >> 5];
 }
 
+// End of a forward workgroup: merge the SPLIT partial softmax states of each row block through LDS
+// (the tiles are no longer needed), then normalise and store the block's rows of ctx and lse.
+template <int NQ, int SPLIT, bool DROP>
+GX_DEVINL void fwd_merge_store(char* smem, f32x16 (&o)[DH / 32], float m, float lsum, int part, int qs, int lane,
+                               int iw, int b, int h, int S, int nl, bf16* __restrict__ ctx,
+                               float* __restrict__ lse, const KeepArgs& keep) {
+  const int g = lane >> 5, l32 = lane & 31;
+  const int Hl = nl * DH;
+  if (SPLIT > 1) {
+    // merge the parts' partial softmax states; the tiles are no longer needed, so parts 1.. park
+    // (m, l, O) in LDS as [part - 1][row block][2 + DH / 2 values][64 lanes] and part 0 folds them
+    // in, in order.  A part that saw no key has m = -inf, l = 0, O = 0 and folds in as nothing
+    // (part 0 always saw key 0, so the merged maximum is finite).
+    constexpr int REGION = (2 + DH / 2) * 64;
+    if (part > 0) {
+      float* park = reinterpret_cast<float*>(smem) + ((part - 1) * NQ + qs) * REGION + lane;
+      park[0] = m;
+      park[64] = lsum;
+#pragma unroll
+      for (int dt = 0; dt < DH / 32; dt++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) park[(2 + 16 * dt + v) * 64] = o[dt][v];
+    }
+    __syncthreads();
+    if (part > 0) return;
+#pragma unroll
+    for (int pp = 1; pp < SPLIT; pp++) {
+      const float* park = reinterpret_cast<const float*>(smem) + ((pp - 1) * NQ + qs) * REGION + lane;
+      const float m1 = park[0], l1 = park[64];
+      const float mm = fmaxf(m, m1);
+      const float a0 = __builtin_amdgcn_exp2f(m - mm), a1 = __builtin_amdgcn_exp2f(m1 - mm);
+      lsum = lsum * a0 + l1 * a1;
+      m = mm;
+#pragma unroll
+      for (int dt = 0; dt < DH / 32; dt++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) o[dt][v] = o[dt][v] * a0 + park[(2 + 16 * dt + v) * 64] * a1;
+    }
+  }
+  lsum += __shfl_xor(lsum, 32, 64);
+  const int i = iw + l32;
+  if (i < S) {
+    const float inv = (DROP ? keep.scale : 1.0f) / lsum;
+    bf16* orow = ctx + ((size_t)b * S + i) * Hl + h * DH;
+#pragma unroll
+    for (int dt = 0; dt < DH / 32; dt++)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; q4++) {
+        bf16x4 pk;
+#pragma unroll
+        for (int e = 0; e < 4; e++) pk[e] = (bf16)(o[dt][4 * q4 + e] * inv);
+        *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * q4 + 4 * g) = pk;
+      }
+    if (g == 0) lse[((size_t)b * nl + h) * S + i] = (m + __builtin_amdgcn_logf(lsum)) * LN2;
+  }
+}
+
 template <int NQ, int SPLIT, int BKV, bool DROP>
 __global__ void __launch_bounds__(64 * NQ * SPLIT, NQ * SPLIT == 4 ? 2 : 1)
     attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ ctx, float* __restrict__ lse, int S, int nl,
@@ -285,53 +375,159 @@ __global__ void __launch_bounds__(64 * NQ * SPLIT, NQ * SPLIT == 4 ? 2 : 1)
     WAIT_VM0();
     __syncthreads();
   }
-  if (SPLIT > 1) {
-    // merge the parts' partial softmax states; the tiles are no longer needed, so parts 1.. park
-    // (m, l, O) in LDS as [part - 1][row block][2 + DH / 2 values][64 lanes] and part 0 folds them
-    // in, in order.  A part that saw no key has m = -inf, l = 0, O = 0 and folds in as nothing
-    // (part 0 always saw key 0, so the merged maximum is finite).
-    constexpr int REGION = (2 + DH / 2) * 64;
-    if (part > 0) {
-      float* park = reinterpret_cast<float*>(smem) + ((part - 1) * NQ + qs) * REGION + lane;
-      park[0] = m;
-      park[64] = lsum;
+  fwd_merge_store<NQ, SPLIT, DROP>(smem, o, m, lsum, part, qs, lane, iw, b, h, S, nl, ctx, lse, keep);
+}
+
+// The split-key shape of the forward pass with the scores one step ahead: while the softmax of step
+// t runs on the vector units, the same wavefront's matrix instructions already compute the scores
+// of step t + 1 (one matrix instruction, then a share of the softmax, kept in that order by
+// scheduling barriers).  The two wavefronts of a SIMD pass the workgroup barrier together and so
+// are in the same phase of a step at the same time; without the interleave inside a wavefront the
+// matrix pipe idles through both softmaxes and the vector units through both score products.
+// K and V have separate double buffers because K runs a step ahead of V: at the top of step t,
+// K(t + 2) goes into the buffer of K(t) (its scores were taken during step t - 1) and V(t + 1)
+// into the buffer of V(t - 1).
+template <int NQ, int SPLIT, bool DROP>
+__global__ void __launch_bounds__(64 * NQ * SPLIT, 1)
+    attn_fwd_ahead_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ ctx, float* __restrict__ lse, int S,
+                          int nl, int npair, unsigned qkv_bytes, KeepArgs keep) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  constexpr int NW = NQ * SPLIT, BQ = 32 * NQ, BKV = 32, ROWS = BKV * SPLIT, TILE = ROWS * ROWB, NS = DH / 16;
+  static_assert((NQ & (NQ - 1)) == 0 && SPLIT > 1, "shape of the step");
+  static_assert((SPLIT - 1) * NQ * (2 + DH / 2) * 256 <= 4 * TILE, "merge area fits the tile buffers");
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int qs = wave % NQ, part = wave / NQ;
+  const int g = lane >> 5, l32 = lane & 31;
+  const int nq = (S + BQ - 1) / BQ;
+  const int pair = blockIdx.x % npair;
+  const int qt = nq - 1 - blockIdx.x / npair;         // longest rows first
+  const int h = pair % nl, b = pair / nl;
+  const int Hl = nl * DH, ld = 3 * Hl;
+  const int i0 = qt * BQ, iw = i0 + qs * 32;          // this wave's first query row
+  const unsigned eq = (unsigned)((size_t)b * S * ld + h * DH);
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(qkv), 0, qkv_bytes,
+                                                                        0x00020000);
+  bf16x8 qf[NS];
+  load_row_frags(qkv + eq, ld, iw + l32, S, g, qf);
+
+  f32x16 o[DH / 32];
 #pragma unroll
-      for (int dt = 0; dt < DH / 32; dt++)
+  for (int dt = 0; dt < DH / 32; dt++) o[dt] = zero16();
+  float m = -INFINITY, lsum = 0.f;
+  const float c2 = rsqrtf((float)DH) * LOG2E;
+  constexpr float MAX_SLACK = 8.0f;
+  unsigned coff[2][DH / 32];
+  cols_lane_offsets(lane, coff);
+
+  char* const kst = smem;                             // K(t) at kst + (t & 1) * TILE
+  char* const vst = smem + 2 * TILE;                  // V(t) at vst + (t & 1) * TILE
+  const int jend = min(S, i0 + BQ);                   // keys 0 .. jend-1 can be visible
+  const int nt = (jend + ROWS - 1) / ROWS;
+  TileStream<ROWS, NW> ksrc, vsrc;
+  ksrc.init(eq + Hl, ld, wave, lane);
+  vsrc.init(eq + 2 * Hl, ld, wave, lane);
+  ksrc.load(rsrc, eq + Hl, ld, 0, S, kst, wave, lane);
+  vsrc.load(rsrc, eq + 2 * Hl, ld, 0, S, vst, wave, lane);
+  if (nt > 1) ksrc.load(rsrc, eq + Hl, ld, ROWS, S, kst + TILE, wave, lane);
+  WAIT_VM0();
+  __syncthreads();
+  // scores of step 0; a wavefront's keys of a step are visible when the step's first key is at or
+  // before the wavefront's last row (wave-uniform; both are multiples of 32 up to the 31)
+  f32x16 s_even = zero16(), s_odd;
+  if (part * BKV <= iw + 31) {
+    const char* k0 = kst + part * BKV * ROWB;
 #pragma unroll
-        for (int v = 0; v < 16; v++) park[(2 + 16 * dt + v) * 64] = o[dt][v];
-    }
-    __syncthreads();
-    if (part > 0) return;
-#pragma unroll
-    for (int pp = 1; pp < SPLIT; pp++) {
-      const float* park = reinterpret_cast<const float*>(smem) + ((pp - 1) * NQ + qs) * REGION + lane;
-      const float m1 = park[0], l1 = park[64];
-      const float mm = fmaxf(m, m1);
-      const float a0 = __builtin_amdgcn_exp2f(m - mm), a1 = __builtin_amdgcn_exp2f(m1 - mm);
-      lsum = lsum * a0 + l1 * a1;
-      m = mm;
-#pragma unroll
-      for (int dt = 0; dt < DH / 32; dt++)
-#pragma unroll
-        for (int v = 0; v < 16; v++) o[dt][v] = o[dt][v] * a0 + park[(2 + 16 * dt + v) * 64] * a1;
-    }
+    for (int s = 0; s < NS; s++) s_even = MFMA(frag_rows(k0, l32, s, g), qf[s], s_even);
   }
-  lsum += __shfl_xor(lsum, 32, 64);
-  const int i = iw + l32;
-  if (i < S) {
-    const float inv = (DROP ? keep.scale : 1.0f) / lsum;
-    bf16* orow = ctx + ((size_t)b * S + i) * Hl + h * DH;
+  // one step: `sacc` holds the scores of step t on entry, `snxt` those of step t + 1 on exit
+  auto step = [&](int t, f32x16& sacc, f32x16& snxt) __attribute__((always_inline)) {
+    if (t + 2 < nt) ksrc.load(rsrc, eq + Hl, ld, (t + 2) * ROWS, S, kst + (t & 1) * TILE, wave, lane);
+    if (t + 1 < nt) vsrc.load(rsrc, eq + 2 * Hl, ld, (t + 1) * ROWS, S, vst + ((t + 1) & 1) * TILE, wave, lane);
+    const int j0 = t * ROWS + part * BKV;              // this wave's keys of the step
+    if (j0 <= iw + 31) {
+      // Scores of the next step are always taken, also when that step does not exist or is not
+      // visible to this wavefront: the buffer then holds an older tile (or nothing yet), the
+      // products are never looked at, and the loop body stays free of a second code path.
+      const char* kn = kst + ((t + 1) & 1) * TILE + part * BKV * ROWB;
+      const char* vt = vst + (t & 1) * TILE + part * BKV * ROWB;
+      unsigned long long kw = ~0ull;                    // keep bits of this query's keys of the step
+      if (DROP && iw + l32 < S)
+        kw = keep_bits_of_step<1>(keep.bits + (((size_t)b * nl + h) * S + iw + l32) * keep.wpr, j0);
+      bf16x8 kf[NS];
 #pragma unroll
-    for (int dt = 0; dt < DH / 32; dt++)
+      for (int s = 0; s < NS; s++) kf[s] = frag_rows(kn, l32, s, g);
+      snxt = zero16();
+      const int i = iw + l32;
+      float psum = 0.f;
+      // the softmax of step t for query column i (base-2 exponentials, scale folded into the
+      // exponent's multiply-add), cut into pieces
+      auto piece = [&](int k) __attribute__((always_inline)) {
+        if (k == 0) {
+          if (j0 + BKV - 1 > iw) {                     // the tile touches the diagonal
 #pragma unroll
-      for (int q4 = 0; q4 < 4; q4++) {
-        bf16x4 pk;
+            for (int v = 0; v < 16; v++)
+              if (j0 + 8 * (v >> 2) + 4 * g + (v & 3) > i) sacc[v] = -INFINITY;
+          }
+        } else if (k == 1) {
+          float mloc = sacc[0];
 #pragma unroll
-        for (int e = 0; e < 4; e++) pk[e] = (bf16)(o[dt][4 * q4 + e] * inv);
-        *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * q4 + 4 * g) = pk;
+          for (int v = 1; v < 16; v++) mloc = fmaxf(mloc, sacc[v]);
+          mloc = max_across_halves(mloc) * c2;
+          // The reference maximum m follows the true one lazily: it moves only when some row's new
+          // maximum exceeds it by more than MAX_SLACK (wave-uniform), so exponentials stay below
+          // 2^MAX_SLACK and the rescaling of O, four multiplies per score, becomes rare.  Any
+          // reference gives the same softmax up to rounding; lse = m + log2(l) is exact for any m.
+          if (__builtin_amdgcn_ballot_w64(mloc > m + MAX_SLACK)) {
+            const float mnew = fmaxf(m, mloc);
+            const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+            m = mnew;
+            lsum *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < DH / 32; dt++)
+#pragma unroll
+              for (int v = 0; v < 16; v++) o[dt][v] *= alpha;
+          }
+        } else if (k >= 2 && k < 6) {
+#pragma unroll
+          for (int v = 4 * (k - 2); v < 4 * (k - 2) + 4; v++) {
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[v], c2, -m));
+            sacc[v] = p;
+            psum += p;
+          }
+        }
+      };
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int s = 0; s < NS; s++) {
+        snxt = MFMA(kf[s], qf[s], snxt);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int k = 0; k < 8; k++)
+          if (k * NS / 8 == s) piece(k);
+        __builtin_amdgcn_sched_barrier(0);
       }
-    if (g == 0) lse[((size_t)b * nl + h) * S + i] = (m + __builtin_amdgcn_logf(lsum)) * LN2;
+      // transposed V fragments travel while the probabilities are rounded
+      const unsigned ct = lds_addr(vt);
+      ColFrags cf[2];
+      cols_issue<0>(ct, coff, cf[0]);
+      cols_issue<1>(ct, coff, cf[1]);
+      lsum += psum;
+      f32x16 pacc[1] = {sacc};
+      if (DROP) drop_unkept<1>(pacc, kw, g);           // the row sum above is the undropped one
+      // O^T += V^T P^T, 16 keys per group
+      bf16x8 pf[2];
+#pragma unroll
+      for (int u = 0; u < 2; u++) pf[u] = pack_half(pacc[0], u);
+      tr_product<true, 2>(o, ct, coff, cf, pf);
+    }
+    WAIT_VM0();
+    __syncthreads();
+  };
+  for (int t = 0; t < nt; t += 2) {
+    step(t, s_even, s_odd);
+    if (t + 1 < nt) step(t + 1, s_odd, s_even);
   }
+  fwd_merge_store<NQ, SPLIT, DROP>(smem, o, m, lsum, part, qs, lane, iw, b, h, S, nl, ctx, lse, keep);
 }
 
 // ------------------------------------------------------------------------------- backward: D
@@ -739,9 +935,9 @@ hipError_t fwd(const AttnArgs& a, hipStream_t s) {
   static bool configured = false;
   if (!configured) {
     hipError_t e = set_smem(attn_fwd_kernel<4, 1, 64, false>, SMEM_MANY);
-    if (e == hipSuccess) e = set_smem(attn_fwd_kernel<2, 4, 32, false>, SMEM_FEW);
+    if (e == hipSuccess) e = set_smem(attn_fwd_ahead_kernel<2, 4, false>, SMEM_FEW);
     if (e == hipSuccess) e = set_smem(attn_fwd_kernel<4, 1, 64, true>, SMEM_MANY);
-    if (e == hipSuccess) e = set_smem(attn_fwd_kernel<2, 4, 32, true>, SMEM_FEW);
+    if (e == hipSuccess) e = set_smem(attn_fwd_ahead_kernel<2, 4, true>, SMEM_FEW);
     if (e != hipSuccess) return e;
     configured = true;
   }
@@ -755,8 +951,8 @@ hipError_t fwd(const AttnArgs& a, hipStream_t s) {
                        a.lse, a.S, a.nl, npair, qkv_bytes, keep);
   };
   if (few_pairs(a)) {
-    if (drop) go(attn_fwd_kernel<2, 4, 32, true>, 64, 512, SMEM_FEW);
-    else go(attn_fwd_kernel<2, 4, 32, false>, 64, 512, SMEM_FEW);
+    if (drop) go(attn_fwd_ahead_kernel<2, 4, true>, 64, 512, SMEM_FEW);
+    else go(attn_fwd_ahead_kernel<2, 4, false>, 64, 512, SMEM_FEW);
   } else {
     if (drop) go(attn_fwd_kernel<4, 1, 64, true>, 128, 256, SMEM_MANY);
     else go(attn_fwd_kernel<4, 1, 64, false>, 128, 256, SMEM_MANY);

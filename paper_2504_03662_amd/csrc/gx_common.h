@@ -88,6 +88,14 @@ GX_DEVINL bf16x4 lds_read_tr_issue(unsigned addr) {
   asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF) : "memory");
   return r;
 }
+// maximum of a value over lanes l and l ^ 32 (the two halves of a wavefront), in every lane, by one
+// v_permlane32_swap instead of a round trip through the LDS crossbar: the swap of two copies of x
+// leaves (low half, low half) in one register and (high half, high half) in the other
+GX_DEVINL float max_across_halves(float x) {
+  const unsigned u = __builtin_bit_cast(unsigned, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+}
 GX_DEVINL void lds_wait_all() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 // wait until at most N LDS operations of this wavefront are outstanding (they complete in order)
 template <int N>
