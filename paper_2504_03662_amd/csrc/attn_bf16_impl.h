@@ -388,7 +388,7 @@ __global__ void __launch_bounds__(64 * NQ * SPLIT, NQ * SPLIT == 4 ? 2 : 1)
 // K(t + 2) goes into the buffer of K(t) (its scores were taken during step t - 1) and V(t + 1)
 // into the buffer of V(t - 1).
 template <int NQ, int SPLIT, bool DROP>
-__global__ void __launch_bounds__(64 * NQ * SPLIT, 1)
+__global__ void __launch_bounds__(64 * NQ * SPLIT, NQ * SPLIT == 4 ? 2 : 1)
     attn_fwd_ahead_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ ctx, float* __restrict__ lse, int S,
                           int nl, int npair, unsigned qkv_bytes, KeepArgs keep) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -400,7 +400,11 @@ __global__ void __launch_bounds__(64 * NQ * SPLIT, 1)
   const int g = lane >> 5, l32 = lane & 31;
   const int nq = (S + BQ - 1) / BQ;
   const int pair = blockIdx.x % npair;
-  const int qt = nq - 1 - blockIdx.x / npair;         // longest rows first
+  // First half of the launch: longest blocks first; second half: shortest first.  With two
+  // workgroups per compute unit and a launch of twice the number of units, workgroups x and
+  // x + gridDim.x / 2 tend to share a unit, and their causal work then adds up to the same total.
+  const int rq = blockIdx.x / npair, hq = (nq + 1) / 2;
+  const int qt = rq < hq ? nq - 1 - rq : rq - hq;
   const int h = pair % nl, b = pair / nl;
   const int Hl = nl * DH, ld = 3 * Hl;
   const int i0 = qt * BQ, iw = i0 + qs * 32;          // this wave's first query row
@@ -792,7 +796,10 @@ __global__ void __launch_bounds__(64 * NQ * SPLIT, NQ * SPLIT == 4 ? 2 : 1)
   const int g = lane >> 5, l32 = lane & 31;
   const int nq = (S + BQ - 1) / BQ;
   const int pair = blockIdx.x % npair;
-  const int qt = nq - 1 - blockIdx.x / npair;
+  // longest blocks first; with two workgroups per compute unit (4 wavefronts each), the second
+  // half of the launch runs shortest first, as in the forward kernel
+  const int rq = blockIdx.x / npair, hq = (nq + 1) / 2;
+  const int qt = (NW == 4 && rq >= hq) ? rq - hq : nq - 1 - rq;
   const int h = pair % nl, b = pair / nl;
   const int Hl = nl * DH, ld = 3 * Hl;
   const int i0 = qt * BQ, iw = i0 + qs * 32;
@@ -935,9 +942,9 @@ hipError_t fwd(const AttnArgs& a, hipStream_t s) {
   static bool configured = false;
   if (!configured) {
     hipError_t e = set_smem(attn_fwd_kernel<4, 1, 64, false>, SMEM_MANY);
-    if (e == hipSuccess) e = set_smem(attn_fwd_ahead_kernel<2, 4, false>, SMEM_FEW);
+    if (e == hipSuccess) e = set_smem(attn_fwd_ahead_kernel<2, 2, false>, SMEM_FEW / 2);
     if (e == hipSuccess) e = set_smem(attn_fwd_kernel<4, 1, 64, true>, SMEM_MANY);
-    if (e == hipSuccess) e = set_smem(attn_fwd_ahead_kernel<2, 4, true>, SMEM_FEW);
+    if (e == hipSuccess) e = set_smem(attn_fwd_ahead_kernel<2, 2, true>, SMEM_FEW / 2);
     if (e != hipSuccess) return e;
     configured = true;
   }
@@ -951,8 +958,8 @@ hipError_t fwd(const AttnArgs& a, hipStream_t s) {
                        a.lse, a.S, a.nl, npair, qkv_bytes, keep);
   };
   if (few_pairs(a)) {
-    if (drop) go(attn_fwd_ahead_kernel<2, 4, true>, 64, 512, SMEM_FEW);
-    else go(attn_fwd_ahead_kernel<2, 4, false>, 64, 512, SMEM_FEW);
+    if (drop) go(attn_fwd_ahead_kernel<2, 2, true>, 64, 256, SMEM_FEW / 2);
+    else go(attn_fwd_ahead_kernel<2, 2, false>, 64, 256, SMEM_FEW / 2);
   } else {
     if (drop) go(attn_fwd_kernel<4, 1, 64, true>, 128, 256, SMEM_MANY);
     else go(attn_fwd_kernel<4, 1, 64, false>, 128, 256, SMEM_MANY);
@@ -971,9 +978,9 @@ hipError_t bwd(const AttnArgs& a, hipStream_t s, hipStream_t s_dq, hipEvent_t fo
     hipError_t e = set_smem(attn_bwd_dkv_kernel<false>, KV_SMEM);
     if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel<true>, KV_SMEM);
     if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<4, 1, 64, false>, SMEM_MANY);
-    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<2, 4, 32, false>, SMEM_FEW);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<2, 2, 32, false>, SMEM_FEW / 2);
     if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<4, 1, 64, true>, SMEM_MANY);
-    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<2, 4, 32, true>, SMEM_FEW);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<2, 2, 32, true>, SMEM_FEW / 2);
     if (e != hipSuccess) return e;
     configured = true;
   }
@@ -1006,8 +1013,8 @@ hipError_t bwd(const AttnArgs& a, hipStream_t s, hipStream_t s_dq, hipEvent_t fo
                        (const bf16*)a.dctx, a.lse, a.dsum, (bf16*)a.dqkv, a.S, a.nl, npair, qkv_bytes, keep_rows);
   };
   if (few_pairs(a)) {
-    if (drop) go_dq(attn_bwd_dq_kernel<2, 4, 32, true>, 64, 512, SMEM_FEW);
-    else go_dq(attn_bwd_dq_kernel<2, 4, 32, false>, 64, 512, SMEM_FEW);
+    if (drop) go_dq(attn_bwd_dq_kernel<2, 2, 32, true>, 64, 256, SMEM_FEW / 2);
+    else go_dq(attn_bwd_dq_kernel<2, 2, 32, false>, 64, 256, SMEM_FEW / 2);
   } else {
     if (drop) go_dq(attn_bwd_dq_kernel<4, 1, 64, true>, 128, 256, SMEM_MANY);
     else go_dq(attn_bwd_dq_kernel<4, 1, 64, false>, 128, 256, SMEM_MANY);
