@@ -176,9 +176,13 @@ GX_DEVINL void tr_product4(f32x16 (&acc)[DH / 32], unsigned ct, const unsigned (
 // into LDS and wavefront (q, part) works on tile `part`; the SPLIT partial softmax states
 // (max, sum, O) of a row block are merged through LDS at the end, in the order of `part`.
 //   many (sample, head) pairs : NQ 4, SPLIT 1, BKV 64 (4 wavefronts, two workgroups per compute unit)
-//   few pairs                 : NQ 2, SPLIT 4, BKV 32 (8 wavefronts): the causal triangle gives query
-//     blocks between 1 and S / 32 NQ units of work, so with few pairs the chip is filled by short
-//     blocks cut fine, each with its keys spread over four wavefronts.
+//   few pairs                 : NQ 2, SPLIT 2, BKV 32 (4 wavefronts, two workgroups per compute unit;
+//     the forward pass in the kernel after this one): the causal triangle gives query blocks
+//     between 1 and S / 32 NQ units of work, so with few pairs the chip is filled by short blocks
+//     cut fine, each with its keys spread over two wavefronts.  Two independent workgroups per
+//     unit matter more than wavefronts per workgroup: the wavefronts of one workgroup pass every
+//     step's barrier together and are then all in the matrix pipe or all in the vector units at
+//     once, while two workgroups drift apart and fill each other's gaps.
 // Workgroups are numbered longest query block first over the whole launch (all pairs' last blocks,
 // then all pairs' next-to-last blocks, ...): the hardware hands them out in that order.
 // Dropout of the probabilities: keep bits (1 = kept) of the whole launch, `wpr` 32-bit words per
@@ -931,20 +935,21 @@ bool attn_shape_ok(const AttnArgs& a) {
 }
 
 // With few (sample, head) pairs the chip is filled by cutting the query blocks fine and spreading
-// each block's keys over four wavefronts (see the forward kernel).
+// each block's keys over two wavefronts (see the forward kernel).
 bool few_pairs(const AttnArgs& a) { return (long)a.B * a.nl * cdiv(a.S, 128) <= 384; }
 
-// row-block kernels (forward, dQ) in their two shapes: <4, 1, 64> with 4 wavefronts and <2, 4, 32> with 8
-constexpr int SMEM_MANY = 2 * 2 * 64 * ROWB, SMEM_FEW = 2 * 2 * 128 * ROWB;
+// row-block kernels (forward, dQ) in their two shapes, <4, 1, 64> and <2, 2, 32>: both 4 wavefronts
+// and two stages of 64 rows of K and of V
+constexpr int SMEM_MANY = 2 * 2 * 64 * ROWB, SMEM_FEW = 2 * 2 * 64 * ROWB;
 
 hipError_t fwd(const AttnArgs& a, hipStream_t s) {
   if (!attn_shape_ok(a)) return hipErrorInvalidValue;
   static bool configured = false;
   if (!configured) {
     hipError_t e = set_smem(attn_fwd_kernel<4, 1, 64, false>, SMEM_MANY);
-    if (e == hipSuccess) e = set_smem(attn_fwd_ahead_kernel<2, 2, false>, SMEM_FEW / 2);
+    if (e == hipSuccess) e = set_smem(attn_fwd_ahead_kernel<2, 2, false>, SMEM_FEW);
     if (e == hipSuccess) e = set_smem(attn_fwd_kernel<4, 1, 64, true>, SMEM_MANY);
-    if (e == hipSuccess) e = set_smem(attn_fwd_ahead_kernel<2, 2, true>, SMEM_FEW / 2);
+    if (e == hipSuccess) e = set_smem(attn_fwd_ahead_kernel<2, 2, true>, SMEM_FEW);
     if (e != hipSuccess) return e;
     configured = true;
   }
@@ -958,8 +963,8 @@ hipError_t fwd(const AttnArgs& a, hipStream_t s) {
                        a.lse, a.S, a.nl, npair, qkv_bytes, keep);
   };
   if (few_pairs(a)) {
-    if (drop) go(attn_fwd_ahead_kernel<2, 2, true>, 64, 256, SMEM_FEW / 2);
-    else go(attn_fwd_ahead_kernel<2, 2, false>, 64, 256, SMEM_FEW / 2);
+    if (drop) go(attn_fwd_ahead_kernel<2, 2, true>, 64, 256, SMEM_FEW);
+    else go(attn_fwd_ahead_kernel<2, 2, false>, 64, 256, SMEM_FEW);
   } else {
     if (drop) go(attn_fwd_kernel<4, 1, 64, true>, 128, 256, SMEM_MANY);
     else go(attn_fwd_kernel<4, 1, 64, false>, 128, 256, SMEM_MANY);
@@ -978,9 +983,9 @@ hipError_t bwd(const AttnArgs& a, hipStream_t s, hipStream_t s_dq, hipEvent_t fo
     hipError_t e = set_smem(attn_bwd_dkv_kernel<false>, KV_SMEM);
     if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel<true>, KV_SMEM);
     if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<4, 1, 64, false>, SMEM_MANY);
-    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<2, 2, 32, false>, SMEM_FEW / 2);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<2, 2, 32, false>, SMEM_FEW);
     if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<4, 1, 64, true>, SMEM_MANY);
-    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<2, 2, 32, true>, SMEM_FEW / 2);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<2, 2, 32, true>, SMEM_FEW);
     if (e != hipSuccess) return e;
     configured = true;
   }
@@ -1013,8 +1018,8 @@ hipError_t bwd(const AttnArgs& a, hipStream_t s, hipStream_t s_dq, hipEvent_t fo
                        (const bf16*)a.dctx, a.lse, a.dsum, (bf16*)a.dqkv, a.S, a.nl, npair, qkv_bytes, keep_rows);
   };
   if (few_pairs(a)) {
-    if (drop) go_dq(attn_bwd_dq_kernel<2, 2, 32, true>, 64, 256, SMEM_FEW / 2);
-    else go_dq(attn_bwd_dq_kernel<2, 2, 32, false>, 64, 256, SMEM_FEW / 2);
+    if (drop) go_dq(attn_bwd_dq_kernel<2, 2, 32, true>, 64, 256, SMEM_FEW);
+    else go_dq(attn_bwd_dq_kernel<2, 2, 32, false>, 64, 256, SMEM_FEW);
   } else {
     if (drop) go_dq(attn_bwd_dq_kernel<4, 1, 64, true>, 128, 256, SMEM_MANY);
     else go_dq(attn_bwd_dq_kernel<4, 1, 64, false>, 128, 256, SMEM_MANY);
