@@ -374,8 +374,30 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
   // one writer.
   static_assert(WM % 64 == 0, "column-sum blocks of 64 rows");
   float cs[4] = {0.f, 0.f, 0.f, 0.f};
+  // What an epilogue reads besides the accumulators (the residual, gelu'(z), the weight gradient
+  // being added to) is fetched one 32-row block ahead, all of a block's loads together.  Written
+  // as load - use - store per row, every load sits behind the previous row's store (the compiler
+  // cannot know that the two tensors do not overlap) and the epilogue pays a memory latency per
+  // row: 52 k cycles instead of 11 k for the residual form.
+  constexpr bool SIDE16 = (EPI == EPI_RESID || EPI == EPI_DGELU), SIDE32 = (EPI == EPI_F32_ACC);
+  constexpr int NJ = 32 / RPI;
+  const bf16* side16 = (EPI == EPI_RESID) ? resid : zin;
+  bf16x4 s16[2][SIDE16 ? NJ : 1];
+  f32x4 s32[2][SIDE32 ? NJ : 1];
+  auto fetch = [&](int mi, int buf) {
+#pragma unroll
+    for (int j = 0; j < NJ; j++) {
+      const int row = m0 + wm * WM + mi * 32 + RPI * j + lane / LPR;
+      if (row >= g.M || ecol >= g.N) continue;
+      const size_t idx = (size_t)row * g.ldc + ecol;
+      if (SIDE16) s16[buf][j] = *reinterpret_cast<const bf16x4*>(side16 + idx);
+      if (SIDE32) s32[buf][j] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(g.C) + idx);
+    }
+  };
+  if (SIDE16 || SIDE32) fetch(0, 0);
 #pragma unroll
   for (int mi = 0; mi < TM; mi++) {
+    if ((SIDE16 || SIDE32) && mi + 1 < TM) fetch(mi + 1, (mi + 1) & 1);
 #pragma unroll
     for (int ni = 0; ni < TN; ni++)
 #pragma unroll
@@ -396,7 +418,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
         *reinterpret_cast<f32x4*>(static_cast<float*>(g.C) + idx) = f32x4{x[0], x[1], x[2], x[3]};
       } else if (EPI == EPI_F32_ACC) {
         f32x4* cp = reinterpret_cast<f32x4*>(static_cast<float*>(g.C) + idx);
-        const f32x4 old = *cp;
+        const f32x4 old = s32[mi & 1][j];
         *cp = f32x4{old[0] + x[0], old[1] + x[1], old[2] + x[2], old[3] + x[3]};
       } else {
         bf16x4 o;
@@ -406,7 +428,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
             for (int e = 0; e < 4; e++) o[e] = (bf16)x[e];
             *reinterpret_cast<bf16x4*>(aux + idx) = o;
           }
-          const bf16x4 rv = *reinterpret_cast<const bf16x4*>(resid + idx);
+          const bf16x4 rv = s16[mi & 1][j];
 #pragma unroll
           for (int e = 0; e < 4; e++) x[e] += (float)rv[e];
         } else if (EPI == EPI_GELU) {
@@ -421,7 +443,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
           }
           *reinterpret_cast<bf16x4*>(aux + idx) = ga;
         } else if (EPI == EPI_DGELU) {
-          const bf16x4 zv = *reinterpret_cast<const bf16x4*>(zin + idx);
+          const bf16x4 zv = s16[mi & 1][j];
 #pragma unroll
           for (int e = 0; e < 4; e++) x[e] *= (float)zv[e];
         }
