@@ -174,6 +174,50 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
 
+  // Epilogue set-up; it sits ahead of the K loop because the first block of what the epilogue
+  // reads is requested two tiles before the loop ends.
+  const bf16* bias = static_cast<const bf16*>(g.bias);
+  const bf16* resid = static_cast<const bf16*>(g.resid);
+  const bf16* zin = static_cast<const bf16*>(g.z);
+  bf16* aux = static_cast<bf16*>(g.aux);
+  constexpr int EPAD = WN + 4;
+  constexpr int LPR = WN / 4;                          // lanes per row when reading back
+  constexpr int RPI = 64 / LPR;                        // rows per read instruction
+  float* stage = reinterpret_cast<float*>(smem + wave * (32 * EPAD * 4));
+  const int ecol = n0 + wn * WN + 4 * (lane % LPR);
+  float bv[4] = {0.f, 0.f, 0.f, 0.f};
+  if ((EPI == EPI_BIAS || EPI == EPI_RESID || EPI == EPI_GELU) && bias && ecol < g.N) {
+    const bf16x4 b4 = *reinterpret_cast<const bf16x4*>(bias + ecol);
+#pragma unroll
+    for (int e = 0; e < 4; e++) bv[e] = (float)b4[e];
+  }
+  // EPI_DGELU may also leave partial column sums of what it stores (stage 1 of the bias gradient of
+  // the product that made z): a wavefront's rows split into blocks of 64 (two 32-row passes), each
+  // lane adds its rows of a block, lanes that share columns combine by shuffles, and the block's
+  // sums go to colpart[(m0 + wave row) / 64 + block][column].  Every (block, column) has exactly
+  // one writer.
+  static_assert(WM % 64 == 0, "column-sum blocks of 64 rows");
+  float cs[4] = {0.f, 0.f, 0.f, 0.f};
+  // What an epilogue reads besides the accumulators (the residual, gelu'(z), the weight gradient
+  // being added to) is fetched one 32-row block ahead, all of a block's loads together.  Written
+  // as load - use - store per row, every load sits behind the previous row's store (the compiler
+  // cannot know that the two tensors do not overlap) and the epilogue pays a memory latency per
+  // row: 52 k cycles instead of 11 k for the residual form.
+  constexpr bool SIDE16 = (EPI == EPI_RESID || EPI == EPI_DGELU), SIDE32 = (EPI == EPI_F32_ACC);
+  constexpr int NJ = 32 / RPI;
+  const bf16* side16 = (EPI == EPI_RESID) ? resid : zin;
+  bf16x4 s16[2][SIDE16 ? NJ : 1];
+  f32x4 s32[2][SIDE32 ? NJ : 1];
+  auto fetch = [&](int mi, int buf) {
+#pragma unroll
+    for (int j = 0; j < NJ; j++) {
+      const int row = m0 + wm * WM + mi * 32 + RPI * j + lane / LPR;
+      if (row >= g.M || ecol >= g.N) continue;
+      const size_t idx = (size_t)row * g.ldc + ecol;
+      if (SIDE16) s16[buf][j] = *reinterpret_cast<const bf16x4*>(side16 + idx);
+      if (SIDE32) s32[buf][j] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(g.C) + idx);
+    }
+  };
   char* sa = smem;                       // A[STAGES]
   char* sb = smem + STAGES * A_BYTES;    // B[STAGES]
   const int nk = (g.K + BK - 1) / BK;
@@ -301,6 +345,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
     request(sa, sb, 0, 0);
     const int ninside = max(0, g.K / BK - 2);   // tiles kt whose prefetch target kt + 2 lies wholly inside K
     for (int kt = 0; kt < ninside; kt++) tile(kt, true);
+    if (SIDE16 || SIDE32) fetch(0, 0);
     for (int kt = ninside; kt < nk; kt++) tile(kt, false);
     // the zero-fill requests of the last two tiles must have landed before the staging below reuses LDS
     __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -339,6 +384,7 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
         });
       }
     }
+    if (SIDE16 || SIDE32) fetch(0, 0);
     // the zero-fill requests of the tail must have landed before the staging below reuses LDS
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
@@ -352,49 +398,6 @@ __global__ void __launch_bounds__(NTHREADS) gemm_kernel(GemmArgs g) {
   // a time (row stride WN + 4 floats keeps the 16 B writes conflict-free), and reads it back so
   // that WN/4 lanes cover one row: every global access of the epilogue (C, residual,
   // pre-activation, second output) is a 16 B or 8 B vector in fully used lines.
-  const bf16* bias = static_cast<const bf16*>(g.bias);
-  const bf16* resid = static_cast<const bf16*>(g.resid);
-  const bf16* zin = static_cast<const bf16*>(g.z);
-  bf16* aux = static_cast<bf16*>(g.aux);
-  constexpr int EPAD = WN + 4;
-  constexpr int LPR = WN / 4;                          // lanes per row when reading back
-  constexpr int RPI = 64 / LPR;                        // rows per read instruction
-  float* stage = reinterpret_cast<float*>(smem + wave * (32 * EPAD * 4));
-  const int ecol = n0 + wn * WN + 4 * (lane % LPR);
-  float bv[4] = {0.f, 0.f, 0.f, 0.f};
-  if ((EPI == EPI_BIAS || EPI == EPI_RESID || EPI == EPI_GELU) && bias && ecol < g.N) {
-    const bf16x4 b4 = *reinterpret_cast<const bf16x4*>(bias + ecol);
-#pragma unroll
-    for (int e = 0; e < 4; e++) bv[e] = (float)b4[e];
-  }
-  // EPI_DGELU may also leave partial column sums of what it stores (stage 1 of the bias gradient of
-  // the product that made z): a wavefront's rows split into blocks of 64 (two 32-row passes), each
-  // lane adds its rows of a block, lanes that share columns combine by shuffles, and the block's
-  // sums go to colpart[(m0 + wave row) / 64 + block][column].  Every (block, column) has exactly
-  // one writer.
-  static_assert(WM % 64 == 0, "column-sum blocks of 64 rows");
-  float cs[4] = {0.f, 0.f, 0.f, 0.f};
-  // What an epilogue reads besides the accumulators (the residual, gelu'(z), the weight gradient
-  // being added to) is fetched one 32-row block ahead, all of a block's loads together.  Written
-  // as load - use - store per row, every load sits behind the previous row's store (the compiler
-  // cannot know that the two tensors do not overlap) and the epilogue pays a memory latency per
-  // row: 52 k cycles instead of 11 k for the residual form.
-  constexpr bool SIDE16 = (EPI == EPI_RESID || EPI == EPI_DGELU), SIDE32 = (EPI == EPI_F32_ACC);
-  constexpr int NJ = 32 / RPI;
-  const bf16* side16 = (EPI == EPI_RESID) ? resid : zin;
-  bf16x4 s16[2][SIDE16 ? NJ : 1];
-  f32x4 s32[2][SIDE32 ? NJ : 1];
-  auto fetch = [&](int mi, int buf) {
-#pragma unroll
-    for (int j = 0; j < NJ; j++) {
-      const int row = m0 + wm * WM + mi * 32 + RPI * j + lane / LPR;
-      if (row >= g.M || ecol >= g.N) continue;
-      const size_t idx = (size_t)row * g.ldc + ecol;
-      if (SIDE16) s16[buf][j] = *reinterpret_cast<const bf16x4*>(side16 + idx);
-      if (SIDE32) s32[buf][j] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(g.C) + idx);
-    }
-  };
-  if (SIDE16 || SIDE32) fetch(0, 0);
 #pragma unroll
   for (int mi = 0; mi < TM; mi++) {
     if ((SIDE16 || SIDE32) && mi + 1 < TM) fetch(mi + 1, (mi + 1) & 1);
