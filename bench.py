@@ -45,7 +45,7 @@ MEASURED_TRAFFIC = {
     # FETCH_SIZE x 1.9997 (copy calibration) + WRITE_SIZE x 1.0, averaged over the class's 4 launches per step:
     # dW2, dW1, dWqkv (256x256 tiles) 257.4 MB per launch on average, dWo (128x128 tiles) 117.5 MB
     ("C3", "gemm_tn_f32"): {"bytes_per_launch": 222.4e6, "algorithmic_bytes_per_launch": 109.1e6,
-                            "source_sha256": "afbf0e0bf4eb11ee1f30dd98ba1318dccf0514b0b1eca73b86d1bac3fa86c9d9"},
+                            "source_sha256": "5ae1b3f5cd749b6cd072dc470d5479fc283f66a8369dd5040c428d379c02bfb6"},
 }
 
 
