@@ -483,12 +483,12 @@ gx_status run_bwd(const gx_layer_cfg& c, const gx_params& p, const void* x, cons
   // The weight-gradient products only consume finished tensors, so they are handed to the side
   // stream, beside the dependent chain on the caller's stream.  When they are handed over matters
   // little (the large products simply share the chip with whatever runs beside them) but measurably:
-  // FC2's after the FC1 input gradient, FC1's and the output projection's after LayerNorm 2, QKV's
-  // after the attention kernels measured best at the benchmark's shard shape (about 1 % over
-  // handing each over as soon as its operands exist), and needs three fork points instead of four.
+  // FC2's, FC1's and the output projection's after LayerNorm 2, QKV's after the attention kernels
+  // measured best at the benchmark's shard shape (about 1 % over handing each over as soon as its
+  // operands exist, 1 - 3 % over handing them over later), and needs two fork points instead of four.
   // Points: 0 start, 1 after dz, 2 after dy2, 3 after LayerNorm 2, 4 after dctx, 5 after attention,
   // 6 after dy1; one character per product (dW2, dW1, dWo, dWqkv).
-  const char sched[5] = "2335";
+  const char sched[5] = "3335";
   const bool ln2_sums_biases = attn && mlp && !dr.hidden;
   const int lnb = ln_bwd_blocks(d.bf, (int)d.T, (int)d.H);
   const void* dp_mlp = dy;
