@@ -125,6 +125,18 @@ def test_bf16_degenerate_sizes():
         compare(gpu, ref, TOL["bf16"])
 
 
+@pytest.mark.parametrize("hidden,heads", [(256, 2), (256, 4)])
+def test_bf16_sequence_lengths_around_tile_edges(hidden, heads):
+    # head dim 128 and 64; lengths on either side of the attention kernels' 32-row blocks, 64-key
+    # steps and 128-key tiles: every count of steps from 1 to 5, odd and even numbers of query
+    # blocks (the launch order pairs long and short blocks), ragged last tiles
+    for seq in (31, 32, 33, 63, 64, 65, 96, 127, 128, 129, 191, 193, 257, 320):
+        shape = I.LayerShape(hidden, heads, 256, 1, 1, 0, seq, 2, "bf16")
+        params, x, dy = _case(shape, 300 + seq)
+        gpu, ref, _ = run_both(shape, params, x, dy, "attn", want_partials=False)
+        compare(gpu, ref, TOL["bf16"], "attn")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_recompute_and_accumulate_flags(dtype):
     hidden, heads = (256, 2) if dtype == "bf16" else (128, 2)
