@@ -361,6 +361,32 @@ typedef struct {
 } gx_strategy_costs;
 gx_status gx_strategy_cost(const gx_strategy_query* query, gx_strategy_costs* costs);
 
+/* ---- Pipeline regrouping (host only) ------------------------------------------------------------
+ * Paper section 4 "Handling Transitions": a pipeline-parallel transition changes how layers are
+ * grouped; the groups are formed anew and every process is told which layers to hold.  The paper
+ * gives no rule for the grouping.  This library's reading: a stage holds consecutive layers, every
+ * stage at least one, and the grouping makes the slowest stage (the pipeline's bottleneck) as fast
+ * as possible given a time per layer, e.g. a column of the cost table.  Among the groupings that
+ * reach the smallest bottleneck the one returned has every stage, from the first on, as short as it
+ * can be.  Exact search (dynamic program over (stage, first layer)); host memory only.
+ *
+ * gx_stage_partition
+ *   layers, stages : 1 <= stages <= layers <= 65536, stages <= 4096
+ *   layer_ms       : host, `layers` positive finite times, or NULL for equal times
+ *   first          : host, out, stages + 1 entries; stage s holds layers first[s] .. first[s+1]-1,
+ *                    first[0] = 0, first[stages] = layers
+ *   bottleneck_ms  : host, out, the largest stage time (sum of its layers' times); may be NULL
+ * gx_stage_moves: what a change of grouping moves.
+ *   old_first, new_first : host, groupings of the same `layers` layers in the format above
+ *   new_stage_of         : host, out, `layers` entries: the stage that holds each layer afterwards
+ *   moved                : host, out, number of layers whose stage index changes
+ * Errors: GX_ERR_NULL, GX_ERR_SHAPE (sizes out of range, a non-positive or non-finite time, a
+ * grouping that is not increasing from 0 to layers). */
+gx_status gx_stage_partition(int32_t layers, int32_t stages, const double* layer_ms, int32_t* first,
+                             double* bottleneck_ms);
+gx_status gx_stage_moves(int32_t layers, int32_t old_stages, const int32_t* old_first, int32_t new_stages,
+                         const int32_t* new_first, int32_t* new_stage_of, int32_t* moved);
+
 /* Static strings; never NULL. */
 const char* gx_status_str(gx_status s);
 const char* gx_version(void);

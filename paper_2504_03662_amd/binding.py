@@ -22,7 +22,8 @@ PARAM_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
 EXPORTS = ("gx_layer_validate", "gx_layer_saved_bytes", "gx_layer_workspace_bytes", "gx_layer_fwd",
            "gx_layer_bwd", "gx_status_str", "gx_version", "gx_prof_enable", "gx_prof_collect", "gx_set_overlap",
-           "gx_adamw_step", "gx_params_slice", "gx_params_merge", "gx_plan_search", "gx_strategy_cost", "gx_layer_bwd_static", "gx_peak_mfma", "gx_peak_copy")
+           "gx_adamw_step", "gx_params_slice", "gx_params_merge", "gx_plan_search", "gx_strategy_cost", "gx_layer_bwd_static", "gx_peak_mfma", "gx_peak_copy",
+           "gx_stage_partition", "gx_stage_moves")
 GX_KC_LN_FWD, GX_KC_LN_BWD, GX_KC_ATTN_FWD, GX_KC_ATTN_BWD, GX_KC_COLSUM, GX_KC_GEMM = 1, 2, 3, 4, 5, 100
 
 
@@ -287,6 +288,30 @@ def strategy_cost(hidden, heads, ffn, seq, dtype, gpus, global_batch, tp_attn, t
     if check and st != GX_OK:
         raise GxError(st, "gx_strategy_cost")
     return int(st), out
+
+
+def stage_partition(layers, stages, layer_ms=None, check=True):
+    """Returns (status, first list of stages + 1 entries, bottleneck_ms)."""
+    ms = (ctypes.c_double * layers)(*[float(t) for t in layer_ms]) if layer_ms is not None else None
+    first = (ctypes.c_int32 * (max(stages, 0) + 1))()
+    bott = ctypes.c_double()
+    st = lib().gx_stage_partition(ctypes.c_int32(layers), ctypes.c_int32(stages), ms, first, ctypes.byref(bott))
+    if check and st != GX_OK:
+        raise GxError(st, "gx_stage_partition")
+    return int(st), list(first), bott.value
+
+
+def stage_moves(layers, old_first, new_first, check=True):
+    """Returns (status, new stage of every layer, number of layers whose stage changes)."""
+    of = (ctypes.c_int32 * len(old_first))(*old_first)
+    nf = (ctypes.c_int32 * len(new_first))(*new_first)
+    out = (ctypes.c_int32 * max(layers, 1))()
+    moved = ctypes.c_int32()
+    st = lib().gx_stage_moves(ctypes.c_int32(layers), ctypes.c_int32(len(old_first) - 1), of,
+                              ctypes.c_int32(len(new_first) - 1), nf, out, ctypes.byref(moved))
+    if check and st != GX_OK:
+        raise GxError(st, "gx_stage_moves")
+    return int(st), list(out)[:layers], moved.value
 
 
 def peak_mfma(scratch, launches=20, stream=0):

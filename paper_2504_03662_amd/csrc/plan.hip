@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <cmath>
 #include <new>
+#include <limits>
 #include <vector>
 
 namespace {
@@ -210,3 +211,74 @@ extern "C" gx_status gx_strategy_cost(const gx_strategy_query* q, gx_strategy_co
   return GX_OK;
 }
 
+// Pipeline regrouping (host code): which consecutive layers each stage holds, chosen so that the
+// slowest stage is as fast as possible, and what a change from one grouping to another moves.
+namespace {
+gx_status partition(int32_t L, int32_t P, const double* ms, int32_t* first, double* bottleneck) {
+  // prefix[i] = time of layers 0 .. i-1; every group time below is a difference of two entries,
+  // so the same group always gets the same floating-point value
+  std::vector<double> prefix((size_t)L + 1, 0.0);
+  for (int32_t i = 0; i < L; i++) {
+    const double t = ms ? ms[i] : 1.0;
+    if (!(t > 0.0) || !std::isfinite(t)) return GX_ERR_SHAPE;
+    prefix[i + 1] = prefix[i] + t;
+  }
+  auto span = [&](int32_t a, int32_t b) { return prefix[b] - prefix[a]; };
+  // best[s][i]: smallest bottleneck of layers i .. L-1 in s stages (s <= L - i)
+  const double INF = std::numeric_limits<double>::infinity();
+  std::vector<std::vector<double>> best((size_t)P + 1, std::vector<double>((size_t)L + 1, INF));
+  for (int32_t i = 0; i < L; i++) best[1][i] = span(i, L);
+  for (int32_t s = 2; s <= P; s++)
+    for (int32_t i = 0; i + s <= L; i++) {
+      double b = INF;
+      for (int32_t e = i + 1; e + (s - 1) <= L; e++) b = std::min(b, std::max(span(i, e), best[s - 1][e]));
+      best[s][i] = b;
+    }
+  const double opt = best[P][0];
+  // among the groupings that reach it: every stage, from the first, as short as it can be
+  first[0] = 0;
+  for (int32_t s = 0; s + 1 < P; s++) {
+    const int32_t i = first[s], rest = P - s - 1;
+    int32_t e = i + 1;
+    while (!(span(i, e) <= opt && best[rest][e] <= opt)) e++;      // ends: the optimum exists
+    first[s + 1] = e;
+  }
+  first[P] = L;
+  if (bottleneck) *bottleneck = opt;
+  return GX_OK;
+}
+}  // namespace
+
+extern "C" gx_status gx_stage_partition(int32_t layers, int32_t stages, const double* layer_ms, int32_t* first,
+                                        double* bottleneck_ms) {
+  if (!first) return GX_ERR_NULL;
+  if (layers <= 0 || stages <= 0 || stages > layers || layers > 65536 || stages > 4096) return GX_ERR_SHAPE;
+  try {
+    return partition(layers, stages, layer_ms, first, bottleneck_ms);
+  } catch (...) {
+    return GX_ERR_SHAPE;
+  }
+}
+
+extern "C" gx_status gx_stage_moves(int32_t layers, int32_t old_stages, const int32_t* old_first, int32_t new_stages,
+                                    const int32_t* new_first, int32_t* new_stage_of, int32_t* moved) {
+  if (!old_first || !new_first || !new_stage_of || !moved) return GX_ERR_NULL;
+  if (layers <= 0 || old_stages <= 0 || new_stages <= 0 || old_stages > layers || new_stages > layers)
+    return GX_ERR_SHAPE;
+  auto valid = [&](const int32_t* f, int32_t n) {
+    if (f[0] != 0 || f[n] != layers) return false;
+    for (int32_t s = 0; s < n; s++)
+      if (f[s + 1] <= f[s]) return false;
+    return true;
+  };
+  if (!valid(old_first, old_stages) || !valid(new_first, new_stages)) return GX_ERR_SHAPE;
+  int32_t so = 0, sn = 0, count = 0;
+  for (int32_t l = 0; l < layers; l++) {
+    while (l >= old_first[so + 1]) so++;
+    while (l >= new_first[sn + 1]) sn++;
+    new_stage_of[l] = sn;
+    if (so != sn) count++;
+  }
+  *moved = count;
+  return GX_OK;
+}

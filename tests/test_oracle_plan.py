@@ -66,3 +66,44 @@ def test_round_up_rule_on_exact_multiples_and_their_one_ulp_neighbours():
     # the decimal 0.3 lies below the double product 3 * 0.1 = 0.30000000000000004, which lies below 4 * 0.1
     assert P.round_up(0.3, 0.1) == 3 * 0.1 and P.round_up(3 * 0.1, 0.1) == 3 * 0.1
     assert P.round_up(np.nextafter(3 * 0.1, 1.0), 0.1) == 4 * 0.1
+
+
+# pipeline regrouping (oracle/regroup.py) ---------------------------------------------------------
+
+def test_regroup_closed_forms():
+    from oracle import regroup as R
+    ms = [3.0, 1.0, 4.0, 1.0, 5.0, 9.0, 2.0, 6.0]
+    assert R.best_bottleneck(ms, 1)[0] == sum(ms)
+    assert R.best_bottleneck(ms, len(ms))[0] == max(ms)
+    for L in range(1, 9):
+        for P in range(1, L + 1):
+            assert R.best_bottleneck([2.5] * L, P)[0] == 2.5 * -(-L // P)
+
+
+def test_regroup_bounds_and_monotonicity():
+    import random
+    from oracle import regroup as R
+    rng = random.Random(7)
+    for _ in range(40):
+        L = rng.randint(1, 9)
+        ms = [rng.choice([0.5, 1.0, 1.5, 2.0, 7.0]) for _ in range(L)]
+        prev = None
+        for P in range(1, L + 1):
+            b, first = R.best_bottleneck(ms, P)
+            assert R.is_grouping(first, L, P) and R.bottleneck(ms, first) == b
+            lower = max(max(ms), sum(ms) / P)
+            assert lower <= b <= lower + max(ms)
+            assert prev is None or b <= prev
+            prev = b
+
+
+def test_regroup_hand_worked():
+    from oracle import regroup as R
+    # 1 2 3 4 5 in two stages: {1 2 3 | 4 5} gives max(6, 9) = 9, {1 2 3 4 | 5} gives 10, {1 2 | 3 4 5} 12
+    assert R.best_bottleneck([1.0, 2.0, 3.0, 4.0, 5.0], 2) == (9.0, (0, 3, 5))
+    # in three: {1 2 3 | 4 | 5} -> 6
+    assert R.best_bottleneck([1.0, 2.0, 3.0, 4.0, 5.0], 3) == (6.0, (0, 3, 4, 5))
+    # six layers from stages {0 1 | 2 3 | 4 5} to {0 1 2 | 3 4 5}: layer 2 goes from stage 1 to 0,
+    # layers 4 and 5 from stage 2 to 1; layer 3 stays in stage 1, layers 0 and 1 in stage 0
+    assert R.moves(6, (0, 2, 4, 6), (0, 3, 6)) == ([0, 0, 0, 1, 1, 1], 3)
+    assert R.moves(4, (0, 4), (0, 1, 2, 3, 4)) == ([0, 1, 2, 3], 3)
